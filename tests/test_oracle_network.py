@@ -1,0 +1,167 @@
+"""Pins for the float64 oracle of the network step and of parameter averaging."""
+import math
+
+import numpy as np
+import pytest
+
+import workloads
+from oracle.averaging import average_parameters
+from oracle.network import (PNORM, TANH, NGSGDNetwork, log_softmax, pnorm_backward,
+                            pnorm_forward)
+
+
+def tiny_net(rng, nonlin, ng=True, rank_in=2, rank_out=3, zero_softmax=False):
+    group = 3
+    dims = [5, 12, 9, 7]
+    in_dims = [5, 12 // group if nonlin[0] == PNORM else 12, 9 // group if nonlin[1] == PNORM else 9]
+    weights = [rng.standard_normal((dims[l + 1], in_dims[l] + 1)) / math.sqrt(in_dims[l]) for l in range(3)]
+    if zero_softmax:
+        weights[-1][:] = 0.0
+    return NGSGDNetwork(dims, nonlin, weights, pnorm_group=group, rank_in=rank_in, rank_out=rank_out,
+                        num_samples_history=40.0, update_period=1, natural_gradient=ng)
+
+
+@pytest.mark.parametrize("nonlin", [[TANH, TANH], [PNORM, PNORM], [PNORM, TANH]])
+def test_gradients_match_central_differences(nonlin):
+    """P11: backward pass against finite differences of sum_i log p(y_i | x_i)."""
+    rng = np.random.default_rng(21)
+    net = tiny_net(rng, nonlin)
+    x = rng.standard_normal((6, 5))
+    y = rng.integers(0, 7, 6)
+    grads = net.gradients(x, y)
+    h = 1e-6
+    for l in range(net.n_layers):
+        num = np.zeros_like(net.W[l])
+        for idx in np.ndindex(*net.W[l].shape):
+            old = net.W[l][idx]
+            net.W[l][idx] = old + h
+            fp = net.objective(x, y)
+            net.W[l][idx] = old - h
+            fm = net.objective(x, y)
+            net.W[l][idx] = old
+            num[idx] = (fp - fm) / (2 * h)
+        np.testing.assert_allclose(grads[l], num, atol=2e-7 * max(1.0, np.abs(num).max()))
+
+
+def test_softmax_and_derivative_properties():
+    rng = np.random.default_rng(22)
+    A = 30.0 * rng.standard_normal((9, 11))
+    lp = log_softmax(A)
+    np.testing.assert_allclose(np.exp(lp).sum(axis=1), 1.0, rtol=1e-13)
+    net = tiny_net(rng, [TANH, TANH])
+    x = rng.standard_normal((8, 5))
+    y = rng.integers(0, 7, 8)
+    Xin, Aff, logp = net.forward(x)
+    O = net.backward(Xin, Aff, logp, y)
+    np.testing.assert_allclose(O[-1].sum(axis=1), 0.0, atol=1e-14)   # onehot - softmax
+    assert all(np.all(X[:, -1] == 1.0) for X in Xin)                 # appended ones column
+    # zero softmax weights: every class has probability 1 / #classes (App. C.7 initialisation)
+    net0 = tiny_net(rng, [PNORM, PNORM], zero_softmax=True)
+    assert net0.objective(x, y) == pytest.approx(-8 * math.log(7), rel=1e-14)
+
+
+def test_pnorm_definition_and_zero_group():
+    A = np.array([[3.0, 4.0, 0.0, 0.0, 0.0, 0.0, 1.0, 2.0, 2.0]])
+    Y = pnorm_forward(A, 3)
+    np.testing.assert_allclose(Y, [[5.0, 0.0, 3.0]])
+    dA = pnorm_backward(np.array([[1.0, 7.0, -2.0]]), A, Y, 3)
+    np.testing.assert_allclose(dA, [[0.6, 0.8, 0.0, 0.0, 0.0, 0.0, -2 / 3, -4 / 3, -4 / 3]])
+
+
+def test_rank_zero_step_is_plain_sgd():
+    """P4 at network level: with R = 0 on both sides NG-SGD equals SGD with summed gradients."""
+    rng = np.random.default_rng(23)
+    a = tiny_net(np.random.default_rng(5), [TANH, PNORM], ng=True, rank_in=0, rank_out=0)
+    b = tiny_net(np.random.default_rng(5), [TANH, PNORM], ng=False)
+    for _ in range(3):
+        x = rng.standard_normal((10, 5))
+        y = rng.integers(0, 7, 10)
+        g = b.gradients(x, y)
+        Wb = [w.copy() for w in b.W]
+        oa = a.step(x, y, 0.01)
+        ob = b.step(x, y, 0.01)
+        assert oa == pytest.approx(ob, rel=1e-14)
+        for l in range(3):
+            np.testing.assert_allclose(b.W[l], Wb[l] + 0.01 * g[l], atol=1e-14)   # summed, not averaged
+            np.testing.assert_allclose(a.W[l], b.W[l], atol=1e-13)
+
+
+def test_step_update_is_product_of_preconditioned_factors():
+    """W += lr Obar^T Xbar with each factor rescaled to the norm of its input (Sec. 4.6, 4.7)."""
+    rng = np.random.default_rng(24)
+    net = tiny_net(rng, [PNORM, TANH])
+    from oracle.online_ng import OnlineNaturalGradient
+    kw = dict(num_samples_history=40.0, update_period=1)
+    shadow_in = [OnlineNaturalGradient(net.in_dims[l] + 1, 2, **kw) for l in range(3)]
+    shadow_out = [OnlineNaturalGradient(net.dims[l + 1], 3, **kw) for l in range(3)]
+    for _ in range(4):
+        x = rng.standard_normal((12, 5))
+        y = rng.integers(0, 7, 12)
+        W0 = [w.copy() for w in net.W]
+        obj_before = net.objective(x, y)
+        obj = net.step(x, y, 0.02)
+        assert obj == pytest.approx(obj_before, rel=1e-14)              # objective is taken before the update
+        for l in range(3):
+            Ob = shadow_out[l].precondition(net.last["O"][l])[0]      # each matrix has its own instance
+            Xb = shadow_in[l].precondition(net.last["Xin"][l])[0]
+            np.testing.assert_allclose(net.W[l], W0[l] + 0.02 * Ob.T @ Xb, atol=1e-14)
+            assert np.linalg.norm(Ob) == pytest.approx(np.linalg.norm(net.last["O"][l]), rel=1e-12)
+            assert np.linalg.norm(Xb) == pytest.approx(np.linalg.norm(net.last["Xin"][l]), rel=1e-12)
+    assert all(p.t == 4 for p in net.precond_in + net.precond_out)
+
+
+def test_small_learning_rate_step_increases_objective():
+    rng = np.random.default_rng(25)
+    net = tiny_net(rng, [TANH, TANH])
+    x = rng.standard_normal((16, 5))
+    y = rng.integers(0, 7, 16)
+    before = net.objective(x, y)
+    net.step(x, y, 1e-3)
+    assert net.objective(x, y) > before
+
+
+def test_parameter_averaging():
+    """P12: mean of identical replicas is the replica; the mean is linear; state is rebuilt afterwards."""
+    rng = np.random.default_rng(26)
+    nets = [tiny_net(np.random.default_rng(9), [TANH, TANH]) for _ in range(3)]
+    ref = [w.copy() for w in nets[0].W]
+    average_parameters(nets)
+    for net in nets:
+        for l in range(3):
+            np.testing.assert_allclose(net.W[l], ref[l], rtol=0, atol=4e-16)   # (3w)/3 rounds once
+    for k, net in enumerate(nets):
+        for l in range(3):
+            net.W[l] = ref[l] + (k + 1.0)
+        net.step(rng.standard_normal((8, 5)), rng.integers(0, 7, 8), 0.0)
+        assert net.precond_in[0].t == 1
+    snapshot = [[w.copy() for w in net.W] for net in nets]
+    average_parameters(nets)
+    for net in nets:
+        for l in range(3):
+            np.testing.assert_allclose(net.W[l], sum(s[l] for s in snapshot) / 3.0, atol=1e-15)
+            np.testing.assert_allclose(net.W[l], ref[l] + 2.0, atol=1e-13)
+        assert all(p.t == 0 and p.R is None for p in net.precond_in + net.precond_out)
+
+
+def test_workload_generators_are_seeded_and_shaped():
+    spec = workloads.c1_pnorm()
+    assert spec.in_dims == [360, 300, 300, 300, 300] and spec.n_params() == 5_297_000
+    assert workloads.c3_wide_tanh().n_params() == 38_276_928
+    spec0 = workloads.c0_tiny()
+    x1, y1 = workloads.minibatch(spec0, 3)
+    x2, y2 = workloads.minibatch(spec0, 3)
+    np.testing.assert_array_equal(x1, x2)
+    np.testing.assert_array_equal(y1, y2)
+    assert x1.shape == (64, 40) and x1.dtype == np.float32 and y1.dtype == np.int32 and y1.max() < 50
+    w = workloads.initial_weights(spec)
+    assert [a.shape for a in w] == [(3000, 361), (3000, 301), (3000, 301), (3000, 301), (5000, 301)]
+    assert not w[-1].any() and np.all(w[0][:, -1] == 0)
+    assert np.std(w[1][:, :-1]) == pytest.approx(1 / math.sqrt(300), rel=0.02)
+    ps = workloads.c2_input_side()
+    m = workloads.spectrum_matrix(ps, 0, rows=64)
+    assert m.shape == (64, 3001) and np.all(m[:, -1] == 1.0)
+    po = workloads.c2_output_side()
+    m = workloads.spectrum_matrix(po, 1, rows=2048).astype(np.float64)
+    sv = np.linalg.svd(m, compute_uv=False)
+    # singular values follow ~ 1/k: the leading ratio s1/s8 is near 8
+    assert 5.0 < sv[0] / sv[7] < 12.0
