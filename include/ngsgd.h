@@ -1,0 +1,170 @@
+/*
+ * ngsgd.h - C ABI of the MI355X NG-SGD minibatch-step library (libngsgd.so).
+ *
+ * One worker's natural-gradient SGD step from "Parallel training of DNNs with
+ * Natural Gradient and Parameter Averaging" (Povey, Zhang, Khudanpur):
+ * forward, objective, backward, online natural-gradient preconditioning of
+ * both matrices that enter each layer's update, the rank-N update itself, and
+ * on-device parameter averaging across replicas held on the same GPU.
+ *
+ * General conventions
+ *   - All `dev_*` pointers are DEVICE pointers (HIP global memory on the
+ *     current device).  Everything else is host memory.
+ *   - Matrices are row-major fp32.  A leading dimension `ld` counts floats
+ *     between consecutive rows; it must be a multiple of 4 and the base
+ *     pointer 16-byte aligned.
+ *   - The library allocates no device memory.  Every handle lives in a device
+ *     workspace the caller allocates (size from the *_workspace_bytes call,
+ *     256-byte aligned) and keeps alive until *_destroy.  Inputs and outputs
+ *     stay caller-owned.
+ *   - All work is enqueued on the HIP stream passed as `hip_stream` (a
+ *     hipStream_t cast to void*; NULL is the default stream) and the calls
+ *     return without waiting for it.  Scalars results are written to device
+ *     memory.  Calls on the same handle must be issued in order on one stream.
+ *     Handles are not thread-safe.
+ *   - Every function returns NGSGD_OK (0) or a negative NGSGD_E* code.  After
+ *     an error the handle's state is unchanged when the error is an argument
+ *     error, and unspecified for NGSGD_EHIP.
+ */
+#ifndef NGSGD_H_
+#define NGSGD_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define NGSGD_OK 0
+#define NGSGD_EINVAL (-1)    /* bad argument: NULL, size, alignment, rank >= dim, N > max_batch ... */
+#define NGSGD_ENOMEM (-2)    /* workspace too small */
+#define NGSGD_EHIP (-3)      /* a HIP runtime call failed; see ngsgd_last_hip_error() */
+#define NGSGD_EUNSUPPORTED (-4)
+
+#define NGSGD_TANH 0
+#define NGSGD_PNORM 1
+
+#define NGSGD_MAX_LAYERS 16
+#define NGSGD_MAX_RANK 96    /* the R x R update runs in one workgroup's LDS */
+
+#define NGSGD_SIDE_INPUT 0   /* preconditioner of the layer-input matrix [X_l, 1]   */
+#define NGSGD_SIDE_OUTPUT 1  /* preconditioner of the output-derivative matrix O_l  */
+
+typedef struct ngsgd_net ngsgd_net;          /* one replica: weights + 2I preconditioners */
+typedef struct ngsgd_precond ngsgd_precond;  /* one instance of the online method         */
+
+/* Network description (host memory, copied by ngsgd_create).
+ * dims[0] is the input dimension, dims[1..n_layers] the output dimension of each affine layer;
+ * nonlin[l] (l < n_layers-1) follows affine layer l, the last affine layer feeds a log-softmax.
+ * A p-norm layer (p = 2) maps groups of `pnorm_group` adjacent outputs to their 2-norm, so the
+ * next layer's input dimension is dims[l+1] / pnorm_group (must divide).  Each affine layer keeps
+ * its bias as the last column of its weight matrix: W_l is dims[l+1] x (in_dim_l + 1)
+ * (Sec. 4.4 of the paper).  Defaults of App. B.4/B.5: rank_in 20, rank_out 80, alpha 4,
+ * num_samples_history 2000, epsilon 1e-10, update_period 4, always_update_first 10. */
+typedef struct {
+  int32_t n_layers;
+  const int32_t* dims;
+  const int32_t* nonlin;
+  int32_t pnorm_group;
+  int32_t max_batch;              /* largest minibatch a step will be given            */
+  int32_t rank_in, rank_out;      /* 0 disables preconditioning on that side           */
+  float alpha;                    /* identity smoothing, Sec. 4.8                      */
+  float num_samples_history;      /* S in eta = 1 - exp(-N/S), App. B.4                */
+  float epsilon;                  /* floor on rho and D, App. B.2-B.3                  */
+  int32_t update_period;          /* J: factors updated when t < always_update_first   */
+  int32_t always_update_first;    /*    or J divides t, App. B.4                       */
+  int32_t renorm;                 /* 1: rows leave each p-norm layer with unit rms     */
+  float max_change_per_sample;    /* App. C.3; 0 disables the limit (paper: 0.075)     */
+} ngsgd_config;
+
+/* ---- one preconditioner instance (App. B) ------------------------------------------------- */
+
+/* Device workspace needed by one instance for matrices of up to max_batch rows. */
+int ngsgd_precond_workspace_bytes(int32_t dim, int32_t rank, int32_t max_batch, size_t* out_bytes);
+
+/* Creates an instance in `dev_workspace`.  Requires 0 <= rank <= NGSGD_MAX_RANK, rank < dim.
+ * The state (W_t = E_t^{1/2} R_t, D_t, rho_t) is built from the first matrix it is given
+ * (App. B.3.2), which therefore needs more than `rank` rows. */
+int ngsgd_precond_create(int32_t dim, int32_t rank, int32_t max_batch, float alpha,
+                         float num_samples_history, float epsilon, int32_t update_period,
+                         int32_t always_update_first, void* dev_workspace, size_t workspace_bytes,
+                         ngsgd_precond** out);
+int ngsgd_precond_destroy(ngsgd_precond* p);
+
+/* Forgets the state: the next call re-initialises from its input, as a new process does. */
+int ngsgd_precond_reset(ngsgd_precond* p);
+
+/* The online natural-gradient call of Sec. 4.6 / App. B.5: overwrites the N x dim matrix dev_M
+ * (leading dimension ld) with gamma_t * M * G_t^{-1}, which has the Frobenius norm of M, using
+ * the factor estimated from the previous calls; then, when t < always_update_first or
+ * update_period divides t, updates the factor with M.  t counts calls since creation / reset.
+ *   dev_gamma     (optional, 1 float)  receives gamma_t (eq. gammat)
+ *   dev_rownorm2  (optional, N floats) receives the squared 2-norm of each output row
+ * Requires N <= max_batch; on the first call after creation/reset also N > rank. */
+int ngsgd_precondition(ngsgd_precond* p, float* dev_M, int32_t N, int32_t ld, float* dev_gamma,
+                       float* dev_rownorm2, void* hip_stream);
+
+/* Copies the state out: dev_W (rank x dim floats, dense), dev_d (rank doubles, diag D_t),
+ * dev_rho (1 double); *t_host receives the call counter.  Any pointer may be NULL. */
+int ngsgd_precond_get_state(const ngsgd_precond* p, float* dev_W, double* dev_d, double* dev_rho,
+                            int64_t* t_host, void* hip_stream);
+
+/* Installs a state given in the definitional form of App. B.1: dev_R (rank x dim doubles, dense,
+ * orthonormal rows), dev_d (rank doubles > 0), rho > 0, and the call counter t >= 1.
+ * W_t = E_t^{1/2} R_t is formed on the device (eq. beta2, etii, wt:def). */
+int ngsgd_precond_set_state(ngsgd_precond* p, const double* dev_R, const double* dev_d, double rho,
+                            int64_t t, void* hip_stream);
+
+/* ---- one replica of the network -------------------------------------------------------------- */
+
+int ngsgd_workspace_bytes(const ngsgd_config* cfg, size_t* out_bytes);
+
+/* Creates a replica in `dev_workspace`; all weights start at zero (set them with
+ * ngsgd_set_params; App. C.7 describes the initialisation the paper uses).  Synchronises the
+ * device once. */
+int ngsgd_create(const ngsgd_config* cfg, void* dev_workspace, size_t workspace_bytes,
+                 ngsgd_net** out);
+int ngsgd_destroy(ngsgd_net* net);
+
+/* One NG-SGD minibatch step (Sec. 2, 4.5-4.7): maximises sum_i log p(y_i | x_i) by
+ * W_l += lr * a_l * Obar_l^T Xbar_l for every layer, gradients summed over the minibatch.
+ *   dev_x       N x dims[0] features, dense (ld = dims[0], which must be a multiple of 4)
+ *   dev_labels  N class indices in [0, dims[n_layers])
+ *   dev_logprob_sum (optional, 1 double) receives sum_i log p(y_i | x_i) evaluated before the update */
+int ngsgd_step(ngsgd_net* net, const float* dev_x, const int32_t* dev_labels, int32_t N, float lr,
+               double* dev_logprob_sum, void* hip_stream);
+
+/* Parameter averaging of Sec. 3.1: every replica's weights are replaced by the arithmetic mean over
+ * the n replicas (same configuration, same device).  With reset_preconditioners != 0 all their
+ * preconditioners are reset, as the paper's re-spawned processes do (App. B.3.2). */
+int ngsgd_average(ngsgd_net* const* nets, int32_t n, int32_t reset_preconditioners, void* hip_stream);
+
+/* Weights of one layer as a dense dims[layer+1] x (in_dim+1) row-major matrix, bias last. */
+int ngsgd_get_params(const ngsgd_net* net, int32_t layer, float* dev_out, void* hip_stream);
+int ngsgd_set_params(ngsgd_net* net, int32_t layer, const float* dev_in, void* hip_stream);
+
+/* Borrowed handle of a layer's preconditioner (side = NGSGD_SIDE_INPUT / NGSGD_SIDE_OUTPUT);
+ * owned by the net, valid until ngsgd_destroy.  NULL result when that side's rank is 0. */
+int ngsgd_net_precond(ngsgd_net* net, int32_t layer, int32_t side, ngsgd_precond** out);
+
+/* Inspection of the latest step, for parity checks.  All outputs are dense row-major copies.
+ *   ngsgd_last_preconditioned: the N x dim matrix Obar_l or Xbar_l (already rescaled by gamma)
+ *   ngsgd_last_gradient:       a_l * Obar_l^T Xbar_l, dims[layer+1] x (in_dim+1), without lr
+ *   ngsgd_last_max_change_scale: a_l of App. C.3 as one double (1 when the limit is disabled) */
+int ngsgd_last_preconditioned(ngsgd_net* net, int32_t layer, int32_t side, float* dev_out,
+                              void* hip_stream);
+int ngsgd_last_gradient(ngsgd_net* net, int32_t layer, float* dev_out, void* hip_stream);
+int ngsgd_last_max_change_scale(ngsgd_net* net, int32_t layer, double* dev_out, void* hip_stream);
+
+/* ---- diagnostics -------------------------------------------------------------------------- */
+const char* ngsgd_strerror(int code);
+/* hipError_t value of the most recent failed HIP call on this thread (0 if none). */
+int ngsgd_last_hip_error(void);
+/* Library version: major * 10000 + minor * 100 + patch. */
+int ngsgd_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NGSGD_H_ */

@@ -19,6 +19,15 @@ the two matrices that enter the update (App. C.3, last paragraph).
 Nonlinearities: tanh, or p-norm with p = 2 over groups of `pnorm_group`
 adjacent outputs, y_j = sqrt(sum_k a_k^2) (the paper cites the p-norm paper for
 the definition; derivative a_k / y_j, taken as 0 where y_j = 0).
+
+Two stabilisers of the paper's recipe are optional here:
+  * `renorm`: the renormalisation layer the paper's p-norm nets carry after
+    each p-norm (App. C.8, footnote).  The paper does not define it; the
+    reading used is: each row y is divided by max(rms(y), RENORM_FLOOR), with
+    rms(y) = sqrt(mean_j y_j^2), so that rows leave with unit rms.
+  * `max_change_per_sample` (App. C.3): the update of each layer is scaled by
+        a_t = min(1, N * max_change_per_sample / (lr * sum_i ||obar_i|| ||xbar_i||))
+    using the rows of the preconditioned matrices (a_t = 1 if the sum is 0).
 """
 from __future__ import annotations
 
@@ -28,6 +37,7 @@ from .online_ng import OnlineNaturalGradient
 
 TANH = 0
 PNORM = 1
+RENORM_FLOOR = 1.0e-20
 
 
 def append_ones(A: np.ndarray) -> np.ndarray:
@@ -46,6 +56,23 @@ def pnorm_backward(dY: np.ndarray, A: np.ndarray, Y: np.ndarray, group: int) -> 
     return (A.reshape(N, D // group, group) * scale[:, :, None]).reshape(N, D)
 
 
+def renorm_forward(Y: np.ndarray):
+    """Rows scaled to unit rms; returns (Y / sigma, sigma) with sigma = max(rms, floor)."""
+    sigma = np.maximum(np.sqrt(np.mean(Y * Y, axis=1)), RENORM_FLOOR)
+    return Y / sigma[:, None], sigma
+
+
+def renorm_backward(dYn: np.ndarray, Yn: np.ndarray, sigma: np.ndarray) -> np.ndarray:
+    """Derivative through y -> y / rms(y): (dYn - Yn * mean_j(dYn_j Yn_j)) / sigma.
+
+    Rows whose rms sat on the floor were scaled by a constant, so only 1/sigma applies there.
+    """
+    K = Yn.shape[1]
+    proj = np.sum(dYn * Yn, axis=1) / K
+    proj = np.where(sigma > RENORM_FLOOR, proj, 0.0)
+    return (dYn - Yn * proj[:, None]) / sigma[:, None]
+
+
 def log_softmax(A: np.ndarray) -> np.ndarray:
     m = np.max(A, axis=1, keepdims=True)
     return A - m - np.log(np.sum(np.exp(A - m), axis=1, keepdims=True))
@@ -61,13 +88,16 @@ class NGSGDNetwork:
 
     def __init__(self, dims, nonlin, weights, pnorm_group: int = 10, rank_in: int = 20,
                  rank_out: int = 80, alpha: float = 4.0, num_samples_history: float = 2000.0,
-                 epsilon: float = 1.0e-10, update_period: int = 4, natural_gradient: bool = True):
+                 epsilon: float = 1.0e-10, update_period: int = 4, natural_gradient: bool = True,
+                 renorm: bool = False, max_change_per_sample: float = 0.0):
         self.dims = list(dims)
         self.n_layers = len(dims) - 1
         self.nonlin = list(nonlin)
         assert len(self.nonlin) == self.n_layers - 1
         self.pnorm_group = pnorm_group
         self.natural_gradient = natural_gradient
+        self.renorm = renorm
+        self.max_change_per_sample = float(max_change_per_sample)
         self.in_dims = []
         d_in = dims[0]
         for l in range(self.n_layers):
@@ -89,6 +119,7 @@ class NGSGDNetwork:
     def forward(self, x: np.ndarray):
         """Returns (layer inputs with ones column, affine outputs, log-probabilities)."""
         Xin, A = [], []
+        self._sigma = [None] * self.n_layers
         cur = np.asarray(x, dtype=np.float64)
         for l in range(self.n_layers):
             Xl = append_ones(cur)
@@ -96,7 +127,12 @@ class NGSGDNetwork:
             Xin.append(Xl)
             A.append(Al)
             if l < self.n_layers - 1:
-                cur = np.tanh(Al) if self.nonlin[l] == TANH else pnorm_forward(Al, self.pnorm_group)
+                if self.nonlin[l] == TANH:
+                    cur = np.tanh(Al)
+                else:
+                    cur = pnorm_forward(Al, self.pnorm_group)
+                    if self.renorm:
+                        cur, self._sigma[l] = renorm_forward(cur)
         return Xin, A, log_softmax(A[-1])
 
     def objective(self, x: np.ndarray, labels: np.ndarray) -> float:
@@ -117,6 +153,10 @@ class NGSGDNetwork:
             if self.nonlin[l - 1] == TANH:
                 O[l - 1] = dX * (1.0 - Yprev * Yprev)
             else:
+                if self.renorm:
+                    sigma = self._sigma[l - 1]
+                    dX = renorm_backward(dX, Yprev, sigma)
+                    Yprev = Yprev * sigma[:, None]             # the p-norm output before renormalisation
                 O[l - 1] = pnorm_backward(dX, Aprev, Yprev, self.pnorm_group)
         return O
 
@@ -133,20 +173,28 @@ class NGSGDNetwork:
         Xin, A, logp = self.forward(x)
         obj = float(np.sum(logp[np.arange(len(labels)), labels]))
         O = self.backward(Xin, A, logp, labels)
-        deltas, Obar_all, Xbar_all = [], [], []
+        deltas, Obar_all, Xbar_all, scales = [], [], [], []
         for l in range(self.n_layers):
             if self.natural_gradient:
-                Obar, _, _ = self.precond_out[l].precondition(O[l])
-                Xbar, _, _ = self.precond_in[l].precondition(Xin[l])
+                Obar, _, rn_o = self.precond_out[l].precondition(O[l])
+                Xbar, _, rn_x = self.precond_in[l].precondition(Xin[l])
             else:
                 Obar, Xbar = O[l], Xin[l]
-            delta = Obar.T @ Xbar
+                rn_o, rn_x = np.sum(Obar * Obar, axis=1), np.sum(Xbar * Xbar, axis=1)
+            a_t = 1.0
+            if self.max_change_per_sample > 0.0:
+                bound = lr * float(np.sum(np.sqrt(rn_o * rn_x)))          # App. C.3, eq. delta_t_approx
+                if bound > 0.0:
+                    a_t = min(1.0, len(labels) * self.max_change_per_sample / bound)
+            scales.append(a_t)
+            delta = a_t * (Obar.T @ Xbar)
             deltas.append(delta)
             Obar_all.append(Obar)
             Xbar_all.append(Xbar)
         for l in range(self.n_layers):
             self.W[l] = self.W[l] + lr * deltas[l]
-        self.last = dict(O=O, Xin=Xin, Obar=Obar_all, Xbar=Xbar_all, delta=deltas, logp=logp)
+        self.last = dict(O=O, Xin=Xin, Obar=Obar_all, Xbar=Xbar_all, delta=deltas, logp=logp,
+                         max_change_scale=scales)
         return obj
 
     def reset_preconditioners(self) -> None:

@@ -35,6 +35,7 @@ class OnlineNaturalGradientEfficient:
         self.trace_identity = bool(trace_identity)   # use eq. trxxt instead of the direct sum
         self.t = 0
         self.W = self.d = self.rho = None
+        self.last = {}
 
     def fisher(self) -> np.ndarray:
         """Dense F_t recovered from W_t = E_t^{1/2} R_t."""
@@ -98,6 +99,7 @@ class OnlineNaturalGradientEfficient:
             A = (eta / N) * (np.sqrt(e_new) / sqrt_c)[:, None] * U.T * inv_sqrt_e[None, :]
             B = J + (N * (1.0 - eta) / eta) * (dr[:, None] * W)
             W_new = A @ B                                      # eq. wt1
+            reorth = False
             if floored or c[0] > ORTHO_COND_LIMIT * c[-1]:
                 s = 1.0 / np.sqrt(e_new)
                 O = s[:, None] * (W_new @ W_new.T) * s[None, :]
@@ -105,6 +107,8 @@ class OnlineNaturalGradientEfficient:
                     Lc = np.linalg.cholesky(O)
                     Mfix = np.sqrt(e_new)[:, None] * np.linalg.inv(Lc) * s[None, :]
                     W_new = Mfix @ W_new
+                    reorth = True
             self.W, self.d, self.rho = W_new, d_new, rho_new
+            self.last = dict(floored=floored, reorthogonalised=reorth)
         self.t += 1
         return Mbar, gamma, rownorm2

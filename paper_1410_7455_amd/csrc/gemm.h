@@ -1,0 +1,421 @@
+// Grouped fp32 MFMA GEMM for gfx950 (CDNA4).
+//
+// One launch runs a list of independent problems C = alpha * op(A) * op(B) [+ beta * C]; every
+// workgroup owns one (problem, split, tile_m, tile_n) unit.  All matrix products of the NG-SGD step
+// go through this kernel: the layer GEMMs (forward A B^T, backward A B, update A^T B) and the
+// skinny products of the online preconditioner (H = X W^T, J = H^T X, Xhat = X - H W, K = J J^T,
+// L = H^T H, W_{t+1} = A_t B_t; App. B.3 of the paper).
+//
+// Tiling: 64-lane wavefronts, v_mfma_f32_16x16x4_f32.  A workgroup of WGM x WGN waves computes a
+// BM x BN tile; a wave owns (BM/WGM) x (BN/WGN) as TM x TN MFMA tiles.  Operand tiles are staged
+// through double-buffered LDS.  An operand whose K index is contiguous in memory is kept as
+// [row][BK+4] and feeds four consecutive MFMAs from one ds_read_b128 (lane group g supplies
+// k = 4g..4g+3, for A and B alike, so the assignment of k to lanes is consistent); an operand
+// whose row index is contiguous is kept as [k][rows+4].
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+namespace ngsgd {
+
+constexpr int kMaxGroup = 16;
+
+enum Epilogue : int {
+  EPI_STORE = 0,        // C = alpha*acc + beta*C
+  EPI_ATOMIC_F32 = 1,   // C += alpha*acc            (split-K, float atomics)
+  EPI_ATOMIC_F64 = 2,   // (double)C += alpha*acc    (split-K, double atomics)
+  EPI_SUB_ROWNORM = 3,  // C = C - acc; aux[tile_n][row] = sum over the tile's columns of C^2
+};
+
+struct GemmProblem {
+  const float* A;
+  const float* B;
+  void* C;
+  int M, N, K;
+  int lda, ldb, ldc;
+  float alpha, beta;
+  const double* alpha_dev[3];  // optional device scalars multiplied into alpha
+  int tiles_m, tiles_n, splits, k_per_split;
+  int tile_begin;              // first workgroup index of this problem
+  float* aux;                  // EPI_SUB_ROWNORM: [tiles_n][M] row-norm partials
+  double* sumsq;               // SUMSQ_A: [splits*tiles_m] partial sums of squares of A
+};
+
+struct GemmGroup {
+  int count;
+  int total_tiles;
+  GemmProblem p[kMaxGroup];
+};
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+// ---- global -> register -> LDS staging ---------------------------------------------------------
+// K-contiguous operand: element (row, k) at base[row*ld + k]; LDS layout [ROWS][BK+4].
+template <int ROWS, int BK, int NT>
+struct StageKC {
+  static constexpr int F4_PER_ROW = BK / 4;
+  static constexpr int TOTAL = ROWS * F4_PER_ROW;
+  static constexpr int ITER = (TOTAL + NT - 1) / NT;
+  static constexpr int LDS_FLOATS = ROWS * (BK + 4);
+  float4 reg[ITER];
+
+  __device__ __forceinline__ void load(const float* __restrict__ base, int ld, int row0, int rows_total,
+                                       int k0, int k_end, int tid) {
+#pragma unroll
+    for (int i = 0; i < ITER; ++i) {
+      const int f = tid + i * NT;
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (TOTAL % NT == 0 || f < TOTAL) {
+        const int r = f / F4_PER_ROW;
+        const int gk = k0 + (f % F4_PER_ROW) * 4;
+        const int gr = row0 + r;
+        if (gr < rows_total && gk < k_end) {
+          const float* p = base + (size_t)gr * ld + gk;
+          if (gk + 3 < k_end) {
+            v = *reinterpret_cast<const float4*>(p);
+          } else {
+            v.x = p[0];
+            if (gk + 1 < k_end) v.y = p[1];
+            if (gk + 2 < k_end) v.z = p[2];
+          }
+        }
+      }
+      reg[i] = v;
+    }
+  }
+  __device__ __forceinline__ void store(float* lds, int tid) const {
+#pragma unroll
+    for (int i = 0; i < ITER; ++i) {
+      const int f = tid + i * NT;
+      if (TOTAL % NT == 0 || f < TOTAL) {
+        const int r = f / F4_PER_ROW;
+        const int kq = (f % F4_PER_ROW) * 4;
+        *reinterpret_cast<float4*>(&lds[r * (BK + 4) + kq]) = reg[i];
+      }
+    }
+  }
+  __device__ __forceinline__ float sumsq() const {
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < ITER; ++i)
+      s += reg[i].x * reg[i].x + reg[i].y * reg[i].y + reg[i].z * reg[i].z + reg[i].w * reg[i].w;
+    return s;
+  }
+  // fragment for MFMA tile at tile row offset `row` and k-group kk (16 k values each)
+  __device__ __forceinline__ static float4 frag(const float* lds, int row, int kk, int g) {
+    return *reinterpret_cast<const float4*>(&lds[row * (BK + 4) + kk * 16 + 4 * g]);
+  }
+};
+
+// Row-contiguous operand: element (row, k) at base[k*ld + row]; LDS layout [BK][ROWS+4].
+template <int ROWS, int BK, int NT>
+struct StageRC {
+  static constexpr int F4_PER_K = ROWS / 4;
+  static constexpr int TOTAL = BK * F4_PER_K;
+  static constexpr int ITER = (TOTAL + NT - 1) / NT;
+  static constexpr int LDS_FLOATS = BK * (ROWS + 4);
+  float4 reg[ITER];
+
+  __device__ __forceinline__ void load(const float* __restrict__ base, int ld, int row0, int rows_total,
+                                       int k0, int k_end, int tid) {
+#pragma unroll
+    for (int i = 0; i < ITER; ++i) {
+      const int f = tid + i * NT;
+      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (TOTAL % NT == 0 || f < TOTAL) {
+        const int k = f / F4_PER_K;
+        const int gr = row0 + (f % F4_PER_K) * 4;
+        const int gk = k0 + k;
+        if (gk < k_end && gr < rows_total) {
+          const float* p = base + (size_t)gk * ld + gr;
+          if (gr + 3 < rows_total) {
+            v = *reinterpret_cast<const float4*>(p);
+          } else {
+            v.x = p[0];
+            if (gr + 1 < rows_total) v.y = p[1];
+            if (gr + 2 < rows_total) v.z = p[2];
+          }
+        }
+      }
+      reg[i] = v;
+    }
+  }
+  __device__ __forceinline__ void store(float* lds, int tid) const {
+#pragma unroll
+    for (int i = 0; i < ITER; ++i) {
+      const int f = tid + i * NT;
+      if (TOTAL % NT == 0 || f < TOTAL) {
+        const int k = f / F4_PER_K;
+        const int r4 = (f % F4_PER_K) * 4;
+        *reinterpret_cast<float4*>(&lds[k * (ROWS + 4) + r4]) = reg[i];
+      }
+    }
+  }
+  __device__ __forceinline__ float sumsq() const {
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < ITER; ++i)
+      s += reg[i].x * reg[i].x + reg[i].y * reg[i].y + reg[i].z * reg[i].z + reg[i].w * reg[i].w;
+    return s;
+  }
+  __device__ __forceinline__ static float4 frag(const float* lds, int row, int kk, int g) {
+    const float* p = &lds[(kk * 16 + 4 * g) * (ROWS + 4) + row];
+    return make_float4(p[0], p[ROWS + 4], p[2 * (ROWS + 4)], p[3 * (ROWS + 4)]);
+  }
+};
+
+template <bool KC, int ROWS, int BK, int NT>
+struct StageSelect {
+  using type = StageKC<ROWS, BK, NT>;
+};
+template <int ROWS, int BK, int NT>
+struct StageSelect<false, ROWS, BK, NT> {
+  using type = StageRC<ROWS, BK, NT>;
+};
+
+__device__ __forceinline__ float group16_sum(float v) {
+  v += __shfl_xor(v, 1);
+  v += __shfl_xor(v, 2);
+  v += __shfl_xor(v, 4);
+  v += __shfl_xor(v, 8);
+  return v;
+}
+
+// A_KC: A is M x K with K contiguous (else stored K x M).  B_KC: B is N x K with K contiguous
+// (else stored K x N).  The product is always sum_k A(m,k) B(n,k).
+template <int BM, int BN, int BK, int WGM, int WGN, bool A_KC, bool B_KC, int EPI, bool SUMSQ_A>
+__global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmGroup g) {
+  constexpr int NT = WGM * WGN * 64;
+  constexpr int WM = BM / WGM, WN = BN / WGN;
+  constexpr int TM = WM / 16, TN = WN / 16;
+  static_assert(WM % 16 == 0 && WN % 16 == 0, "wave tile must be a multiple of 16x16");
+  static_assert(BK % 16 == 0, "BK must be a multiple of 16");
+  using StageA = typename StageSelect<A_KC, BM, BK, NT>::type;
+  using StageB = typename StageSelect<B_KC, BN, BK, NT>::type;
+  constexpr int EPI_LDS = (EPI == EPI_SUB_ROWNORM) ? WGN * BM : 0;
+  constexpr int LDS_TOTAL = 2 * (StageA::LDS_FLOATS + StageB::LDS_FLOATS);
+  __shared__ __attribute__((aligned(16))) float lds[(LDS_TOTAL > EPI_LDS ? LDS_TOTAL : EPI_LDS)];
+  __shared__ double red[NT / 64];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int wm = wave / WGN, wn = wave % WGN;
+  const int r16 = lane & 15, g4 = lane >> 4;
+
+  int pi = 0;
+  for (int i = 1; i < g.count; ++i)
+    if ((int)blockIdx.x >= g.p[i].tile_begin) pi = i;
+  const GemmProblem& P = g.p[pi];
+  int local = blockIdx.x - P.tile_begin;
+  const int tn = local % P.tiles_n;
+  local /= P.tiles_n;
+  const int tm = local % P.tiles_m;
+  const int split = local / P.tiles_m;
+  const int m0 = tm * BM, n0 = tn * BN;
+  const int k_begin = split * P.k_per_split;
+  const int k_end = min(P.K, k_begin + P.k_per_split);
+  const int M = P.M, N = P.N;
+
+  float* const As = lds;                             // two buffers of StageA::LDS_FLOATS
+  float* const Bs = lds + 2 * StageA::LDS_FLOATS;    // two buffers of StageB::LDS_FLOATS
+
+  floatx4 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  StageA sa;
+  StageB sb;
+  float ssq = 0.f;
+  const int nk = (k_end - k_begin + BK - 1) / BK;
+  if (nk > 0) {
+    sa.load(P.A, P.lda, m0, M, k_begin, k_end, tid);
+    sb.load(P.B, P.ldb, n0, N, k_begin, k_end, tid);
+    if (SUMSQ_A) ssq += sa.sumsq();
+    sa.store(As, tid);
+    sb.store(Bs, tid);
+  }
+  __syncthreads();
+  for (int it = 0; it < nk; ++it) {
+    const int cur = it & 1;
+    const bool more = it + 1 < nk;
+    if (more) {
+      const int k0 = k_begin + (it + 1) * BK;
+      sa.load(P.A, P.lda, m0, M, k0, k_end, tid);
+      sb.load(P.B, P.ldb, n0, N, k0, k_end, tid);
+      if (SUMSQ_A) ssq += sa.sumsq();
+    }
+    const float* a_lds = As + cur * StageA::LDS_FLOATS;
+    const float* b_lds = Bs + cur * StageB::LDS_FLOATS;
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      float4 af[TM], bf[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) af[i] = StageA::frag(a_lds, wm * WM + i * 16 + r16, kk, g4);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) bf[j] = StageB::frag(b_lds, wn * WN + j * 16 + r16, kk, g4);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(af[i].x, bf[j].x, acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(af[i].y, bf[j].y, acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(af[i].z, bf[j].z, acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(af[i].w, bf[j].w, acc[i][j], 0, 0, 0);
+        }
+    }
+    if (more) {
+      sa.store(As + (cur ^ 1) * StageA::LDS_FLOATS, tid);
+      sb.store(Bs + (cur ^ 1) * StageB::LDS_FLOATS, tid);
+    }
+    __syncthreads();
+  }
+
+  if (SUMSQ_A) {
+    // every element of A's row block is staged exactly once by the tile_n == 0 workgroups
+    double s = (double)ssq;
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
+    if (lane == 0) red[wave] = s;
+    __syncthreads();
+    if (tid == 0 && tn == 0 && P.sumsq != nullptr) {
+      double t = 0.0;
+      for (int w = 0; w < NT / 64; ++w) t += red[w];
+      P.sumsq[split * P.tiles_m + tm] = t;
+    }
+  }
+
+  float alpha = P.alpha;
+#pragma unroll
+  for (int i = 0; i < 3; ++i)
+    if (P.alpha_dev[i] != nullptr) alpha *= (float)(*P.alpha_dev[i]);
+
+  // accumulator layout of v_mfma_f32_16x16x4_f32: register i of lane l holds (row 4*(l/16)+i, col l%16)
+  if (EPI == EPI_SUB_ROWNORM) {
+    float* C = static_cast<float*>(P.C);
+    float* rowsum = lds;  // [WGN][BM], operand tiles are no longer needed
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int lrow = wm * WM + i * 16 + 4 * g4 + r;
+        const int row = m0 + lrow;
+        float sq = 0.f;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          const int col = n0 + wn * WN + j * 16 + r16;
+          if (row < M && col < N) {
+            float* c = C + (size_t)row * P.ldc + col;
+            const float v = *c - acc[i][j][r];
+            *c = v;
+            sq += v * v;
+          }
+        }
+        sq = group16_sum(sq);
+        if (r16 == 0) rowsum[wn * BM + lrow] = sq;
+      }
+    }
+    __syncthreads();
+    for (int lrow = tid; lrow < BM; lrow += NT) {
+      const int row = m0 + lrow;
+      if (row < M) {
+        float s = 0.f;
+#pragma unroll
+        for (int w = 0; w < WGN; ++w) s += rowsum[w * BM + lrow];
+        P.aux[(size_t)tn * M + row] = s;
+      }
+    }
+    return;
+  }
+
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int col = n0 + wn * WN + j * 16 + r16;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int row = m0 + wm * WM + i * 16 + 4 * g4 + r;
+        if (row < M && col < N) {
+          const float v = alpha * acc[i][j][r];
+          if (EPI == EPI_STORE) {
+            float* c = static_cast<float*>(P.C) + (size_t)row * P.ldc + col;
+            *c = (P.beta != 0.f) ? v + P.beta * (*c) : v;
+          } else if (EPI == EPI_ATOMIC_F32) {
+            unsafeAtomicAdd(static_cast<float*>(P.C) + (size_t)row * P.ldc + col, v);
+          } else if (EPI == EPI_ATOMIC_F64) {
+            unsafeAtomicAdd(static_cast<double*>(P.C) + (size_t)row * P.ldc + col, (double)v);
+          }
+        }
+      }
+    }
+  }
+}
+
+// ---- host side -------------------------------------------------------------------------------
+struct GemmDesc {  // what a caller states; tiling is filled in by the launcher
+  const float* A = nullptr;
+  const float* B = nullptr;
+  void* C = nullptr;
+  int M = 0, N = 0, K = 0;
+  int lda = 0, ldb = 0, ldc = 0;
+  float alpha = 1.f, beta = 0.f;
+  const double* alpha_dev[3] = {nullptr, nullptr, nullptr};
+  float* aux = nullptr;
+  double* sumsq = nullptr;
+  int splits = 1;  // requested split-K factor (atomic epilogues only)
+};
+
+template <int BM, int BN, int BK>
+inline void plan_tiles(const GemmDesc& d, GemmProblem& p) {
+  p.A = d.A; p.B = d.B; p.C = d.C;
+  p.M = d.M; p.N = d.N; p.K = d.K;
+  p.lda = d.lda; p.ldb = d.ldb; p.ldc = d.ldc;
+  p.alpha = d.alpha; p.beta = d.beta;
+  for (int i = 0; i < 3; ++i) p.alpha_dev[i] = d.alpha_dev[i];
+  p.aux = d.aux; p.sumsq = d.sumsq;
+  p.tiles_m = (d.M + BM - 1) / BM;
+  p.tiles_n = (d.N + BN - 1) / BN;
+  const int ksteps = (d.K + BK - 1) / BK;
+  int splits = d.splits < 1 ? 1 : d.splits;
+  if (splits > ksteps) splits = ksteps > 0 ? ksteps : 1;
+  const int steps_per = (ksteps + splits - 1) / splits;
+  p.k_per_split = (steps_per > 0 ? steps_per : 1) * BK;
+  p.splits = ksteps > 0 ? (ksteps + steps_per - 1) / steps_per : 1;
+}
+
+template <int BM, int BN, int BK, int WGM, int WGN, bool A_KC, bool B_KC, int EPI, bool SUMSQ_A>
+inline hipError_t launch_gemm_group(const GemmDesc* descs, int count, hipStream_t stream) {
+  int done = 0;
+  while (done < count) {
+    GemmGroup grp;
+    const int n = (count - done) < kMaxGroup ? (count - done) : kMaxGroup;
+    grp.count = n;
+    int total = 0;
+    for (int i = 0; i < n; ++i) {
+      plan_tiles<BM, BN, BK>(descs[done + i], grp.p[i]);
+      grp.p[i].tile_begin = total;
+      total += grp.p[i].tiles_m * grp.p[i].tiles_n * grp.p[i].splits;
+    }
+    grp.total_tiles = total;
+    if (total > 0) {
+      hipLaunchKernelGGL((gemm_kernel<BM, BN, BK, WGM, WGN, A_KC, B_KC, EPI, SUMSQ_A>), dim3(total),
+                         dim3(WGM * WGN * 64), 0, stream, grp);
+      hipError_t e = hipGetLastError();
+      if (e != hipSuccess) return e;
+    }
+    done += n;
+  }
+  return hipSuccess;
+}
+
+// number of sumsq partials the SUMSQ_A variant writes for a problem planned with these tiles
+template <int BM, int BN, int BK>
+inline int planned_sumsq_partials(const GemmDesc& d) {
+  GemmProblem p;
+  plan_tiles<BM, BN, BK>(d, p);
+  return p.splits * p.tiles_m;
+}
+
+}  // namespace ngsgd

@@ -1,0 +1,980 @@
+// C ABI of the NG-SGD minibatch-step library: host-side orchestration of the HIP kernels.
+// Declarations and argument contracts are in include/ngsgd.h.
+#include "ngsgd.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "gemm.h"
+#include "init.h"
+#include "kernels.h"
+#include "small_update.h"
+#include "state.h"
+
+using namespace ngsgd;
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+#define HIP_TRY(expr)                         \
+  do {                                        \
+    hipError_t e__ = (expr);                  \
+    if (e__ != hipSuccess) {                  \
+      g_last_hip_error = (int)e__;            \
+      return NGSGD_EHIP;                      \
+    }                                         \
+  } while (0)
+#define NG_TRY(expr)                \
+  do {                              \
+    int rc__ = (expr);              \
+    if (rc__ != NGSGD_OK) return rc__; \
+  } while (0)
+#define LAUNCH_CHECK() HIP_TRY(hipGetLastError())
+
+inline int pad32(int x) { return (x + 31) / 32 * 32; }
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Carves typed arrays out of a caller-provided device workspace; with base == nullptr it only sizes.
+struct Carver {
+  char* base;
+  size_t off = 0;
+  explicit Carver(void* b) : base(static_cast<char*>(b)) {}
+  template <typename T>
+  T* take(size_t n) {
+    off = align_up(off, 256);
+    T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
+    off += n * sizeof(T);
+    return p;
+  }
+};
+
+constexpr int kSumsqMax = 1024;   // partial sums of squares per preconditioner call
+constexpr int kTargetBlocks = 512;
+
+inline int rank_class(int rank) { return rank <= 32 ? 32 : (rank <= 80 ? 80 : 96); }
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------------------
+struct ngsgd_precond {
+  int dim = 0, rank = 0, max_batch = 0;
+  double alpha = 4.0, num_samples_history = 2000.0, epsilon = 1e-10;
+  int update_period = 4, always_update_first = 10;
+  int64_t t = 0;
+  int ldw = 0;   // leading dimension of W and J
+  int ldh = 0;   // leading dimension of H and A_t (= rank class)
+  PrecondScalars* st = nullptr;
+  float* zero_region = nullptr;   // [H | J | K | L], cleared before each call
+  size_t zero_floats_all = 0;
+  float* H = nullptr;
+  float* J = nullptr;
+  double* K = nullptr;
+  double* L = nullptr;
+  float* W = nullptr;
+  float* At = nullptr;
+  float* rownorm_part = nullptr;
+  int max_col_tiles = 0;
+  double* sumsq_part = nullptr;
+  double* prow = nullptr;
+  // initialisation scratch
+  int n_init_max = 0;
+  double* Ai[2] = {nullptr, nullptr};
+  double* Vi[2] = {nullptr, nullptr};
+  int* idx = nullptr;
+  double* vwork = nullptr;
+  bool owned_by_net = false;
+};
+
+namespace {
+
+void precond_layout(ngsgd_precond& p, Carver& c) {
+  const int R = p.rank, D = p.dim, NB = p.max_batch;
+  p.ldw = pad32(D);
+  p.ldh = R > 0 ? rank_class(R) : 0;
+  p.st = c.take<PrecondScalars>(1);
+  p.prow = c.take<double>(NB);
+  if (R == 0) return;
+  const size_t h_floats = (size_t)NB * p.ldh, j_floats = (size_t)R * p.ldw, kl_floats = (size_t)4 * R * R;
+  p.zero_floats_all = h_floats + j_floats + kl_floats;
+  p.zero_region = c.take<float>(p.zero_floats_all + 8);
+  if (p.zero_region) {
+    p.H = p.zero_region;
+    p.J = p.H + h_floats;
+    float* kl = p.J + j_floats;
+    kl = reinterpret_cast<float*>(align_up(reinterpret_cast<uintptr_t>(kl), 8));
+    p.K = reinterpret_cast<double*>(kl);
+    p.L = p.K + (size_t)R * R;
+  }
+  p.W = c.take<float>((size_t)R * p.ldw);
+  p.At = c.take<float>((size_t)R * p.ldh);
+  p.max_col_tiles = (D + 63) / 64;
+  p.rownorm_part = c.take<float>((size_t)p.max_col_tiles * NB);
+  p.sumsq_part = c.take<double>(kSumsqMax);
+  p.n_init_max = NB < D ? NB : D;
+  const size_t nn = (size_t)p.n_init_max * p.n_init_max;
+  p.Ai[0] = c.take<double>(nn);
+  p.Ai[1] = c.take<double>(nn);
+  p.Vi[0] = c.take<double>(nn);
+  p.Vi[1] = c.take<double>(nn);
+  p.idx = c.take<int>(kMaxRank);
+  p.vwork = c.take<double>((size_t)kMaxRank + D);
+}
+
+int precond_check_config(int dim, int rank, int max_batch, float alpha, float S, float eps, int period, int first) {
+  if (dim < 1 || rank < 0 || rank > NGSGD_MAX_RANK || rank >= dim || max_batch < 1) return NGSGD_EINVAL;
+  if (!(alpha >= 0.f) || !(S > 0.f) || !(eps > 0.f) || period < 1 || first < 0) return NGSGD_EINVAL;
+  return NGSGD_OK;
+}
+
+void precond_configure(ngsgd_precond& p, int dim, int rank, int max_batch, float alpha, float S, float eps,
+                       int period, int first) {
+  p.dim = dim;
+  p.rank = rank;
+  p.max_batch = max_batch;
+  p.alpha = alpha;
+  p.num_samples_history = S;
+  p.epsilon = eps;
+  p.update_period = period;
+  p.always_update_first = first;
+  p.t = 0;
+}
+
+bool g_attr_done = false;
+int ensure_kernel_attributes() {
+  if (g_attr_done) return NGSGD_OK;
+  const int max_dyn = 2 * kMaxRank * (kMaxRank | 1) * (int)sizeof(double);
+  HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(small_update_kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, max_dyn));
+  HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(orth_fix_kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, max_dyn));
+  g_attr_done = true;
+  return NGSGD_OK;
+}
+
+int fill_zero(void* p, size_t n_u32, hipStream_t s) {
+  if (n_u32 == 0) return NGSGD_OK;
+  size_t blocks = (n_u32 + 256 * 8 - 1) / (256 * 8);
+  if (blocks > 2048) blocks = 2048;
+  hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)blocks), dim3(256), 0, s, static_cast<uint32_t*>(p), n_u32, 0u);
+  LAUNCH_CHECK();
+  return NGSGD_OK;
+}
+
+inline int choose_splits(int tiles, int ksteps) {
+  int s = kTargetBlocks / (tiles > 0 ? tiles : 1);
+  if (s < 1) s = 1;
+  if (s > ksteps) s = ksteps;
+  return s < 1 ? 1 : s;
+}
+
+// ---- GEMM dispatch ---------------------------------------------------------------------------------
+constexpr int BK = 16;
+
+enum LayerGemm { GEMM_FWD, GEMM_BWD, GEMM_UPD };
+
+// layer GEMMs: 128x128 tiles when they already fill the chip, 64x64 otherwise
+int launch_layer_gemms(LayerGemm kind, const GemmDesc* d, int n, hipStream_t s) {
+  long long big_tiles = 0;
+  for (int i = 0; i < n; ++i) big_tiles += (long long)((d[i].M + 127) / 128) * ((d[i].N + 127) / 128);
+  const bool big = big_tiles >= 400;
+  hipError_t e = hipSuccess;
+  switch (kind) {
+    case GEMM_FWD:
+      e = big ? launch_gemm_group<128, 128, BK, 2, 2, true, true, EPI_STORE, false>(d, n, s)
+              : launch_gemm_group<64, 64, BK, 2, 2, true, true, EPI_STORE, false>(d, n, s);
+      break;
+    case GEMM_BWD:
+      e = big ? launch_gemm_group<128, 128, BK, 2, 2, true, false, EPI_STORE, false>(d, n, s)
+              : launch_gemm_group<64, 64, BK, 2, 2, true, false, EPI_STORE, false>(d, n, s);
+      break;
+    case GEMM_UPD:
+      e = big ? launch_gemm_group<128, 128, BK, 2, 2, false, false, EPI_STORE, false>(d, n, s)
+              : launch_gemm_group<64, 64, BK, 2, 2, false, false, EPI_STORE, false>(d, n, s);
+      break;
+  }
+  HIP_TRY(e);
+  return NGSGD_OK;
+}
+
+// H = X W^T (split over D, float atomics) with the sum of squares of X as a by-product
+template <int RC>
+hipError_t launch_h(const GemmDesc* d, int n, hipStream_t s) {
+  return launch_gemm_group<64, RC, BK, 4, 1, true, true, EPI_ATOMIC_F32, true>(d, n, s);
+}
+// J = H^T X (split over the rows, float atomics)
+template <int RC>
+hipError_t launch_j(const GemmDesc* d, int n, hipStream_t s) {
+  return launch_gemm_group<RC, 128, BK, 1, 4, false, false, EPI_ATOMIC_F32, false>(d, n, s);
+}
+// W_{t+1} = A_t B_t
+template <int RC>
+hipError_t launch_wnew(const GemmDesc* d, int n, hipStream_t s) {
+  return launch_gemm_group<RC, 128, BK, 1, 4, true, false, EPI_STORE, false>(d, n, s);
+}
+
+template <typename F32, typename F80, typename F96>
+hipError_t by_rank_class(int rc, F32 f32, F80 f80, F96 f96) {
+  return rc == 32 ? f32() : (rc == 80 ? f80() : f96());
+}
+
+struct PrecondCall {
+  ngsgd_precond* p;
+  float* M;
+  int ld;
+  int N;
+  float* gamma_out;
+  float* rownorm2_out;
+};
+
+int run_init(const std::vector<PrecondCall>& calls, hipStream_t s) {
+  size_t done = 0;
+  while (done < calls.size()) {
+    InitGroup g;
+    const int n = (int)std::min<size_t>(kMaxInstances, calls.size() - done);
+    g.count = n;
+    int n_max = 0, ldw_max = 0, r_max = 0;
+    for (int i = 0; i < n; ++i) {
+      const PrecondCall& c = calls[done + i];
+      ngsgd_precond& p = *c.p;
+      InitArgs& a = g.a[i];
+      a.st = p.st;
+      a.M = c.M;
+      a.ld = c.ld;
+      a.N = c.N;
+      a.D = p.dim;
+      a.R = p.rank;
+      a.use_cov = p.dim <= c.N ? 1 : 0;
+      a.n = a.use_cov ? p.dim : c.N;
+      a.A[0] = p.Ai[0];
+      a.A[1] = p.Ai[1];
+      a.V[0] = p.Vi[0];
+      a.V[1] = p.Vi[1];
+      a.idx = p.idx;
+      a.W = p.W;
+      a.ldw = p.ldw;
+      a.vwork = p.vwork;
+      n_max = std::max(n_max, a.n);
+      ldw_max = std::max(ldw_max, p.ldw);
+      r_max = std::max(r_max, p.rank);
+      g.alpha = p.alpha;       // one configuration per group (instances of one net share it)
+      g.epsilon = p.epsilon;
+    }
+    const int tiles = (n_max + 31) / 32;
+    hipLaunchKernelGGL(init_gram_kernel, dim3(tiles, tiles, n), dim3(256), 0, s, g);
+    LAUNCH_CHECK();
+    const int m_max = (n_max + 1) & ~1;
+    const int rounds = kInitSweeps * (m_max - 1);
+    const long long work = (long long)(m_max / 2) * (m_max / 2) + (long long)n_max * (m_max / 2);
+    int blocks = (int)std::min<long long>((work + 255) / 256, 4096);
+    if (blocks < 1) blocks = 1;
+    int src = 0;
+    for (int r = 0; r < rounds; ++r) {
+      hipLaunchKernelGGL(init_jacobi_round_kernel, dim3(blocks, 1, n), dim3(256), 0, s, g, r, src);
+      src ^= 1;
+    }
+    LAUNCH_CHECK();
+    hipLaunchKernelGGL(init_select_kernel, dim3(n), dim3(1024), 0, s, g, src);
+    LAUNCH_CHECK();
+    hipLaunchKernelGGL(init_rows_kernel, dim3((ldw_max + 63) / 64, r_max, n), dim3(256), 0, s, g, src);
+    LAUNCH_CHECK();
+    hipLaunchKernelGGL(init_complete_kernel, dim3(n), dim3(1024), 0, s, g);
+    LAUNCH_CHECK();
+    done += n;
+  }
+  return NGSGD_OK;
+}
+
+// The online natural-gradient call (App. B.5) for a list of independent instances.  With
+// scale_output the matrices are left as gamma * Xhat; without it they are left as Xhat and gamma
+// stays in the instance's state for the caller to fold into a later product.
+int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStream_t s) {
+  NG_TRY(ensure_kernel_attributes());
+  std::vector<PrecondCall> full, to_init, to_update;
+  for (auto& c : calls) {
+    ngsgd_precond& p = *c.p;
+    if (c.N < 1 || c.N > p.max_batch || c.ld < p.dim || (c.ld & 3) || !aligned16(c.M)) return NGSGD_EINVAL;
+    if (p.rank > 0 && p.t == 0 && c.N <= p.rank) return NGSGD_EINVAL;
+  }
+  for (auto& c : calls) {
+    ngsgd_precond& p = *c.p;
+    if (p.rank == 0) {
+      hipLaunchKernelGGL(rownorm_kernel, dim3((c.N + 3) / 4), dim3(256), 0, s, c.M, c.ld, c.N, p.dim, p.prow,
+                         c.rownorm2_out);
+      LAUNCH_CHECK();
+      if (c.gamma_out != nullptr) {
+        const uint32_t one_bits = 0x3f800000u;
+        hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(c.gamma_out),
+                           (size_t)1, one_bits);
+        LAUNCH_CHECK();
+      }
+      continue;
+    }
+    full.push_back(c);
+    if (p.t == 0) to_init.push_back(c);
+    if (p.t < p.always_update_first || p.t % p.update_period == 0) to_update.push_back(c);
+  }
+  if (!to_init.empty()) NG_TRY(run_init(to_init, s));
+
+  // clear the accumulation buffers
+  for (auto& c : full) {
+    ngsgd_precond& p = *c.p;
+    const bool upd = p.t < p.always_update_first || p.t % p.update_period == 0;
+    NG_TRY(fill_zero(p.zero_region, upd ? p.zero_floats_all + 8 : (size_t)c.N * p.ldh, s));
+  }
+  // H = X W^T   (eq. ht), tr(X X^T) partials
+  for (int rc : {32, 80, 96}) {
+    std::vector<GemmDesc> d;
+    for (auto& c : full) {
+      ngsgd_precond& p = *c.p;
+      if (p.ldh != rc) continue;
+      GemmDesc g;
+      g.A = c.M; g.lda = c.ld;
+      g.B = p.W; g.ldb = p.ldw;
+      g.C = p.H; g.ldc = p.ldh;
+      g.M = c.N; g.N = p.rank; g.K = p.dim;
+      g.sumsq = p.sumsq_part;
+      const int tiles_m = (c.N + 63) / 64, ksteps = (p.dim + BK - 1) / BK;
+      int splits = choose_splits(tiles_m, ksteps);
+      while (splits > 1 && splits * tiles_m > kSumsqMax) --splits;
+      g.splits = splits;
+      d.push_back(g);
+    }
+    if (d.empty()) continue;
+    HIP_TRY(by_rank_class(rc, [&] { return launch_h<32>(d.data(), (int)d.size(), s); },
+                          [&] { return launch_h<80>(d.data(), (int)d.size(), s); },
+                          [&] { return launch_h<96>(d.data(), (int)d.size(), s); }));
+  }
+  // J = H^T X   (must read X before it is overwritten by Xhat)
+  for (int rc : {32, 80, 96}) {
+    std::vector<GemmDesc> d;
+    for (auto& c : to_update) {
+      ngsgd_precond& p = *c.p;
+      if (p.ldh != rc) continue;
+      GemmDesc g;
+      g.A = p.H; g.lda = p.ldh;
+      g.B = c.M; g.ldb = c.ld;
+      g.C = p.J; g.ldc = p.ldw;
+      g.M = p.rank; g.N = p.dim; g.K = c.N;
+      g.splits = choose_splits((p.dim + 127) / 128, (c.N + BK - 1) / BK);
+      d.push_back(g);
+    }
+    if (d.empty()) continue;
+    HIP_TRY(by_rank_class(rc, [&] { return launch_j<32>(d.data(), (int)d.size(), s); },
+                          [&] { return launch_j<80>(d.data(), (int)d.size(), s); },
+                          [&] { return launch_j<96>(d.data(), (int)d.size(), s); }));
+  }
+  // Xhat = X - H W   (eq. hatxt:compute:2), row-norm partials (eq. pi)
+  {
+    std::vector<GemmDesc> d;
+    for (auto& c : full) {
+      ngsgd_precond& p = *c.p;
+      GemmDesc g;
+      g.A = p.H; g.lda = p.ldh;
+      g.B = p.W; g.ldb = p.ldw;
+      g.C = c.M; g.ldc = c.ld;
+      g.M = c.N; g.N = p.dim; g.K = p.rank;
+      g.aux = p.rownorm_part;
+      d.push_back(g);
+    }
+    HIP_TRY((launch_gemm_group<64, 64, BK, 2, 2, true, false, EPI_SUB_ROWNORM, false>(d.data(), (int)d.size(), s)));
+  }
+  // gamma_t, tr(X X^T), tr(Xhat Xhat^T)
+  for (size_t done = 0; done < full.size();) {
+    FinishGroup g;
+    const int n = (int)std::min<size_t>(kMaxInstances, full.size() - done);
+    g.count = n;
+    for (int i = 0; i < n; ++i) {
+      const PrecondCall& c = full[done + i];
+      ngsgd_precond& p = *c.p;
+      FinishArgs& a = g.a[i];
+      a.st = p.st;
+      a.sumsq_part = p.sumsq_part;
+      GemmDesc hd;
+      hd.M = c.N; hd.N = p.rank; hd.K = p.dim;
+      {
+        const int tiles_m = (c.N + 63) / 64, ksteps = (p.dim + BK - 1) / BK;
+        int splits = choose_splits(tiles_m, ksteps);
+        while (splits > 1 && splits * tiles_m > kSumsqMax) --splits;
+        hd.splits = splits;
+      }
+      a.n_sumsq = planned_sumsq_partials<64, 32, BK>(hd);   // independent of the tile width
+      a.rownorm_part = p.rownorm_part;
+      a.n_col_tiles = (p.dim + 63) / 64;
+      a.N = c.N;
+      a.prow = p.prow;
+      a.gamma_out = c.gamma_out;
+      a.rownorm2_out = c.rownorm2_out;
+    }
+    hipLaunchKernelGGL(finish_apply_kernel, dim3(n), dim3(256), 0, s, g);
+    LAUNCH_CHECK();
+    done += n;
+  }
+  if (scale_output) {
+    for (auto& c : full) {
+      ngsgd_precond& p = *c.p;
+      hipLaunchKernelGGL(scale_rows_kernel, dim3((p.dim + 1023) / 1024, c.N), dim3(256), 0, s, c.M, c.ld, c.N, p.dim,
+                         &p.st->gamma);
+      LAUNCH_CHECK();
+    }
+  }
+  if (!to_update.empty()) {
+    // K = J J^T, L = H^T H   (App. B.3), fp64 accumulation across the splits
+    std::vector<GemmDesc> dk, dl;
+    for (auto& c : to_update) {
+      ngsgd_precond& p = *c.p;
+      GemmDesc g;
+      g.A = p.J; g.lda = p.ldw;
+      g.B = p.J; g.ldb = p.ldw;
+      g.C = p.K; g.ldc = p.rank;
+      g.M = p.rank; g.N = p.rank; g.K = p.dim;
+      const int tiles = ((p.rank + 63) / 64) * ((p.rank + 63) / 64);
+      g.splits = choose_splits(tiles * (int)to_update.size(), (p.dim + BK - 1) / BK);
+      dk.push_back(g);
+      GemmDesc h;
+      h.A = p.H; h.lda = p.ldh;
+      h.B = p.H; h.ldb = p.ldh;
+      h.C = p.L; h.ldc = p.rank;
+      h.M = p.rank; h.N = p.rank; h.K = c.N;
+      h.splits = choose_splits(tiles * (int)to_update.size(), (c.N + BK - 1) / BK);
+      dl.push_back(h);
+    }
+    HIP_TRY((launch_gemm_group<64, 64, BK, 2, 2, true, true, EPI_ATOMIC_F64, false>(dk.data(), (int)dk.size(), s)));
+    HIP_TRY((launch_gemm_group<64, 64, BK, 2, 2, false, false, EPI_ATOMIC_F64, false>(dl.data(), (int)dl.size(), s)));
+    // B_t over J (needs D_t, rho_t: before the R x R update)
+    for (auto& c : to_update) {
+      ngsgd_precond& p = *c.p;
+      hipLaunchKernelGGL(make_bt_kernel, dim3((p.dim + 1023) / 1024, p.rank), dim3(256), 0, s, p.J, p.W, p.ldw, p.dim,
+                         p.st, c.N, p.num_samples_history);
+      LAUNCH_CHECK();
+    }
+    // Z_t, eigen-decomposition, rho_{t+1}, D_{t+1}, A_t
+    for (size_t done = 0; done < to_update.size();) {
+      // instances of one launch share alpha / epsilon / S (instances of one net do)
+      SmallGroup g;
+      OrthGroup og;
+      const ngsgd_precond& p0 = *to_update[done].p;
+      g.alpha = p0.alpha;
+      g.epsilon = p0.epsilon;
+      g.num_samples_history = p0.num_samples_history;
+      int n = 0, r_max = 0;
+      while (n < kMaxInstances && done + n < to_update.size()) {
+        const PrecondCall& c = to_update[done + n];
+        const ngsgd_precond& p = *c.p;
+        if (p.alpha != g.alpha || p.epsilon != g.epsilon || p.num_samples_history != g.num_samples_history) break;
+        SmallArgs& a = g.a[n];
+        a.st = p.st; a.K = p.K; a.L = p.L; a.At = p.At; a.ldat = p.ldh;
+        a.R = p.rank; a.D = p.dim; a.N = c.N;
+        OrthArgs& o = og.a[n];
+        o.st = p.st; o.W = p.W; o.ld = p.ldw; o.R = p.rank; o.D = p.dim;
+        r_max = std::max(r_max, p.rank);
+        ++n;
+      }
+      g.count = og.count = n;
+      const size_t dyn = (size_t)2 * r_max * (r_max | 1) * sizeof(double);
+      hipLaunchKernelGGL(small_update_kernel, dim3(n), dim3(kSmallThreads), dyn, s, g);
+      LAUNCH_CHECK();
+      // W_{t+1} = A_t B_t   (eq. wt1)
+      for (int rc : {32, 80, 96}) {
+        std::vector<GemmDesc> d;
+        for (int i = 0; i < n; ++i) {
+          ngsgd_precond& p = *to_update[done + i].p;
+          if (p.ldh != rc) continue;
+          GemmDesc w;
+          w.A = p.At; w.lda = p.ldh;
+          w.B = p.J; w.ldb = p.ldw;
+          w.C = p.W; w.ldc = p.ldw;
+          w.M = p.rank; w.N = p.dim; w.K = p.rank;
+          d.push_back(w);
+        }
+        if (d.empty()) continue;
+        HIP_TRY(by_rank_class(rc, [&] { return launch_wnew<32>(d.data(), (int)d.size(), s); },
+                              [&] { return launch_wnew<80>(d.data(), (int)d.size(), s); },
+                              [&] { return launch_wnew<96>(d.data(), (int)d.size(), s); }));
+      }
+      hipLaunchKernelGGL(orth_fix_kernel, dim3(n), dim3(kSmallThreads), dyn, s, og);
+      LAUNCH_CHECK();
+      done += n;
+    }
+  }
+  for (auto& c : calls) c.p->t += 1;
+  return NGSGD_OK;
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------------------
+// preconditioner C ABI
+extern "C" int ngsgd_precond_workspace_bytes(int32_t dim, int32_t rank, int32_t max_batch, size_t* out_bytes) {
+  if (out_bytes == nullptr) return NGSGD_EINVAL;
+  NG_TRY(precond_check_config(dim, rank, max_batch, 4.f, 2000.f, 1e-10f, 4, 10));
+  ngsgd_precond p;
+  p.dim = dim; p.rank = rank; p.max_batch = max_batch;
+  Carver c(nullptr);
+  precond_layout(p, c);
+  *out_bytes = align_up(c.off, 256);
+  return NGSGD_OK;
+}
+
+extern "C" int ngsgd_precond_create(int32_t dim, int32_t rank, int32_t max_batch, float alpha,
+                                    float num_samples_history, float epsilon, int32_t update_period,
+                                    int32_t always_update_first, void* dev_workspace, size_t workspace_bytes,
+                                    ngsgd_precond** out) {
+  if (out == nullptr || dev_workspace == nullptr) return NGSGD_EINVAL;
+  if (reinterpret_cast<uintptr_t>(dev_workspace) & 255u) return NGSGD_EINVAL;
+  NG_TRY(precond_check_config(dim, rank, max_batch, alpha, num_samples_history, epsilon, update_period,
+                              always_update_first));
+  size_t need = 0;
+  NG_TRY(ngsgd_precond_workspace_bytes(dim, rank, max_batch, &need));
+  if (workspace_bytes < need) return NGSGD_ENOMEM;
+  ngsgd_precond* p = new (std::nothrow) ngsgd_precond();
+  if (p == nullptr) return NGSGD_ENOMEM;
+  precond_configure(*p, dim, rank, max_batch, alpha, num_samples_history, epsilon, update_period,
+                    always_update_first);
+  Carver c(dev_workspace);
+  precond_layout(*p, c);
+  hipError_t e = hipMemset(dev_workspace, 0, need);
+  if (e == hipSuccess) {
+    PrecondScalars init;
+    std::memset(&init, 0, sizeof(init));
+    init.gamma = 1.0;
+    e = hipMemcpy(p->st, &init, sizeof(init), hipMemcpyHostToDevice);
+  }
+  if (e != hipSuccess) {
+    g_last_hip_error = (int)e;
+    delete p;
+    return NGSGD_EHIP;
+  }
+  *out = p;
+  return NGSGD_OK;
+}
+
+extern "C" int ngsgd_precond_destroy(ngsgd_precond* p) {
+  if (p == nullptr || p->owned_by_net) return NGSGD_EINVAL;
+  delete p;
+  return NGSGD_OK;
+}
+
+extern "C" int ngsgd_precond_reset(ngsgd_precond* p) {
+  if (p == nullptr) return NGSGD_EINVAL;
+  p->t = 0;
+  return NGSGD_OK;
+}
+
+extern "C" int ngsgd_precondition(ngsgd_precond* p, float* dev_M, int32_t N, int32_t ld, float* dev_gamma,
+                                  float* dev_rownorm2, void* hip_stream) {
+  if (p == nullptr || dev_M == nullptr) return NGSGD_EINVAL;
+  std::vector<PrecondCall> calls(1);
+  calls[0] = PrecondCall{p, dev_M, ld, N, dev_gamma, dev_rownorm2};
+  return precondition_many(calls, true, static_cast<hipStream_t>(hip_stream));
+}
+
+extern "C" int ngsgd_precond_get_state(const ngsgd_precond* p, float* dev_W, double* dev_d, double* dev_rho,
+                                       int64_t* t_host, void* hip_stream) {
+  if (p == nullptr) return NGSGD_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  if (t_host != nullptr) *t_host = p->t;
+  if (p->rank == 0) {
+    if (dev_rho != nullptr) HIP_TRY(hipMemsetAsync(dev_rho, 0, sizeof(double), s));
+    return NGSGD_OK;
+  }
+  if (dev_W != nullptr)
+    HIP_TRY(hipMemcpy2DAsync(dev_W, (size_t)p->dim * sizeof(float), p->W, (size_t)p->ldw * sizeof(float),
+                             (size_t)p->dim * sizeof(float), p->rank, hipMemcpyDeviceToDevice, s));
+  if (dev_d != nullptr)
+    HIP_TRY(hipMemcpyAsync(dev_d, p->st->d, (size_t)p->rank * sizeof(double), hipMemcpyDeviceToDevice, s));
+  if (dev_rho != nullptr)
+    HIP_TRY(hipMemcpyAsync(dev_rho, &p->st->rho, sizeof(double), hipMemcpyDeviceToDevice, s));
+  return NGSGD_OK;
+}
+
+extern "C" int ngsgd_precond_set_state(ngsgd_precond* p, const double* dev_R, const double* dev_d, double rho,
+                                       int64_t t, void* hip_stream) {
+  if (p == nullptr || t < 1 || !(rho > 0.0)) return NGSGD_EINVAL;
+  if (p->rank == 0) {
+    p->t = t;
+    return NGSGD_OK;
+  }
+  if (dev_R == nullptr || dev_d == nullptr) return NGSGD_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  hipLaunchKernelGGL(set_state_kernel, dim3(p->rank), dim3(256), 0, s, dev_R, dev_d, rho, p->alpha, p->rank, p->dim,
+                     p->W, p->ldw, p->st);
+  LAUNCH_CHECK();
+  p->t = t;
+  return NGSGD_OK;
+}
+
+// ---------------------------------------------------------------------------------------------------
+// network
+struct ngsgd_layer {
+  int din = 0, dout = 0, in1 = 0;   // in1 = din + 1 (bias input)
+  int ldw = 0, ldx = 0, lda = 0;
+  int nonlin = -1;                  // nonlinearity after this layer, -1 for the last
+  int groups = 0;                   // p-norm output dimension
+  float* W = nullptr;               // dout x ldw
+  float* Xin = nullptr;             // max_batch x ldx, [input, 1]
+  float* A = nullptr;               // max_batch x lda, affine output, later O_l
+  float* sigma = nullptr;           // max_batch renorm divisors
+  double* mc_scale = nullptr;       // max-change scale of the latest step
+  ngsgd_precond pin, pout;
+};
+
+struct ngsgd_net {
+  int n_layers = 0;
+  int max_batch = 0;
+  int pnorm_group = 10;
+  int renorm = 0;
+  double max_change_per_sample = 0.0;
+  std::vector<ngsgd_layer> layers;
+  float* params = nullptr;
+  size_t n_params_padded = 0;
+  float* dX = nullptr;
+  int lddx = 0;
+  double* rowobj = nullptr;
+  double* logprob = nullptr;
+  int last_N = 0;
+  float last_lr = 0.f;
+};
+
+namespace {
+
+int net_check_config(const ngsgd_config* cfg) {
+  if (cfg == nullptr || cfg->dims == nullptr || cfg->n_layers < 1 || cfg->n_layers > NGSGD_MAX_LAYERS)
+    return NGSGD_EINVAL;
+  if (cfg->n_layers > 1 && cfg->nonlin == nullptr) return NGSGD_EINVAL;
+  if (cfg->max_batch < 1 || cfg->pnorm_group < 1) return NGSGD_EINVAL;
+  if (cfg->dims[0] < 1 || (cfg->dims[0] & 3)) return NGSGD_EINVAL;
+  if (!(cfg->max_change_per_sample >= 0.f)) return NGSGD_EINVAL;
+  int din = cfg->dims[0];
+  for (int l = 0; l < cfg->n_layers; ++l) {
+    const int dout = cfg->dims[l + 1];
+    if (dout < 1) return NGSGD_EINVAL;
+    NG_TRY(precond_check_config(din + 1, cfg->rank_in, cfg->max_batch, cfg->alpha, cfg->num_samples_history,
+                                cfg->epsilon, cfg->update_period, cfg->always_update_first));
+    NG_TRY(precond_check_config(dout, cfg->rank_out, cfg->max_batch, cfg->alpha, cfg->num_samples_history,
+                                cfg->epsilon, cfg->update_period, cfg->always_update_first));
+    if (l < cfg->n_layers - 1) {
+      if (cfg->nonlin[l] == NGSGD_PNORM) {
+        if (dout % cfg->pnorm_group) return NGSGD_EINVAL;
+        din = dout / cfg->pnorm_group;
+      } else if (cfg->nonlin[l] == NGSGD_TANH) {
+        din = dout;
+      } else {
+        return NGSGD_EINVAL;
+      }
+    }
+  }
+  return NGSGD_OK;
+}
+
+void net_layout(ngsgd_net& net, const ngsgd_config* cfg, Carver& c) {
+  net.n_layers = cfg->n_layers;
+  net.max_batch = cfg->max_batch;
+  net.pnorm_group = cfg->pnorm_group;
+  net.renorm = cfg->renorm ? 1 : 0;
+  net.max_change_per_sample = cfg->max_change_per_sample;
+  net.layers.assign(cfg->n_layers, ngsgd_layer());
+  int din = cfg->dims[0];
+  size_t n_params = 0;
+  int max_ldx = 0;
+  for (int l = 0; l < cfg->n_layers; ++l) {
+    ngsgd_layer& L = net.layers[l];
+    L.din = din;
+    L.dout = cfg->dims[l + 1];
+    L.in1 = din + 1;
+    L.ldw = pad32(L.in1);
+    L.ldx = pad32(L.in1);
+    L.lda = pad32(L.dout);
+    L.nonlin = l < cfg->n_layers - 1 ? cfg->nonlin[l] : -1;
+    L.groups = L.nonlin == NGSGD_PNORM ? L.dout / cfg->pnorm_group : L.dout;
+    n_params += (size_t)L.dout * L.ldw;
+    max_ldx = std::max(max_ldx, L.ldx);
+    din = L.groups;
+  }
+  net.n_params_padded = n_params;
+  net.params = c.take<float>(n_params);
+  size_t off = 0;
+  for (auto& L : net.layers) {
+    L.W = net.params ? net.params + off : nullptr;
+    off += (size_t)L.dout * L.ldw;
+  }
+  net.lddx = max_ldx;
+  net.dX = c.take<float>((size_t)net.max_batch * net.lddx);
+  net.rowobj = c.take<double>(net.max_batch);
+  net.logprob = c.take<double>(1);
+  for (auto& L : net.layers) {
+    L.Xin = c.take<float>((size_t)net.max_batch * L.ldx);
+    L.A = c.take<float>((size_t)net.max_batch * L.lda);
+    L.sigma = c.take<float>(net.max_batch);
+    L.mc_scale = c.take<double>(1);
+    precond_configure(L.pin, L.in1, cfg->rank_in, cfg->max_batch, cfg->alpha, cfg->num_samples_history, cfg->epsilon,
+                      cfg->update_period, cfg->always_update_first);
+    precond_configure(L.pout, L.dout, cfg->rank_out, cfg->max_batch, cfg->alpha, cfg->num_samples_history,
+                      cfg->epsilon, cfg->update_period, cfg->always_update_first);
+    L.pin.owned_by_net = L.pout.owned_by_net = true;
+    precond_layout(L.pin, c);
+    precond_layout(L.pout, c);
+  }
+}
+
+int copy2d(const float* src, int lds_, float* dst, int ldd, int rows, int cols, float scale, const double* scale_dev,
+           hipStream_t s) {
+  hipLaunchKernelGGL(copy2d_kernel, dim3((cols + 1023) / 1024, rows), dim3(256), 0, s, src, lds_, dst, ldd, rows, cols,
+                     scale, scale_dev);
+  LAUNCH_CHECK();
+  return NGSGD_OK;
+}
+
+GemmDesc update_desc(const ngsgd_layer& L, int N, float alpha, float beta, float* C, int ldc) {
+  GemmDesc g;
+  g.A = L.A; g.lda = L.lda;          // O_l stored N x dout: A^T
+  g.B = L.Xin; g.ldb = L.ldx;        // Xbar_l stored N x in1
+  g.C = C; g.ldc = ldc;
+  g.M = L.dout; g.N = L.in1; g.K = N;
+  g.alpha = alpha; g.beta = beta;
+  g.alpha_dev[0] = &L.pout.st->gamma;
+  g.alpha_dev[1] = &L.pin.st->gamma;
+  g.alpha_dev[2] = L.mc_scale;
+  return g;
+}
+
+}  // namespace
+
+extern "C" int ngsgd_workspace_bytes(const ngsgd_config* cfg, size_t* out_bytes) {
+  if (out_bytes == nullptr) return NGSGD_EINVAL;
+  NG_TRY(net_check_config(cfg));
+  ngsgd_net net;
+  Carver c(nullptr);
+  net_layout(net, cfg, c);
+  *out_bytes = align_up(c.off, 256);
+  return NGSGD_OK;
+}
+
+extern "C" int ngsgd_create(const ngsgd_config* cfg, void* dev_workspace, size_t workspace_bytes, ngsgd_net** out) {
+  if (out == nullptr || dev_workspace == nullptr) return NGSGD_EINVAL;
+  if (reinterpret_cast<uintptr_t>(dev_workspace) & 255u) return NGSGD_EINVAL;
+  size_t need = 0;
+  NG_TRY(ngsgd_workspace_bytes(cfg, &need));
+  if (workspace_bytes < need) return NGSGD_ENOMEM;
+  ngsgd_net* net = new (std::nothrow) ngsgd_net();
+  if (net == nullptr) return NGSGD_ENOMEM;
+  Carver c(dev_workspace);
+  net_layout(*net, cfg, c);
+  hipError_t e = hipMemset(dev_workspace, 0, need);
+  PrecondScalars init;
+  std::memset(&init, 0, sizeof(init));
+  init.gamma = 1.0;
+  const double one = 1.0;
+  for (auto& L : net->layers) {
+    if (e == hipSuccess) e = hipMemcpy(L.pin.st, &init, sizeof(init), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(L.pout.st, &init, sizeof(init), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipMemcpy(L.mc_scale, &one, sizeof(one), hipMemcpyHostToDevice);
+  }
+  if (e == hipSuccess) e = hipDeviceSynchronize();
+  if (e != hipSuccess) {
+    g_last_hip_error = (int)e;
+    delete net;
+    return NGSGD_EHIP;
+  }
+  *out = net;
+  return NGSGD_OK;
+}
+
+extern "C" int ngsgd_destroy(ngsgd_net* net) {
+  if (net == nullptr) return NGSGD_EINVAL;
+  delete net;
+  return NGSGD_OK;
+}
+
+extern "C" int ngsgd_step(ngsgd_net* net, const float* dev_x, const int32_t* dev_labels, int32_t N, float lr,
+                          double* dev_logprob_sum, void* hip_stream) {
+  if (net == nullptr || dev_x == nullptr || dev_labels == nullptr) return NGSGD_EINVAL;
+  if (N < 1 || N > net->max_batch || !aligned16(dev_x)) return NGSGD_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const int nl = net->n_layers;
+  auto& Ls = net->layers;
+  for (auto& L : Ls) {   // argument errors must leave the state untouched: check before any launch
+    if (L.pin.rank > 0 && L.pin.t == 0 && N <= L.pin.rank) return NGSGD_EINVAL;
+    if (L.pout.rank > 0 && L.pout.t == 0 && N <= L.pout.rank) return NGSGD_EINVAL;
+  }
+
+  // forward (Sec. 2): A_l = [X_l, 1] W_l^T, nonlinearity, log-softmax
+  hipLaunchKernelGGL(copy_append_ones_kernel, dim3((Ls[0].ldx + 255) / 256, N), dim3(256), 0, s, dev_x, Ls[0].din,
+                     Ls[0].Xin, Ls[0].ldx, N, Ls[0].din);
+  LAUNCH_CHECK();
+  for (int l = 0; l < nl; ++l) {
+    ngsgd_layer& L = Ls[l];
+    GemmDesc g;
+    g.A = L.Xin; g.lda = L.ldx;
+    g.B = L.W; g.ldb = L.ldw;
+    g.C = L.A; g.ldc = L.lda;
+    g.M = N; g.N = L.dout; g.K = L.in1;
+    NG_TRY(launch_layer_gemms(GEMM_FWD, &g, 1, s));
+    if (l < nl - 1) {
+      ngsgd_layer& Nx = Ls[l + 1];
+      if (L.nonlin == NGSGD_TANH) {
+        hipLaunchKernelGGL(tanh_forward_kernel, dim3((Nx.ldx + 1023) / 1024, N), dim3(256), 0, s, L.A, L.lda, Nx.Xin,
+                           Nx.ldx, N, L.dout);
+      } else {
+        hipLaunchKernelGGL(pnorm_forward_kernel, dim3((N + 3) / 4), dim3(256), 0, s, L.A, L.lda, Nx.Xin, Nx.ldx,
+                           L.sigma, N, L.groups, net->pnorm_group, net->renorm);
+      }
+      LAUNCH_CHECK();
+    }
+  }
+  ngsgd_layer& last = Ls[nl - 1];
+  hipLaunchKernelGGL(softmax_xent_kernel, dim3(N), dim3(256), 0, s, last.A, last.lda, dev_labels, N, last.dout,
+                     net->rowobj);
+  LAUNCH_CHECK();
+  hipLaunchKernelGGL(sum_double_kernel, dim3(1), dim3(256), 0, s, net->rowobj, N,
+                     dev_logprob_sum != nullptr ? dev_logprob_sum : net->logprob);
+  LAUNCH_CHECK();
+
+  // backward on the unmodified derivatives (App. C.3, last paragraph)
+  for (int l = nl - 1; l >= 1; --l) {
+    ngsgd_layer& L = Ls[l];
+    ngsgd_layer& P = Ls[l - 1];
+    GemmDesc g;
+    g.A = L.A; g.lda = L.lda;           // O_l, N x dout
+    g.B = L.W; g.ldb = L.ldw;           // W_l as dout x din (bias column dropped)
+    g.C = net->dX; g.ldc = net->lddx;
+    g.M = N; g.N = L.din; g.K = L.dout;
+    NG_TRY(launch_layer_gemms(GEMM_BWD, &g, 1, s));
+    if (P.nonlin == NGSGD_TANH) {
+      hipLaunchKernelGGL(tanh_backward_kernel, dim3((P.dout + 1023) / 1024, N), dim3(256), 0, s, net->dX, net->lddx,
+                         L.Xin, L.ldx, P.A, P.lda, N, P.dout);
+    } else {
+      hipLaunchKernelGGL(pnorm_backward_kernel, dim3((N + 3) / 4), dim3(256), 0, s, net->dX, net->lddx, L.Xin, L.ldx,
+                         P.sigma, P.A, P.lda, N, P.groups, net->pnorm_group, net->renorm);
+    }
+    LAUNCH_CHECK();
+  }
+
+  // natural gradient: both matrices of every layer (Sec. 4.6; 2I instances)
+  std::vector<PrecondCall> calls;
+  for (auto& L : Ls) {
+    calls.push_back(PrecondCall{&L.pout, L.A, L.lda, N, nullptr, nullptr});
+    calls.push_back(PrecondCall{&L.pin, L.Xin, L.ldx, N, nullptr, nullptr});
+  }
+  NG_TRY(precondition_many(calls, false, s));
+
+  // maximum parameter change (App. C.3), then W_l += lr a_l gamma_o gamma_x Ohat_l^T Xhat_l  (Sec. 4.6)
+  {
+    MaxChangeGroup g;
+    g.count = nl;
+    g.lr = lr;
+    g.max_change_per_sample = net->max_change_per_sample;
+    for (int l = 0; l < nl; ++l) {
+      MaxChangeArgs& a = g.a[l];
+      a.prow_o = Ls[l].pout.prow;
+      a.prow_x = Ls[l].pin.prow;
+      a.gamma_o = &Ls[l].pout.st->gamma;
+      a.gamma_x = &Ls[l].pin.st->gamma;
+      a.scale_out = Ls[l].mc_scale;
+      a.N = N;
+    }
+    if (net->max_change_per_sample > 0.0) {
+      hipLaunchKernelGGL(max_change_kernel, dim3(nl), dim3(256), 0, s, g);
+      LAUNCH_CHECK();
+    }
+  }
+  std::vector<GemmDesc> upd;
+  for (auto& L : Ls) upd.push_back(update_desc(L, N, lr, 1.f, L.W, L.ldw));
+  NG_TRY(launch_layer_gemms(GEMM_UPD, upd.data(), (int)upd.size(), s));
+  net->last_N = N;
+  net->last_lr = lr;
+  return NGSGD_OK;
+}
+
+extern "C" int ngsgd_average(ngsgd_net* const* nets, int32_t n, int32_t reset_preconditioners, void* hip_stream) {
+  if (nets == nullptr || n < 1 || n > kMaxReplicas) return NGSGD_EINVAL;
+  for (int i = 0; i < n; ++i) {
+    if (nets[i] == nullptr) return NGSGD_EINVAL;
+    if (nets[i]->n_params_padded != nets[0]->n_params_padded || nets[i]->n_layers != nets[0]->n_layers)
+      return NGSGD_EINVAL;
+    for (int l = 0; l < nets[0]->n_layers; ++l)
+      if (nets[i]->layers[l].dout != nets[0]->layers[l].dout || nets[i]->layers[l].din != nets[0]->layers[l].din)
+        return NGSGD_EINVAL;
+  }
+  AverageArgs a;
+  a.n = n;
+  a.count = nets[0]->n_params_padded;
+  for (int i = 0; i < n; ++i) a.params[i] = nets[i]->params;
+  size_t blocks = (a.count + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  hipLaunchKernelGGL(average_kernel, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream), a);
+  LAUNCH_CHECK();
+  if (reset_preconditioners)
+    for (int i = 0; i < n; ++i)
+      for (auto& L : nets[i]->layers) L.pin.t = L.pout.t = 0;
+  return NGSGD_OK;
+}
+
+extern "C" int ngsgd_get_params(const ngsgd_net* net, int32_t layer, float* dev_out, void* hip_stream) {
+  if (net == nullptr || dev_out == nullptr || layer < 0 || layer >= net->n_layers) return NGSGD_EINVAL;
+  const ngsgd_layer& L = net->layers[layer];
+  return copy2d(L.W, L.ldw, dev_out, L.in1, L.dout, L.in1, 1.f, nullptr, static_cast<hipStream_t>(hip_stream));
+}
+
+extern "C" int ngsgd_set_params(ngsgd_net* net, int32_t layer, const float* dev_in, void* hip_stream) {
+  if (net == nullptr || dev_in == nullptr || layer < 0 || layer >= net->n_layers) return NGSGD_EINVAL;
+  ngsgd_layer& L = net->layers[layer];
+  return copy2d(dev_in, L.in1, L.W, L.ldw, L.dout, L.in1, 1.f, nullptr, static_cast<hipStream_t>(hip_stream));
+}
+
+extern "C" int ngsgd_net_precond(ngsgd_net* net, int32_t layer, int32_t side, ngsgd_precond** out) {
+  if (net == nullptr || out == nullptr || layer < 0 || layer >= net->n_layers) return NGSGD_EINVAL;
+  if (side != NGSGD_SIDE_INPUT && side != NGSGD_SIDE_OUTPUT) return NGSGD_EINVAL;
+  ngsgd_layer& L = net->layers[layer];
+  ngsgd_precond* p = side == NGSGD_SIDE_INPUT ? &L.pin : &L.pout;
+  *out = p->rank > 0 ? p : nullptr;
+  return NGSGD_OK;
+}
+
+extern "C" int ngsgd_last_preconditioned(ngsgd_net* net, int32_t layer, int32_t side, float* dev_out,
+                                         void* hip_stream) {
+  if (net == nullptr || dev_out == nullptr || layer < 0 || layer >= net->n_layers || net->last_N < 1)
+    return NGSGD_EINVAL;
+  if (side != NGSGD_SIDE_INPUT && side != NGSGD_SIDE_OUTPUT) return NGSGD_EINVAL;
+  ngsgd_layer& L = net->layers[layer];
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  if (side == NGSGD_SIDE_INPUT)
+    return copy2d(L.Xin, L.ldx, dev_out, L.in1, net->last_N, L.in1, 1.f, &L.pin.st->gamma, s);
+  return copy2d(L.A, L.lda, dev_out, L.dout, net->last_N, L.dout, 1.f, &L.pout.st->gamma, s);
+}
+
+extern "C" int ngsgd_last_gradient(ngsgd_net* net, int32_t layer, float* dev_out, void* hip_stream) {
+  if (net == nullptr || dev_out == nullptr || layer < 0 || layer >= net->n_layers || net->last_N < 1)
+    return NGSGD_EINVAL;
+  ngsgd_layer& L = net->layers[layer];
+  GemmDesc g = update_desc(L, net->last_N, 1.f, 0.f, dev_out, L.in1);
+  return launch_layer_gemms(GEMM_UPD, &g, 1, static_cast<hipStream_t>(hip_stream));
+}
+
+extern "C" int ngsgd_last_max_change_scale(ngsgd_net* net, int32_t layer, double* dev_out, void* hip_stream) {
+  if (net == nullptr || dev_out == nullptr || layer < 0 || layer >= net->n_layers) return NGSGD_EINVAL;
+  HIP_TRY(hipMemcpyAsync(dev_out, net->layers[layer].mc_scale, sizeof(double), hipMemcpyDeviceToDevice,
+                         static_cast<hipStream_t>(hip_stream)));
+  return NGSGD_OK;
+}
+
+extern "C" const char* ngsgd_strerror(int code) {
+  switch (code) {
+    case NGSGD_OK: return "ok";
+    case NGSGD_EINVAL: return "invalid argument";
+    case NGSGD_ENOMEM: return "workspace too small";
+    case NGSGD_EHIP: return "HIP runtime error";
+    case NGSGD_EUNSUPPORTED: return "unsupported";
+    default: return "unknown error";
+  }
+}
+
+extern "C" int ngsgd_last_hip_error(void) { return g_last_hip_error; }
+extern "C" int ngsgd_version(void) { return 100; }

@@ -1,0 +1,153 @@
+"""GPU parity: ngsgd_step / ngsgd_average (through the C ABI) against the float64 oracle.
+
+Bars (the benchmark spec): 1e-4 relative Frobenius error per preconditioned matrix and per gradient on the
+same seeded inputs; 1e-3 absolute on the mean per-frame log-probability after 10 free-running steps.
+"""
+import numpy as np
+import pytest
+
+import workloads
+from oracle.averaging import average_parameters
+from oracle.network import NGSGDNetwork
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1.0e-4
+
+
+def rel(a, b):
+    a = np.asarray(a, np.float64)
+    b = np.asarray(b, np.float64)
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
+
+
+def make_pair(ngsgd, spec, renorm=False, max_change=0.0, weights=None, max_batch=None):
+    import torch
+    weights = workloads.initial_weights(spec) if weights is None else weights
+    ora = NGSGDNetwork(spec.dims, spec.nonlin, weights, spec.pnorm_group, spec.rank_in, spec.rank_out, spec.alpha,
+                       spec.num_samples_history, spec.epsilon, spec.update_period, renorm=renorm,
+                       max_change_per_sample=max_change)
+    gpu = ngsgd.Network(spec.dims, spec.nonlin, max_batch or spec.minibatch, spec.pnorm_group, spec.rank_in,
+                        spec.rank_out, spec.alpha, spec.num_samples_history, spec.epsilon, spec.update_period,
+                        renorm=renorm, max_change_per_sample=max_change)
+    for l, w in enumerate(weights):
+        gpu.set_params(l, torch.from_numpy(np.ascontiguousarray(w, dtype=np.float32)).cuda())
+    return ora, gpu
+
+
+def run_and_compare(ngsgd, spec, ora, gpu, steps, check_every=1, rows=None, tol=TOL, logp_tol=1e-3):
+    import torch
+    worst = dict(pre=0.0, grad=0.0, logp=0.0)
+    for t in range(steps):
+        x, y = workloads.minibatch(spec, t, rows=rows)
+        obj_o = ora.step(x, y, spec.lr)
+        out = gpu.step(torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda(), spec.lr)
+        torch.cuda.synchronize()
+        obj_g = float(out.item())
+        n = len(y)
+        worst["logp"] = max(worst["logp"], abs(obj_g - obj_o) / n)
+        assert abs(obj_g - obj_o) / n < logp_tol, f"step {t}: mean log-prob {obj_g / n} vs {obj_o / n}"
+        if t % check_every == 0 or t == steps - 1:
+            for l in range(spec.n_layers):
+                xo = gpu.last_preconditioned(l, ngsgd.NGSGD_SIDE_INPUT, n).cpu().numpy()
+                oo = gpu.last_preconditioned(l, ngsgd.NGSGD_SIDE_OUTPUT, n).cpu().numpy()
+                e_x, e_o = rel(xo, ora.last["Xbar"][l]), rel(oo, ora.last["Obar"][l])
+                grad = gpu.last_gradient(l).cpu().numpy()
+                e_g = rel(grad, ora.last["delta"][l])
+                worst["pre"] = max(worst["pre"], e_x, e_o)
+                worst["grad"] = max(worst["grad"], e_g)
+                assert e_x < tol and e_o < tol, f"step {t} layer {l}: Xbar {e_x:.2e} Obar {e_o:.2e}"
+                assert e_g < tol, f"step {t} layer {l}: gradient {e_g:.2e}"
+                mc = float(gpu.last_max_change_scale(l).item())
+                assert mc == pytest.approx(ora.last["max_change_scale"][l], rel=1e-4)
+    for l in range(spec.n_layers):
+        assert rel(gpu.get_params(l).cpu().numpy(), ora.W[l]) < tol
+    return worst
+
+
+def test_c0_ten_steps_free_running(ngsgd):
+    """BASELINE configs[0]: tiny tanh MLP, minibatch 64, ranks 4 / 8, lr 0.01, 10 steps from the seed."""
+    spec = workloads.c0_tiny()
+    ora, gpu = make_pair(ngsgd, spec)
+    worst = run_and_compare(ngsgd, spec, ora, gpu, spec.steps)
+    print("c0 worst errors", worst)
+
+
+def test_small_pnorm_net_with_renorm_and_max_change(ngsgd):
+    """Reduced p-norm net with ragged sizes: p-norm, renormalisation, max-change, zero-initialised softmax."""
+    spec = workloads.small_pnorm()
+    ora, gpu = make_pair(ngsgd, spec, renorm=True, max_change=0.075)
+    run_and_compare(ngsgd, spec, ora, gpu, spec.steps)
+    assert min(ora.last["max_change_scale"]) <= 1.0
+
+
+def test_small_pnorm_net_plain(ngsgd):
+    """Same net without the stabilisers, smaller last minibatch, update period 1."""
+    spec = workloads.small_pnorm()
+    spec.update_period = 1
+    spec.lr = 0.002
+    ora, gpu = make_pair(ngsgd, spec)
+    run_and_compare(ngsgd, spec, ora, gpu, 5)
+    run_and_compare(ngsgd, spec, ora, gpu, 2, rows=spec.minibatch - 9)
+
+
+def test_rank_zero_is_plain_sgd(ngsgd):
+    spec = workloads.c0_tiny()
+    spec.rank_in = spec.rank_out = 0
+    ora, gpu = make_pair(ngsgd, spec)
+    run_and_compare(ngsgd, spec, ora, gpu, 3)
+    assert gpu.precond(0, ngsgd.NGSGD_SIDE_INPUT) is None
+
+
+def test_c1_full_size_first_steps(ngsgd):
+    """BASELINE configs[1] at full size (360 -> 4 x p-norm 3000/300 -> 5000, minibatch 512, ranks 20 / 80) in the
+    configuration bench.py times: renormalised p-norm layers and the max-change limit."""
+    spec = workloads.c1_pnorm()
+    ora, gpu = make_pair(ngsgd, spec, renorm=True, max_change=0.075)
+    worst = run_and_compare(ngsgd, spec, ora, gpu, 4)
+    print("c1 worst errors", worst)
+
+
+def test_step_argument_errors(ngsgd):
+    import torch
+    spec = workloads.c0_tiny()
+    _, gpu = make_pair(ngsgd, spec)
+    x, y = workloads.minibatch(spec, 0, rows=80)
+    with pytest.raises(ngsgd.NgsgdError):
+        gpu.step(torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda(), 0.01)       # N > max_batch
+    x, y = workloads.minibatch(spec, 0, rows=6)
+    with pytest.raises(ngsgd.NgsgdError):
+        gpu.step(torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda(), 0.01)       # N <= rank on the first step
+    torch.cuda.synchronize()
+
+
+def test_average_replicas(ngsgd):
+    """Sec. 3.1: every replica ends with the arithmetic mean; preconditioners restart as new processes do."""
+    import torch
+    spec = workloads.c0_tiny()
+    pairs = [make_pair(ngsgd, spec) for _ in range(3)]
+    for r, (ora, gpu) in enumerate(pairs):
+        for t in range(2):
+            x, y = workloads.minibatch(spec, t, replica=r)
+            ora.step(x, y, spec.lr)
+            gpu.step(torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda(), spec.lr)
+    before = [[g.get_params(l).cpu().numpy().astype(np.float64) for l in range(spec.n_layers)] for _, g in pairs]
+    average_parameters([o for o, _ in pairs])
+    ngsgd.average([g for _, g in pairs], reset_preconditioners=True)
+    torch.cuda.synchronize()
+    for _, g in pairs:
+        for l in range(spec.n_layers):
+            got = g.get_params(l).cpu().numpy()
+            mean = sum(b[l] for b in before) / 3.0
+            np.testing.assert_allclose(got, mean, rtol=0, atol=2e-7 * np.abs(mean).max())
+            assert rel(got, pairs[0][0].W[l]) < TOL
+        assert g.precond(0, ngsgd.NGSGD_SIDE_OUTPUT).get_state()[3] == 0
+    # replicas continue (re-initialising their factors) and still match the oracle
+    for r, (ora, gpu) in enumerate(pairs[:2]):
+        x, y = workloads.minibatch(spec, 5, replica=r)
+        obj_o = ora.step(x, y, spec.lr)
+        out = gpu.step(torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda(), spec.lr)
+        torch.cuda.synchronize()
+        assert abs(float(out.item()) - obj_o) / len(y) < 1e-3
+        for l in range(spec.n_layers):
+            assert rel(gpu.last_gradient(l).cpu().numpy(), ora.last["delta"][l]) < TOL

@@ -1,0 +1,109 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every declared symbol, and its host-only
+entry points (sizing, argument validation, error strings) behave.  No kernel is launched here."""
+import ctypes
+import os
+import re
+from ctypes import byref, c_int32, c_size_t, c_void_p
+
+import pytest
+
+import paper_1410_7455_amd as ng
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "ngsgd.h")
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ngsgd_[a-z0-9_]+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(ng.LIB_PATH):
+        from paper_1410_7455_amd.build import build
+        build()
+    return ng.load_library()
+
+
+def test_every_declared_symbol_is_exported_and_bound(lib):
+    names = declared_functions()
+    assert len(names) >= 20
+    for name in names:
+        assert hasattr(lib, name), f"{name} is declared in ngsgd.h but not exported"
+        assert name in ng._SIGNATURES, f"{name} has no Python signature"
+    assert sorted(ng._SIGNATURES) == names
+
+
+def test_error_strings_and_version(lib):
+    assert lib.ngsgd_strerror(0) == b"ok"
+    assert lib.ngsgd_strerror(ng.NGSGD_EINVAL) == b"invalid argument"
+    assert lib.ngsgd_strerror(ng.NGSGD_ENOMEM) == b"workspace too small"
+    assert lib.ngsgd_version() >= 100
+
+
+def test_precond_workspace_sizing_and_argument_errors(lib):
+    n = c_size_t(0)
+    assert lib.ngsgd_precond_workspace_bytes(5000, 80, 512, byref(n)) == 0
+    big = n.value
+    assert big % 256 == 0 and big > 80 * 5000 * 4
+    assert lib.ngsgd_precond_workspace_bytes(301, 20, 512, byref(n)) == 0
+    assert 0 < n.value < big
+    assert lib.ngsgd_precond_workspace_bytes(301, 0, 512, byref(n)) == 0        # rank 0 is allowed
+    for dim, rank, mb in [(20, 20, 64), (20, 25, 64), (100, ng.NGSGD_MAX_RANK + 1, 64), (0, 0, 64), (100, 4, 0),
+                          (100, -1, 64)]:
+        assert lib.ngsgd_precond_workspace_bytes(dim, rank, mb, byref(n)) == ng.NGSGD_EINVAL
+    h = c_void_p(0)
+    # NULL workspace / NULL out pointer are rejected before any device work
+    assert lib.ngsgd_precond_create(100, 4, 64, 4.0, 2000.0, 1e-10, 4, 10, None, 1 << 20, byref(h)) == ng.NGSGD_EINVAL
+    assert lib.ngsgd_precond_reset(None) == ng.NGSGD_EINVAL
+    assert lib.ngsgd_precondition(None, None, 1, 4, None, None, None) == ng.NGSGD_EINVAL
+
+
+def make_cfg(dims, nonlin, **kw):
+    d = (c_int32 * len(dims))(*dims)
+    nl = (c_int32 * max(1, len(nonlin)))(*nonlin)
+    vals = dict(pnorm_group=10, max_batch=512, rank_in=20, rank_out=80, alpha=4.0, num_samples_history=2000.0,
+                epsilon=1e-10, update_period=4, always_update_first=10, renorm=0, max_change_per_sample=0.0)
+    vals.update(kw)
+    cfg = ng.ngsgd_config(len(dims) - 1, d, nl, vals["pnorm_group"], vals["max_batch"], vals["rank_in"],
+                          vals["rank_out"], vals["alpha"], vals["num_samples_history"], vals["epsilon"],
+                          vals["update_period"], vals["always_update_first"], vals["renorm"],
+                          vals["max_change_per_sample"])
+    cfg._keep = (d, nl)
+    return cfg
+
+
+def test_network_workspace_sizing_and_config_validation(lib):
+    n = c_size_t(0)
+    cfg = make_cfg([360, 3000, 3000, 3000, 3000, 5000], [1, 1, 1, 1])
+    assert lib.ngsgd_workspace_bytes(byref(cfg), byref(n)) == 0
+    # at least the parameters (5.297 M floats) and the activations of one minibatch
+    assert n.value > 5_297_000 * 4 + 512 * (4 * 3000 + 5000) * 4
+    assert n.value < 1 << 30
+    bad = [
+        make_cfg([360, 3005, 5000], [1]),                 # p-norm group does not divide
+        make_cfg([361, 3000, 5000], [1]),                 # input dimension not a multiple of 4
+        make_cfg([360, 3000, 5000], [7]),                 # unknown nonlinearity
+        make_cfg([360, 3000, 5000], [1], rank_out=97),    # rank above the limit
+        make_cfg([360, 3000, 50], [1], rank_out=50),      # rank >= dim
+        make_cfg([360, 3000, 5000], [1], max_batch=0),
+        make_cfg([360, 3000, 5000], [1], update_period=0),
+        make_cfg([360, 3000, 5000], [1], max_change_per_sample=-1.0),
+    ]
+    for cfg in bad:
+        assert lib.ngsgd_workspace_bytes(byref(cfg), byref(n)) == ng.NGSGD_EINVAL
+    assert lib.ngsgd_workspace_bytes(None, byref(n)) == ng.NGSGD_EINVAL
+    h = c_void_p(0)
+    cfg = make_cfg([40, 128, 50], [0], rank_in=4, rank_out=8, max_batch=64)
+    assert lib.ngsgd_create(byref(cfg), None, 1 << 20, byref(h)) == ng.NGSGD_EINVAL
+    assert lib.ngsgd_step(None, None, None, 1, 0.01, None, None) == ng.NGSGD_EINVAL
+    assert lib.ngsgd_average(None, 1, 1, None) == ng.NGSGD_EINVAL
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(ng, "_lib", None)
+    monkeypatch.setattr(ng, "LIB_PATH", os.path.join(ROOT, "does_not_exist", "libngsgd.so"))
+    with pytest.raises(ImportError):
+        ng.load_library()
