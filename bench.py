@@ -1,0 +1,249 @@
+"""Benchmark of the NG-SGD minibatch step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+A step is one pass of the whole hot path (forward, objective, backward, natural-gradient
+preconditioning of both matrices of every layer, rank-N update) over one synthetic minibatch of the
+speech-shaped p-norm DNN workload (BASELINE configs[1]: 360 -> 4 x (affine 3000, p-norm 10 -> 300) ->
+5000-way softmax, minibatch 512, ranks 20 / 80, fp32), with the renormalisation layer and the
+max-change limit of the paper's recipe enabled.  Inputs are resident in HBM before the timed region.
+
+Prints ONE JSON line on stdout; progress and the breakdown go to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_MFMA_F32_TFLOPS = 157.3      # MI355X dense fp32 matrix peak
+PEAK_HBM_GBS = 8000.0             # MI355X HBM3E
+POOL = 16                         # distinct minibatches resident on the GPU, cycled
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def gemm_flops_per_step(spec, n):
+    fwd = sum(2.0 * n * (spec.in_dims[l] + 1) * spec.dims[l + 1] for l in range(spec.n_layers))
+    bwd = sum(2.0 * n * spec.in_dims[l] * spec.dims[l + 1] for l in range(1, spec.n_layers))
+    return dict(gemm_fwd=fwd, gemm_bwd=bwd, gemm_upd=fwd)
+
+
+def precond_flops(n, d, r, update):
+    f = 2.0 * n * d * r * 2            # H and Xhat
+    if update:
+        f += 2.0 * n * d * r           # J
+        f += 2.0 * r * r * d + 2.0 * r * r * n + 2.0 * r * r * d   # K, L, W_{t+1}
+    return f
+
+
+def precond_bytes(n, d, r, update):
+    # read X once, write Xbar once, read W (and write it when the factor is updated)
+    return 4.0 * (2.0 * n * d + (2.0 if update else 1.0) * r * d)
+
+
+def run_step_bench(args):
+    import numpy as np
+    import torch
+
+    import paper_1410_7455_amd as ng
+    import workloads
+
+    spec = workloads.c1_pnorm()
+    n = spec.minibatch
+    net = ng.Network(spec.dims, spec.nonlin, n, spec.pnorm_group, spec.rank_in, spec.rank_out, spec.alpha,
+                     spec.num_samples_history, spec.epsilon, spec.update_period, renorm=True,
+                     max_change_per_sample=0.075)
+    for l, w in enumerate(workloads.initial_weights(spec)):
+        net.set_params(l, torch.from_numpy(w).cuda())
+    pool = []
+    for t in range(POOL):
+        x, y = workloads.minibatch(spec, t)
+        pool.append((torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda()))
+    logp = torch.zeros(1, dtype=torch.float64, device="cuda")
+    torch.cuda.synchronize()
+
+    step_no = 0
+    for _ in range(args.warmup):
+        x, y = pool[step_no % POOL]
+        net.step(x, y, spec.lr, logp)
+        step_no += 1
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        x, y = pool[step_no % POOL]
+        net.step(x, y, spec.lr, logp)
+        step_no += 1
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    final_logp = float(logp.item()) / n
+    ms_per_step = elapsed * 1e3 / args.steps
+    frames_per_s = n * args.steps / elapsed
+    log(f"[bench] {args.steps} steps in {elapsed:.3f} s -> {ms_per_step:.3f} ms/step, {frames_per_s:,.0f} frames/s, "
+        f"mean log-prob of last minibatch {final_logp:.4f}")
+    if not np.isfinite(final_logp):
+        raise RuntimeError("training diverged: the benchmark number would be meaningless")
+
+    # second pass with per-category HIP events on the launch stream (same steps, same shapes)
+    ng.profile_enable(True)
+    for _ in range(args.steps):
+        x, y = pool[step_no % POOL]
+        net.step(x, y, spec.lr, logp)
+        step_no += 1
+    torch.cuda.synchronize()
+    prof = ng.profile_read()
+    ng.profile_enable(False)
+    flops = gemm_flops_per_step(spec, n)
+    total_ms = sum(ms for ms, _ in prof.values())
+    breakdown = {}
+    for name, (ms, cnt) in prof.items():
+        if cnt == 0:
+            continue
+        entry = dict(ms_per_step=ms / args.steps, launches_per_step=cnt / args.steps, share=ms / total_ms)
+        if name in flops:
+            entry["tflops"] = flops[name] * args.steps / (ms * 1e-3) / 1e12
+        breakdown[name] = entry
+        log(f"[bench]   {name:14s} {entry['ms_per_step'] * 1e3:9.1f} us/step  {entry['share'] * 100:5.1f} %"
+            + (f"  {entry['tflops']:6.1f} TFLOP/s" if "tflops" in entry else ""))
+    dominant = max((k for k in breakdown if k in flops), key=lambda k: breakdown[k]["ms_per_step"])
+    ms, cnt = prof[dominant]
+    achieved = flops[dominant] * args.steps / (ms * 1e-3) / 1e12
+    roofline = dict(bound="mfma", kernel=dominant, achieved=achieved, peak=PEAK_MFMA_F32_TFLOPS, unit="TFLOP/s",
+                    frac=achieved / PEAK_MFMA_F32_TFLOPS, traffic=None,
+                    flops_per_launch=flops[dominant] * args.steps / cnt, avg_launch_us=ms * 1e3 / cnt,
+                    all_gemms_tflops=sum(flops.values()) * args.steps /
+                    (sum(prof[k][0] for k in flops) * 1e-3) / 1e12)
+    return spec, ms_per_step, frames_per_s, roofline, breakdown, final_logp
+
+
+def run_precond_bench(calls=200):
+    """BASELINE configs[2]: the preconditioner alone, successive online updates (update on every call)."""
+    import torch
+
+    import paper_1410_7455_amd as ng
+    import workloads
+
+    out = []
+    for spec in (workloads.c2_input_side(), workloads.c2_output_side()):
+        ld = (spec.dim + 3) // 4 * 4
+        pre = ng.Preconditioner(spec.dim, spec.rank, spec.rows, update_period=spec.update_period)
+        pool = []
+        for t in range(POOL):
+            buf = torch.zeros((spec.rows, ld), dtype=torch.float32, device="cuda")
+            buf[:, :spec.dim] = torch.from_numpy(workloads.spectrum_matrix(spec, t)).cuda()
+            pool.append(buf)
+        work = torch.empty_like(pool[0])
+        for t in range(12):                      # initialisation and the first updates are not timed
+            work.copy_(pool[t % POOL])
+            pre.precondition(work)
+        torch.cuda.synchronize()
+        starts = [torch.cuda.Event(enable_timing=True) for _ in range(calls)]
+        stops = [torch.cuda.Event(enable_timing=True) for _ in range(calls)]
+        for t in range(calls):
+            work.copy_(pool[t % POOL])
+            starts[t].record()
+            pre.precondition(work)
+            stops[t].record()
+        torch.cuda.synchronize()
+        us = sum(s.elapsed_time(e) for s, e in zip(starts, stops)) * 1e3 / calls
+        nbytes = precond_bytes(spec.rows, spec.dim, spec.rank, True)
+        fl = precond_flops(spec.rows, spec.dim, spec.rank, True)
+        gbs = nbytes / (us * 1e-6) / 1e9
+        tfl = fl / (us * 1e-6) / 1e12
+        entry = dict(workload=spec.name, us_per_call=us, algorithmic_bytes=nbytes, achieved_gbs=gbs,
+                     hbm_frac=gbs / PEAK_HBM_GBS, flops=fl, achieved_tflops=tfl,
+                     mfma_frac=tfl / PEAK_MFMA_F32_TFLOPS, update_every_call=True)
+        log(f"[bench] precondition {spec.name}: {us:.1f} us/call, {gbs:.0f} GB/s algorithmic "
+            f"({entry['hbm_frac'] * 100:.1f} % of HBM peak), {tfl:.2f} TFLOP/s")
+        out.append(entry)
+        del pre
+    return out
+
+
+def run_cpu_baseline(max_steps=20, budget_s=25.0):
+    """The float64 oracle as it stands, timed on the host cores on a bounded sample of the same workload."""
+    import workloads
+    from oracle.network import NGSGDNetwork
+
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count() or 1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    spec = workloads.c1_pnorm()
+    net = NGSGDNetwork(spec.dims, spec.nonlin, workloads.initial_weights(spec), spec.pnorm_group, spec.rank_in,
+                       spec.rank_out, spec.alpha, spec.num_samples_history, spec.epsilon, spec.update_period,
+                       renorm=True, max_change_per_sample=0.075)
+    batches = [workloads.minibatch(spec, t) for t in range(max_steps + 1)]
+    net.step(*batches[0], spec.lr)          # state initialisation (eigen-decompositions) is not timed
+    done = 0
+    t0 = time.perf_counter()
+    while done < max_steps and time.perf_counter() - t0 < budget_s:
+        net.step(*batches[done + 1], spec.lr)
+        done += 1
+    elapsed = time.perf_counter() - t0
+    value = spec.minibatch * done / elapsed
+    log(f"[bench] oracle (float64 NumPy, {threads} threads): {done} steps in {elapsed:.1f} s -> {value:,.0f} frames/s")
+    return dict(value=value, unit="frames/s", cores=threads, kind="oracle",
+                sample=f"{done} steps of the same workload after 1 untimed initialisation step")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-precond", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py measures one GPU: this build has no multi-GPU path (replicas only exchange parameters "
+            "at averaging points; see DESIGN.md).  Run with --gpus 1.")
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        log("bench.py needs a GPU")
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    spec, ms_per_step, frames_per_s, roofline, breakdown, final_logp = run_step_bench(args)
+    precond = None if args.no_precond else run_precond_bench()
+    cpu = None if args.no_cpu_baseline else run_cpu_baseline()
+    result = {
+        "metric": "NG-SGD training frames/sec (p-norm DNN, mb 512) + precondition % roofline",
+        "value": frames_per_s,
+        "unit": "frames/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {
+            "workload": "configs[1] speech-shaped p-norm DNN: 360 -> 4x(3000 -> p-norm 300) -> 5000, "
+                        "minibatch 512, ranks 20/80, update period 4, renorm + max-change 0.075, lr 0.01",
+            "minibatch": spec.minibatch,
+            "params": spec.n_params(),
+            "pool_minibatches": POOL,
+            "final_mean_logprob": final_logp,
+        },
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "precondition_roofline": precond,
+        "breakdown": breakdown,
+    }
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

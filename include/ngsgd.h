@@ -157,6 +157,28 @@ int ngsgd_last_preconditioned(ngsgd_net* net, int32_t layer, int32_t side, float
 int ngsgd_last_gradient(ngsgd_net* net, int32_t layer, float* dev_out, void* hip_stream);
 int ngsgd_last_max_change_scale(ngsgd_net* net, int32_t layer, double* dev_out, void* hip_stream);
 
+/* ---- timing of kernel groups (for benchmarks) ------------------------------------------------
+ * While enabled, every launch group of the categories below is bracketed by a pair of HIP events
+ * recorded on the launch stream.  ngsgd_profile_read waits for the recorded events, adds the elapsed
+ * milliseconds and the number of bracketed groups per category into ms_out / launches_out (arrays of
+ * n_categories >= NGSGD_PROF_CATEGORIES entries, host memory) and clears the record.  Process-wide,
+ * not thread-safe; at most 32768 groups are kept between reads. */
+#define NGSGD_PROF_GEMM_FWD 0        /* A_l = [X_l, 1] W_l^T                                     */
+#define NGSGD_PROF_GEMM_BWD 1        /* dX_l = O_l W_l                                           */
+#define NGSGD_PROF_GEMM_UPD 2        /* W_l += lr Obar_l^T Xbar_l (one grouped launch per step)  */
+#define NGSGD_PROF_PRECOND_H 3       /* H = X W^T and tr(X X^T)                                  */
+#define NGSGD_PROF_PRECOND_J 4       /* J = H^T X                                                */
+#define NGSGD_PROF_PRECOND_XHAT 5    /* Xhat = X - H W and row norms                             */
+#define NGSGD_PROF_PRECOND_KL 6      /* K = J J^T, L = H^T H                                     */
+#define NGSGD_PROF_PRECOND_SMALL 7   /* R x R update: Z_t, eigen-decomposition, A_t              */
+#define NGSGD_PROF_PRECOND_WNEW 8    /* W_{t+1} = A_t B_t                                        */
+#define NGSGD_PROF_ELEMENTWISE 9     /* nonlinearities, log-softmax, max-change                  */
+#define NGSGD_PROF_PRECOND_MISC 10   /* clears, gamma, B_t, orthogonality check, rescale         */
+#define NGSGD_PROF_INIT 11           /* state initialisation from the first minibatch            */
+#define NGSGD_PROF_CATEGORIES 12
+int ngsgd_profile_enable(int32_t on);
+int ngsgd_profile_read(double* ms_out, int64_t* launches_out, int32_t n_categories);
+
 /* ---- diagnostics -------------------------------------------------------------------------- */
 const char* ngsgd_strerror(int code);
 /* hipError_t value of the most recent failed HIP call on this thread (0 if none). */

@@ -66,6 +66,8 @@ _SIGNATURES = {
     "ngsgd_last_preconditioned": (c_int, [c_void_p, c_int32, c_int32, c_void_p, c_void_p]),
     "ngsgd_last_gradient": (c_int, [c_void_p, c_int32, c_void_p, c_void_p]),
     "ngsgd_last_max_change_scale": (c_int, [c_void_p, c_int32, c_void_p, c_void_p]),
+    "ngsgd_profile_enable": (c_int, [c_int32]),
+    "ngsgd_profile_read": (c_int, [POINTER(c_double), POINTER(c_int64), c_int32]),
     "ngsgd_strerror": (c_char_p, [c_int]),
     "ngsgd_last_hip_error": (c_int, []),
     "ngsgd_version": (c_int, []),
@@ -263,6 +265,23 @@ class Network:
         _check(self.lib.ngsgd_last_max_change_scale(self.handle, layer, _ptr(out), _stream_ptr()),
                "ngsgd_last_max_change_scale")
         return out
+
+
+PROFILE_CATEGORIES = ["gemm_fwd", "gemm_bwd", "gemm_upd", "precond_h", "precond_j", "precond_xhat", "precond_kl",
+                      "precond_small", "precond_wnew", "elementwise", "precond_misc", "init"]
+
+
+def profile_enable(on: bool) -> None:
+    _check(load_library().ngsgd_profile_enable(1 if on else 0), "ngsgd_profile_enable")
+
+
+def profile_read():
+    """{category: (milliseconds, bracketed launch groups)} since the last read."""
+    n = len(PROFILE_CATEGORIES)
+    ms = (c_double * n)()
+    cnt = (c_int64 * n)()
+    _check(load_library().ngsgd_profile_read(ms, cnt, n), "ngsgd_profile_read")
+    return {name: (ms[i], cnt[i]) for i, name in enumerate(PROFILE_CATEGORIES)}
 
 
 def average(networks, reset_preconditioners=True, stream=None):

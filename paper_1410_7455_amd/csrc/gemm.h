@@ -39,6 +39,9 @@ struct GemmProblem {
   int tile_begin;              // first workgroup index of this problem
   float* aux;                  // EPI_SUB_ROWNORM: [tiles_n][M] row-norm partials
   double* sumsq;               // SUMSQ_A: [splits*tiles_m] partial sums of squares of A
+  long long c_split_stride;    // EPI_STORE with splits > 1: split s writes its partial product to C + s*stride
+  const int* gate;             // optional: the problem is skipped unless (*gate & gate_mask) != 0
+  int gate_mask;
 };
 
 struct GemmGroup {
@@ -48,6 +51,30 @@ struct GemmGroup {
 };
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef double doublex4 __attribute__((ext_vector_type(4)));
+
+// Four consecutive 16x16x4 MFMAs on the k values a lane group holds.  The double variant multiplies the fp32
+// operands exactly and accumulates in fp64 (v_mfma_f64_16x16x4_f64, same operand and result layout).
+__device__ __forceinline__ void mfma_k4(floatx4& c, const float4& a, const float4& b) {
+  c = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x, b.x, c, 0, 0, 0);
+  c = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, b.y, c, 0, 0, 0);
+  c = __builtin_amdgcn_mfma_f32_16x16x4f32(a.z, b.z, c, 0, 0, 0);
+  c = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, b.w, c, 0, 0, 0);
+}
+__device__ __forceinline__ void mfma_k4(doublex4& c, const float4& a, const float4& b) {
+  c = __builtin_amdgcn_mfma_f64_16x16x4f64((double)a.x, (double)b.x, c, 0, 0, 0);
+  c = __builtin_amdgcn_mfma_f64_16x16x4f64((double)a.y, (double)b.y, c, 0, 0, 0);
+  c = __builtin_amdgcn_mfma_f64_16x16x4f64((double)a.z, (double)b.z, c, 0, 0, 0);
+  c = __builtin_amdgcn_mfma_f64_16x16x4f64((double)a.w, (double)b.w, c, 0, 0, 0);
+}
+template <bool ACC64>
+struct AccType {
+  using type = floatx4;
+};
+template <>
+struct AccType<true> {
+  using type = doublex4;
+};
 
 // ---- global -> register -> LDS staging ---------------------------------------------------------
 // K-contiguous operand: element (row, k) at base[row*ld + k]; LDS layout [ROWS][BK+4].
@@ -183,8 +210,19 @@ __device__ __forceinline__ float group16_sum(float v) {
 
 // A_KC: A is M x K with K contiguous (else stored K x M).  B_KC: B is N x K with K contiguous
 // (else stored K x N).  The product is always sum_k A(m,k) B(n,k).
-template <int BM, int BN, int BK, int WGM, int WGN, bool A_KC, bool B_KC, int EPI, bool SUMSQ_A>
+//
+// ACC_CHUNK > 0 selects two-level accumulation: the MFMA chain runs over ACC_CHUNK staged K-blocks from a zero
+// accumulator and is then added to a running total with an ordinary (round-to-nearest) fp32 add.  A long MFMA
+// chain adds small products into a large accumulator, and the matrix unit does not round those additions to
+// nearest, so its error grows linearly with K; the two-level form restores sqrt-like growth.
+//
+// ACC64 accumulates in fp64 on the fp64 matrix unit (half the fp32 rate).  The factor update needs it: J, K and
+// L hold nearly parallel rows while the factor is still turning towards the data, and the weak directions then
+// sit in differences that fp32 accumulation wipes out.
+template <int BM, int BN, int BK, int WGM, int WGN, bool A_KC, bool B_KC, int EPI, bool SUMSQ_A, int ACC_CHUNK = 0,
+          bool ACC64 = false>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmGroup g) {
+  using acc_t = typename AccType<ACC64>::type;
   constexpr int NT = WGM * WGN * 64;
   constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int TM = WM / 16, TN = WN / 16;
@@ -207,6 +245,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmGroup g) 
   for (int i = 1; i < g.count; ++i)
     if ((int)blockIdx.x >= g.p[i].tile_begin) pi = i;
   const GemmProblem& P = g.p[pi];
+  if (P.gate != nullptr && ((*P.gate) & P.gate_mask) == 0) return;   // uniform over the workgroup
   int local = blockIdx.x - P.tile_begin;
   const int tn = local % P.tiles_n;
   local /= P.tiles_n;
@@ -220,11 +259,15 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmGroup g) 
   float* const As = lds;                             // two buffers of StageA::LDS_FLOATS
   float* const Bs = lds + 2 * StageA::LDS_FLOATS;    // two buffers of StageB::LDS_FLOATS
 
-  floatx4 acc[TM][TN];
+  acc_t acc[TM][TN];
+  acc_t total[ACC_CHUNK > 0 ? TM : 1][ACC_CHUNK > 0 ? TN : 1];
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < TN; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < TN; ++j) {
+      acc[i][j] = acc_t{0, 0, 0, 0};
+      if (ACC_CHUNK > 0) total[i][j] = acc_t{0, 0, 0, 0};
+    }
 
   StageA sa;
   StageB sb;
@@ -259,11 +302,15 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmGroup g) 
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
+        for (int j = 0; j < TN; ++j) mfma_k4(acc[i][j], af[i], bf[j]);
+    }
+    if (ACC_CHUNK > 0 && ((it + 1) % (ACC_CHUNK > 0 ? ACC_CHUNK : 1) == 0 || !more)) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
         for (int j = 0; j < TN; ++j) {
-          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(af[i].x, bf[j].x, acc[i][j], 0, 0, 0);
-          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(af[i].y, bf[j].y, acc[i][j], 0, 0, 0);
-          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(af[i].z, bf[j].z, acc[i][j], 0, 0, 0);
-          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(af[i].w, bf[j].w, acc[i][j], 0, 0, 0);
+          total[i][j] += acc[i][j];
+          acc[i][j] = acc_t{0, 0, 0, 0};
         }
     }
     if (more) {
@@ -271,6 +318,12 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmGroup g) 
       sb.store(Bs + (cur ^ 1) * StageB::LDS_FLOATS, tid);
     }
     __syncthreads();
+  }
+  if (ACC_CHUNK > 0) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) acc[i][j] = total[i][j];
   }
 
   if (SUMSQ_A) {
@@ -291,7 +344,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmGroup g) 
   for (int i = 0; i < 3; ++i)
     if (P.alpha_dev[i] != nullptr) alpha *= (float)(*P.alpha_dev[i]);
 
-  // accumulator layout of v_mfma_f32_16x16x4_f32: register i of lane l holds (row 4*(l/16)+i, col l%16)
+  // accumulator layout: register r of lane l holds column l%16 and row 4*(l/16)+r for v_mfma_f32_16x16x4_f32,
+  // row 4*r+(l/16) for v_mfma_f64_16x16x4_f64
   if (EPI == EPI_SUB_ROWNORM) {
     float* C = static_cast<float*>(P.C);
     float* rowsum = lds;  // [WGN][BM], operand tiles are no longer needed
@@ -299,7 +353,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmGroup g) 
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        const int lrow = wm * WM + i * 16 + 4 * g4 + r;
+        const int lrow = wm * WM + i * 16 + (ACC64 ? 4 * r + g4 : 4 * g4 + r);
         const int row = m0 + lrow;
         float sq = 0.f;
 #pragma unroll
@@ -307,7 +361,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmGroup g) 
           const int col = n0 + wn * WN + j * 16 + r16;
           if (row < M && col < N) {
             float* c = C + (size_t)row * P.ldc + col;
-            const float v = *c - acc[i][j][r];
+            const float v = *c - (float)acc[i][j][r];
             *c = v;
             sq += v * v;
           }
@@ -336,16 +390,17 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmGroup g) 
       const int col = n0 + wn * WN + j * 16 + r16;
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        const int row = m0 + wm * WM + i * 16 + 4 * g4 + r;
+        const int row = m0 + wm * WM + i * 16 + (ACC64 ? 4 * r + g4 : 4 * g4 + r);
         if (row < M && col < N) {
-          const float v = alpha * acc[i][j][r];
+          const float v = ACC64 ? (float)((double)alpha * (double)acc[i][j][r]) : alpha * (float)acc[i][j][r];
           if (EPI == EPI_STORE) {
-            float* c = static_cast<float*>(P.C) + (size_t)row * P.ldc + col;
+            float* c = static_cast<float*>(P.C) + (size_t)split * P.c_split_stride + (size_t)row * P.ldc + col;
             *c = (P.beta != 0.f) ? v + P.beta * (*c) : v;
           } else if (EPI == EPI_ATOMIC_F32) {
             unsafeAtomicAdd(static_cast<float*>(P.C) + (size_t)row * P.ldc + col, v);
           } else if (EPI == EPI_ATOMIC_F64) {
-            unsafeAtomicAdd(static_cast<double*>(P.C) + (size_t)row * P.ldc + col, (double)v);
+            unsafeAtomicAdd(static_cast<double*>(P.C) + (size_t)row * P.ldc + col,
+                            ACC64 ? (double)alpha * (double)acc[i][j][r] : (double)v);
           }
         }
       }
@@ -364,7 +419,10 @@ struct GemmDesc {  // what a caller states; tiling is filled in by the launcher
   const double* alpha_dev[3] = {nullptr, nullptr, nullptr};
   float* aux = nullptr;
   double* sumsq = nullptr;
-  int splits = 1;  // requested split-K factor (atomic epilogues only)
+  int splits = 1;  // requested split-K factor (atomic epilogues, or EPI_STORE with c_split_stride)
+  long long c_split_stride = 0;
+  const int* gate = nullptr;
+  int gate_mask = 0;
 };
 
 template <int BM, int BN, int BK>
@@ -375,6 +433,8 @@ inline void plan_tiles(const GemmDesc& d, GemmProblem& p) {
   p.alpha = d.alpha; p.beta = d.beta;
   for (int i = 0; i < 3; ++i) p.alpha_dev[i] = d.alpha_dev[i];
   p.aux = d.aux; p.sumsq = d.sumsq;
+  p.c_split_stride = d.c_split_stride;
+  p.gate = d.gate; p.gate_mask = d.gate_mask;
   p.tiles_m = (d.M + BM - 1) / BM;
   p.tiles_n = (d.N + BN - 1) / BN;
   const int ksteps = (d.K + BK - 1) / BK;
@@ -385,7 +445,8 @@ inline void plan_tiles(const GemmDesc& d, GemmProblem& p) {
   p.splits = ksteps > 0 ? (ksteps + steps_per - 1) / steps_per : 1;
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, bool A_KC, bool B_KC, int EPI, bool SUMSQ_A>
+template <int BM, int BN, int BK, int WGM, int WGN, bool A_KC, bool B_KC, int EPI, bool SUMSQ_A, int ACC_CHUNK = 0,
+          bool ACC64 = false>
 inline hipError_t launch_gemm_group(const GemmDesc* descs, int count, hipStream_t stream) {
   int done = 0;
   while (done < count) {
@@ -400,7 +461,8 @@ inline hipError_t launch_gemm_group(const GemmDesc* descs, int count, hipStream_
     }
     grp.total_tiles = total;
     if (total > 0) {
-      hipLaunchKernelGGL((gemm_kernel<BM, BN, BK, WGM, WGN, A_KC, B_KC, EPI, SUMSQ_A>), dim3(total),
+      hipLaunchKernelGGL((gemm_kernel<BM, BN, BK, WGM, WGN, A_KC, B_KC, EPI, SUMSQ_A, ACC_CHUNK, ACC64>),
+                         dim3(total),
                          dim3(WGM * WGN * 64), 0, stream, grp);
       hipError_t e = hipGetLastError();
       if (e != hipSuccess) return e;
@@ -408,6 +470,14 @@ inline hipError_t launch_gemm_group(const GemmDesc* descs, int count, hipStream_
     done += n;
   }
   return hipSuccess;
+}
+
+// number of K splits a problem is actually planned with
+template <int BM, int BN, int BK>
+inline int planned_splits(const GemmDesc& d) {
+  GemmProblem p;
+  plan_tiles<BM, BN, BK>(d, p);
+  return p.splits;
 }
 
 // number of sumsq partials the SUMSQ_A variant writes for a problem planned with these tiles

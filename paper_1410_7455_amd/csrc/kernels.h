@@ -86,13 +86,22 @@ __global__ void tanh_forward_kernel(const float* __restrict__ A, int lda, float*
     Y[(size_t)row * ldy + c] = c < D ? tanhf(A[(size_t)row * lda + c]) : (c == D ? 1.f : 0.f);
 }
 
+// The derivative w.r.t. a layer's input arrives as n_slabs partial products (split-K slabs of the backward
+// GEMM, slab_stride floats apart) that are summed here in a fixed order.
+__device__ __forceinline__ float slab_sum(const float* __restrict__ p, int n_slabs, size_t slab_stride) {
+  float v = p[0];
+  for (int s = 1; s < n_slabs; ++s) v += p[(size_t)s * slab_stride];
+  return v;
+}
+
 // O[n][j] = dY[n][j] * (1 - Y[n][j]^2)
-__global__ void tanh_backward_kernel(const float* __restrict__ dY, int ldd, const float* __restrict__ Y, int ldy,
-                                     float* __restrict__ O, int ldo, int N, int D) {
+__global__ void tanh_backward_kernel(const float* __restrict__ dY, int ldd, int n_slabs, size_t slab_stride,
+                                     const float* __restrict__ Y, int ldy, float* __restrict__ O, int ldo, int N,
+                                     int D) {
   const int row = blockIdx.y;
   for (int c = blockIdx.x * blockDim.x + threadIdx.x; c < D; c += gridDim.x * blockDim.x) {
     const float y = Y[(size_t)row * ldy + c];
-    O[(size_t)row * ldo + c] = dY[(size_t)row * ldd + c] * (1.f - y * y);
+    O[(size_t)row * ldo + c] = slab_sum(dY + (size_t)row * ldd + c, n_slabs, slab_stride) * (1.f - y * y);
   }
 }
 
@@ -134,7 +143,8 @@ __global__ __launch_bounds__(256) void pnorm_forward_kernel(const float* __restr
 // Backward through (renorm o p-norm), one wavefront per row, in place over the affine outputs:
 //   AO[n][Gj+k] <- dy_j * a_{Gj+k} / y_j   (0 where y_j = 0)
 // with dy = dYn, y = Yn without renorm; with renorm  y = Yn*sigma, dy = (dYn - Yn * mean_j(dYn_j Yn_j)) / sigma.
-__global__ __launch_bounds__(256) void pnorm_backward_kernel(const float* __restrict__ dYn, int ldd,
+__global__ __launch_bounds__(256) void pnorm_backward_kernel(const float* __restrict__ dYn, int ldd, int n_slabs,
+                                                             size_t slab_stride,
                                                              const float* __restrict__ Yn, int ldy,
                                                              const float* __restrict__ sigma,
                                                              float* __restrict__ AO, int lda, int N, int groups,
@@ -148,7 +158,7 @@ __global__ __launch_bounds__(256) void pnorm_backward_kernel(const float* __rest
   float proj = 0.f, sg = 1.f;
   if (renorm) {
     float dot = 0.f;
-    for (int j = lane; j < groups; j += 64) dot += dy[j] * yn[j];
+    for (int j = lane; j < groups; j += 64) dot += slab_sum(dy + j, n_slabs, slab_stride) * yn[j];
     dot = wave_sum(dot);
     sg = sigma[row];
     proj = sg > kRenormFloor ? dot / (float)groups : 0.f;
@@ -156,7 +166,7 @@ __global__ __launch_bounds__(256) void pnorm_backward_kernel(const float* __rest
   const float inv_sg = 1.f / sg;
   for (int j = lane; j < groups; j += 64) {
     const float ynj = yn[j];
-    const float d = (dy[j] - ynj * proj) * inv_sg;
+    const float d = (slab_sum(dy + j, n_slabs, slab_stride) - ynj * proj) * inv_sg;
     const float yj = ynj * sg;
     const float f = yj > 0.f ? d / yj : 0.f;
     for (int k = 0; k < G; ++k) ao[j * G + k] *= f;

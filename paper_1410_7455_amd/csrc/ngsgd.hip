@@ -56,6 +56,41 @@ struct Carver {
   }
 };
 
+// ---- optional per-category kernel timing with HIP events on the launch stream ----------------------
+struct Profiler {
+  bool on = false;
+  std::vector<hipEvent_t> pool;
+  struct Rec {
+    int cat;
+    size_t e0;
+  };
+  std::vector<Rec> recs;
+  size_t used = 0;
+};
+Profiler g_prof;
+constexpr size_t kProfMaxEvents = 1 << 16;
+
+struct ProfScope {
+  hipStream_t s;
+  bool active = false;
+  size_t e0 = 0;
+  ProfScope(int cat, hipStream_t stream) : s(stream) {
+    if (!g_prof.on || g_prof.used + 2 > kProfMaxEvents) return;
+    while (g_prof.pool.size() < g_prof.used + 2) {
+      hipEvent_t e;
+      if (hipEventCreate(&e) != hipSuccess) return;
+      g_prof.pool.push_back(e);
+    }
+    e0 = g_prof.used;
+    g_prof.used += 2;
+    g_prof.recs.push_back({cat, e0});
+    active = hipEventRecord(g_prof.pool[e0], s) == hipSuccess;
+  }
+  ~ProfScope() {
+    if (active) (void)hipEventRecord(g_prof.pool[e0 + 1], s);
+  }
+};
+
 constexpr int kSumsqMax = 1024;   // partial sums of squares per preconditioner call
 constexpr int kTargetBlocks = 512;
 
@@ -72,7 +107,7 @@ struct ngsgd_precond {
   int ldw = 0;   // leading dimension of W and J
   int ldh = 0;   // leading dimension of H and A_t (= rank class)
   PrecondScalars* st = nullptr;
-  float* zero_region = nullptr;   // [H | J | K | L], cleared before each call
+  float* zero_region = nullptr;   // [H | K | L], cleared before each call
   size_t zero_floats_all = 0;
   float* H = nullptr;
   float* J = nullptr;
@@ -102,17 +137,15 @@ void precond_layout(ngsgd_precond& p, Carver& c) {
   p.st = c.take<PrecondScalars>(1);
   p.prow = c.take<double>(NB);
   if (R == 0) return;
-  const size_t h_floats = (size_t)NB * p.ldh, j_floats = (size_t)R * p.ldw, kl_floats = (size_t)4 * R * R;
-  p.zero_floats_all = h_floats + j_floats + kl_floats;
-  p.zero_region = c.take<float>(p.zero_floats_all + 8);
+  const size_t h_floats = (size_t)NB * p.ldh, kl_floats = (size_t)4 * R * R;   // ldh is a multiple of 16
+  p.zero_floats_all = h_floats + kl_floats;
+  p.zero_region = c.take<float>(p.zero_floats_all);
   if (p.zero_region) {
     p.H = p.zero_region;
-    p.J = p.H + h_floats;
-    float* kl = p.J + j_floats;
-    kl = reinterpret_cast<float*>(align_up(reinterpret_cast<uintptr_t>(kl), 8));
-    p.K = reinterpret_cast<double*>(kl);
+    p.K = reinterpret_cast<double*>(p.H + h_floats);
     p.L = p.K + (size_t)R * R;
   }
+  p.J = c.take<float>((size_t)R * p.ldw);
   p.W = c.take<float>((size_t)R * p.ldw);
   p.At = c.take<float>((size_t)R * p.ldh);
   p.max_col_tiles = (D + 63) / 64;
@@ -179,21 +212,29 @@ inline int choose_splits(int tiles, int ksteps) {
 constexpr int BK = 16;
 
 enum LayerGemm { GEMM_FWD, GEMM_BWD, GEMM_UPD };
+constexpr int kBwdAccChunk = 8;     // K-blocks per MFMA chain in the backward GEMM
+constexpr int kMaxBwdSplits = 8;    // split-K slabs of the backward GEMM, summed by the nonlinearity's backward kernel
+
+inline bool layer_gemm_is_big(const GemmDesc* d, int n) {
+  long long big_tiles = 0;
+  for (int i = 0; i < n; ++i) big_tiles += (long long)((d[i].M + 127) / 128) * ((d[i].N + 127) / 128);
+  return big_tiles >= 400;
+}
 
 // layer GEMMs: 128x128 tiles when they already fill the chip, 64x64 otherwise
 int launch_layer_gemms(LayerGemm kind, const GemmDesc* d, int n, hipStream_t s) {
-  long long big_tiles = 0;
-  for (int i = 0; i < n; ++i) big_tiles += (long long)((d[i].M + 127) / 128) * ((d[i].N + 127) / 128);
-  const bool big = big_tiles >= 400;
+  ProfScope prof(kind == GEMM_FWD ? NGSGD_PROF_GEMM_FWD : (kind == GEMM_BWD ? NGSGD_PROF_GEMM_BWD : NGSGD_PROF_GEMM_UPD),
+                 s);
+  const bool big = layer_gemm_is_big(d, n);
   hipError_t e = hipSuccess;
   switch (kind) {
     case GEMM_FWD:
       e = big ? launch_gemm_group<128, 128, BK, 2, 2, true, true, EPI_STORE, false>(d, n, s)
               : launch_gemm_group<64, 64, BK, 2, 2, true, true, EPI_STORE, false>(d, n, s);
       break;
-    case GEMM_BWD:
-      e = big ? launch_gemm_group<128, 128, BK, 2, 2, true, false, EPI_STORE, false>(d, n, s)
-              : launch_gemm_group<64, 64, BK, 2, 2, true, false, EPI_STORE, false>(d, n, s);
+    case GEMM_BWD:   // long K (the layer's output dimension): two-level accumulation
+      e = big ? launch_gemm_group<128, 128, BK, 2, 2, true, false, EPI_STORE, false, kBwdAccChunk>(d, n, s)
+              : launch_gemm_group<64, 64, BK, 2, 2, true, false, EPI_STORE, false, kBwdAccChunk>(d, n, s);
       break;
     case GEMM_UPD:
       e = big ? launch_gemm_group<128, 128, BK, 2, 2, false, false, EPI_STORE, false>(d, n, s)
@@ -209,10 +250,10 @@ template <int RC>
 hipError_t launch_h(const GemmDesc* d, int n, hipStream_t s) {
   return launch_gemm_group<64, RC, BK, 4, 1, true, true, EPI_ATOMIC_F32, true>(d, n, s);
 }
-// J = H^T X (split over the rows, float atomics)
+// J = H^T X, accumulated in fp64 and rounded once to fp32; narrow column tiles instead of a split over the rows
 template <int RC>
 hipError_t launch_j(const GemmDesc* d, int n, hipStream_t s) {
-  return launch_gemm_group<RC, 128, BK, 1, 4, false, false, EPI_ATOMIC_F32, false>(d, n, s);
+  return launch_gemm_group<RC, 32, BK, 1, 2, false, false, EPI_STORE, false, 0, true>(d, n, s);
 }
 // W_{t+1} = A_t B_t
 template <int RC>
@@ -235,6 +276,7 @@ struct PrecondCall {
 };
 
 int run_init(const std::vector<PrecondCall>& calls, hipStream_t s) {
+  ProfScope prof(NGSGD_PROF_INIT, s);
   size_t done = 0;
   while (done < calls.size()) {
     InitGroup g;
@@ -324,10 +366,13 @@ int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStr
   if (!to_init.empty()) NG_TRY(run_init(to_init, s));
 
   // clear the accumulation buffers
+  {
+    ProfScope prof(NGSGD_PROF_PRECOND_MISC, s);
   for (auto& c : full) {
     ngsgd_precond& p = *c.p;
     const bool upd = p.t < p.always_update_first || p.t % p.update_period == 0;
-    NG_TRY(fill_zero(p.zero_region, upd ? p.zero_floats_all + 8 : (size_t)c.N * p.ldh, s));
+    NG_TRY(fill_zero(p.zero_region, upd ? p.zero_floats_all : (size_t)c.N * p.ldh, s));
+  }
   }
   // H = X W^T   (eq. ht), tr(X X^T) partials
   for (int rc : {32, 80, 96}) {
@@ -348,6 +393,7 @@ int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStr
       d.push_back(g);
     }
     if (d.empty()) continue;
+    ProfScope prof(NGSGD_PROF_PRECOND_H, s);
     HIP_TRY(by_rank_class(rc, [&] { return launch_h<32>(d.data(), (int)d.size(), s); },
                           [&] { return launch_h<80>(d.data(), (int)d.size(), s); },
                           [&] { return launch_h<96>(d.data(), (int)d.size(), s); }));
@@ -363,10 +409,10 @@ int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStr
       g.B = c.M; g.ldb = c.ld;
       g.C = p.J; g.ldc = p.ldw;
       g.M = p.rank; g.N = p.dim; g.K = c.N;
-      g.splits = choose_splits((p.dim + 127) / 128, (c.N + BK - 1) / BK);
       d.push_back(g);
     }
     if (d.empty()) continue;
+    ProfScope prof(NGSGD_PROF_PRECOND_J, s);
     HIP_TRY(by_rank_class(rc, [&] { return launch_j<32>(d.data(), (int)d.size(), s); },
                           [&] { return launch_j<80>(d.data(), (int)d.size(), s); },
                           [&] { return launch_j<96>(d.data(), (int)d.size(), s); }));
@@ -384,10 +430,12 @@ int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStr
       g.aux = p.rownorm_part;
       d.push_back(g);
     }
+    ProfScope prof(NGSGD_PROF_PRECOND_XHAT, s);
     HIP_TRY((launch_gemm_group<64, 64, BK, 2, 2, true, false, EPI_SUB_ROWNORM, false>(d.data(), (int)d.size(), s)));
   }
   // gamma_t, tr(X X^T), tr(Xhat Xhat^T)
   for (size_t done = 0; done < full.size();) {
+    ProfScope prof(NGSGD_PROF_PRECOND_MISC, s);
     FinishGroup g;
     const int n = (int)std::min<size_t>(kMaxInstances, full.size() - done);
     g.count = n;
@@ -418,6 +466,7 @@ int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStr
     done += n;
   }
   if (scale_output) {
+    ProfScope prof(NGSGD_PROF_PRECOND_MISC, s);
     for (auto& c : full) {
       ngsgd_precond& p = *c.p;
       hipLaunchKernelGGL(scale_rows_kernel, dim3((p.dim + 1023) / 1024, c.N), dim3(256), 0, s, c.M, c.ld, c.N, p.dim,
@@ -446,14 +495,22 @@ int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStr
       h.splits = choose_splits(tiles * (int)to_update.size(), (c.N + BK - 1) / BK);
       dl.push_back(h);
     }
-    HIP_TRY((launch_gemm_group<64, 64, BK, 2, 2, true, true, EPI_ATOMIC_F64, false>(dk.data(), (int)dk.size(), s)));
-    HIP_TRY((launch_gemm_group<64, 64, BK, 2, 2, false, false, EPI_ATOMIC_F64, false>(dl.data(), (int)dl.size(), s)));
+    {
+      ProfScope prof(NGSGD_PROF_PRECOND_KL, s);
+      HIP_TRY((launch_gemm_group<64, 64, BK, 2, 2, true, true, EPI_ATOMIC_F64, false, 0, true>(dk.data(),
+                                                                                             (int)dk.size(), s)));
+      HIP_TRY((launch_gemm_group<64, 64, BK, 2, 2, false, false, EPI_ATOMIC_F64, false, 0, true>(dl.data(),
+                                                                                               (int)dl.size(), s)));
+    }
     // B_t over J (needs D_t, rho_t: before the R x R update)
-    for (auto& c : to_update) {
-      ngsgd_precond& p = *c.p;
-      hipLaunchKernelGGL(make_bt_kernel, dim3((p.dim + 1023) / 1024, p.rank), dim3(256), 0, s, p.J, p.W, p.ldw, p.dim,
-                         p.st, c.N, p.num_samples_history);
-      LAUNCH_CHECK();
+    {
+      ProfScope prof(NGSGD_PROF_PRECOND_MISC, s);
+      for (auto& c : to_update) {
+        ngsgd_precond& p = *c.p;
+        hipLaunchKernelGGL(make_bt_kernel, dim3((p.dim + 1023) / 1024, p.rank), dim3(256), 0, s, p.J, p.W, p.ldw,
+                           p.dim, p.st, c.N, p.num_samples_history);
+        LAUNCH_CHECK();
+      }
     }
     // Z_t, eigen-decomposition, rho_{t+1}, D_{t+1}, A_t
     for (size_t done = 0; done < to_update.size();) {
@@ -473,14 +530,17 @@ int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStr
         a.st = p.st; a.K = p.K; a.L = p.L; a.At = p.At; a.ldat = p.ldh;
         a.R = p.rank; a.D = p.dim; a.N = c.N;
         OrthArgs& o = og.a[n];
-        o.st = p.st; o.W = p.W; o.ld = p.ldw; o.R = p.rank; o.D = p.dim;
+        o.st = p.st; o.G = p.K; o.W = p.W; o.ld = p.ldw; o.R = p.rank; o.D = p.dim;
         r_max = std::max(r_max, p.rank);
         ++n;
       }
       g.count = og.count = n;
       const size_t dyn = (size_t)2 * r_max * (r_max | 1) * sizeof(double);
-      hipLaunchKernelGGL(small_update_kernel, dim3(n), dim3(kSmallThreads), dyn, s, g);
-      LAUNCH_CHECK();
+      {
+        ProfScope prof(NGSGD_PROF_PRECOND_SMALL, s);
+        hipLaunchKernelGGL(small_update_kernel, dim3(n), dim3(kSmallThreads), dyn, s, g);
+        LAUNCH_CHECK();
+      }
       // W_{t+1} = A_t B_t   (eq. wt1)
       for (int rc : {32, 80, 96}) {
         std::vector<GemmDesc> d;
@@ -495,12 +555,34 @@ int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStr
           d.push_back(w);
         }
         if (d.empty()) continue;
+        ProfScope prof(NGSGD_PROF_PRECOND_WNEW, s);
         HIP_TRY(by_rank_class(rc, [&] { return launch_wnew<32>(d.data(), (int)d.size(), s); },
                               [&] { return launch_wnew<80>(d.data(), (int)d.size(), s); },
                               [&] { return launch_wnew<96>(d.data(), (int)d.size(), s); }));
       }
-      hipLaunchKernelGGL(orth_fix_kernel, dim3(n), dim3(kSmallThreads), dyn, s, og);
-      LAUNCH_CHECK();
+      {
+        // App. B.3.1: W W^T of the new factor, accumulated into K (cleared by the R x R kernel) only for the
+        // instances whose update asked for the check, then the check itself and, if needed, the Cholesky fix
+        ProfScope prof(NGSGD_PROF_PRECOND_MISC, s);
+        std::vector<GemmDesc> dg;
+        for (int i = 0; i < n; ++i) {
+          ngsgd_precond& p = *to_update[done + i].p;
+          GemmDesc w;
+          w.A = p.W; w.lda = p.ldw;
+          w.B = p.W; w.ldb = p.ldw;
+          w.C = p.K; w.ldc = p.rank;
+          w.M = p.rank; w.N = p.rank; w.K = p.dim;
+          const int tiles = ((p.rank + 63) / 64) * ((p.rank + 63) / 64);
+          w.splits = choose_splits(tiles * n, (p.dim + BK - 1) / BK);
+          w.gate = &p.st->flags;
+          w.gate_mask = kFlagOrthCheck;
+          dg.push_back(w);
+        }
+        HIP_TRY((launch_gemm_group<64, 64, BK, 2, 2, true, true, EPI_ATOMIC_F64, false, 0, true>(dg.data(),
+                                                                                               (int)dg.size(), s)));
+        hipLaunchKernelGGL(orth_fix_kernel, dim3(n), dim3(kSmallThreads), dyn, s, og);
+        LAUNCH_CHECK();
+      }
       done += n;
     }
   }
@@ -706,7 +788,7 @@ void net_layout(ngsgd_net& net, const ngsgd_config* cfg, Carver& c) {
     off += (size_t)L.dout * L.ldw;
   }
   net.lddx = max_ldx;
-  net.dX = c.take<float>((size_t)net.max_batch * net.lddx);
+  net.dX = c.take<float>((size_t)kMaxBwdSplits * net.max_batch * net.lddx);
   net.rowobj = c.take<double>(net.max_batch);
   net.logprob = c.take<double>(1);
   for (auto& L : net.layers) {
@@ -806,9 +888,12 @@ extern "C" int ngsgd_step(ngsgd_net* net, const float* dev_x, const int32_t* dev
   }
 
   // forward (Sec. 2): A_l = [X_l, 1] W_l^T, nonlinearity, log-softmax
-  hipLaunchKernelGGL(copy_append_ones_kernel, dim3((Ls[0].ldx + 255) / 256, N), dim3(256), 0, s, dev_x, Ls[0].din,
-                     Ls[0].Xin, Ls[0].ldx, N, Ls[0].din);
-  LAUNCH_CHECK();
+  {
+    ProfScope prof(NGSGD_PROF_ELEMENTWISE, s);
+    hipLaunchKernelGGL(copy_append_ones_kernel, dim3((Ls[0].ldx + 255) / 256, N), dim3(256), 0, s, dev_x, Ls[0].din,
+                       Ls[0].Xin, Ls[0].ldx, N, Ls[0].din);
+    LAUNCH_CHECK();
+  }
   for (int l = 0; l < nl; ++l) {
     ngsgd_layer& L = Ls[l];
     GemmDesc g;
@@ -818,6 +903,7 @@ extern "C" int ngsgd_step(ngsgd_net* net, const float* dev_x, const int32_t* dev
     g.M = N; g.N = L.dout; g.K = L.in1;
     NG_TRY(launch_layer_gemms(GEMM_FWD, &g, 1, s));
     if (l < nl - 1) {
+      ProfScope prof(NGSGD_PROF_ELEMENTWISE, s);
       ngsgd_layer& Nx = Ls[l + 1];
       if (L.nonlin == NGSGD_TANH) {
         hipLaunchKernelGGL(tanh_forward_kernel, dim3((Nx.ldx + 1023) / 1024, N), dim3(256), 0, s, L.A, L.lda, Nx.Xin,
@@ -830,12 +916,15 @@ extern "C" int ngsgd_step(ngsgd_net* net, const float* dev_x, const int32_t* dev
     }
   }
   ngsgd_layer& last = Ls[nl - 1];
+  {
+  ProfScope prof(NGSGD_PROF_ELEMENTWISE, s);
   hipLaunchKernelGGL(softmax_xent_kernel, dim3(N), dim3(256), 0, s, last.A, last.lda, dev_labels, N, last.dout,
                      net->rowobj);
   LAUNCH_CHECK();
   hipLaunchKernelGGL(sum_double_kernel, dim3(1), dim3(256), 0, s, net->rowobj, N,
                      dev_logprob_sum != nullptr ? dev_logprob_sum : net->logprob);
   LAUNCH_CHECK();
+  }
 
   // backward on the unmodified derivatives (App. C.3, last paragraph)
   for (int l = nl - 1; l >= 1; --l) {
@@ -846,13 +935,26 @@ extern "C" int ngsgd_step(ngsgd_net* net, const float* dev_x, const int32_t* dev
     g.B = L.W; g.ldb = L.ldw;           // W_l as dout x din (bias column dropped)
     g.C = net->dX; g.ldc = net->lddx;
     g.M = N; g.N = L.din; g.K = L.dout;
+    // few output tiles and a long K: split K into slabs that the nonlinearity's backward kernel sums
+    const size_t slab = (size_t)net->max_batch * net->lddx;
+    g.c_split_stride = (long long)slab;
+    int n_slabs;
+    if (layer_gemm_is_big(&g, 1)) {
+      g.splits = 1;
+      n_slabs = 1;
+    } else {
+      const int tiles = ((N + 63) / 64) * ((L.din + 63) / 64);
+      g.splits = std::min(kMaxBwdSplits, choose_splits(tiles, (L.dout + BK - 1) / BK));
+      n_slabs = planned_splits<64, 64, BK>(g);
+    }
     NG_TRY(launch_layer_gemms(GEMM_BWD, &g, 1, s));
+    ProfScope prof(NGSGD_PROF_ELEMENTWISE, s);
     if (P.nonlin == NGSGD_TANH) {
       hipLaunchKernelGGL(tanh_backward_kernel, dim3((P.dout + 1023) / 1024, N), dim3(256), 0, s, net->dX, net->lddx,
-                         L.Xin, L.ldx, P.A, P.lda, N, P.dout);
+                         n_slabs, slab, L.Xin, L.ldx, P.A, P.lda, N, P.dout);
     } else {
-      hipLaunchKernelGGL(pnorm_backward_kernel, dim3((N + 3) / 4), dim3(256), 0, s, net->dX, net->lddx, L.Xin, L.ldx,
-                         P.sigma, P.A, P.lda, N, P.groups, net->pnorm_group, net->renorm);
+      hipLaunchKernelGGL(pnorm_backward_kernel, dim3((N + 3) / 4), dim3(256), 0, s, net->dX, net->lddx, n_slabs, slab,
+                         L.Xin, L.ldx, P.sigma, P.A, P.lda, N, P.groups, net->pnorm_group, net->renorm);
     }
     LAUNCH_CHECK();
   }
@@ -881,6 +983,7 @@ extern "C" int ngsgd_step(ngsgd_net* net, const float* dev_x, const int32_t* dev
       a.N = N;
     }
     if (net->max_change_per_sample > 0.0) {
+      ProfScope prof(NGSGD_PROF_ELEMENTWISE, s);
       hipLaunchKernelGGL(max_change_kernel, dim3(nl), dim3(256), 0, s, g);
       LAUNCH_CHECK();
     }
@@ -974,6 +1077,31 @@ extern "C" const char* ngsgd_strerror(int code) {
     case NGSGD_EUNSUPPORTED: return "unsupported";
     default: return "unknown error";
   }
+}
+
+extern "C" int ngsgd_profile_enable(int32_t on) {
+  g_prof.on = on != 0;
+  g_prof.used = 0;
+  g_prof.recs.clear();
+  return NGSGD_OK;
+}
+
+extern "C" int ngsgd_profile_read(double* ms_out, int64_t* launches_out, int32_t n_categories) {
+  if (ms_out == nullptr || launches_out == nullptr || n_categories < NGSGD_PROF_CATEGORIES) return NGSGD_EINVAL;
+  for (int i = 0; i < n_categories; ++i) {
+    ms_out[i] = 0.0;
+    launches_out[i] = 0;
+  }
+  for (const auto& r : g_prof.recs) {
+    HIP_TRY(hipEventSynchronize(g_prof.pool[r.e0 + 1]));
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, g_prof.pool[r.e0], g_prof.pool[r.e0 + 1]));
+    ms_out[r.cat] += (double)ms;
+    launches_out[r.cat] += 1;
+  }
+  g_prof.used = 0;
+  g_prof.recs.clear();
+  return NGSGD_OK;
 }
 
 extern "C" int ngsgd_last_hip_error(void) { return g_last_hip_error; }

@@ -16,13 +16,13 @@ namespace ngsgd {
 
 constexpr int kSmallThreads = 1024;
 constexpr int kMaxSweeps = 30;
-constexpr double kJacobiTol = 1.0e-14;       // off-diagonal Frobenius norm relative to the whole
+constexpr double kJacobiTol = 1.0e-13;       // a pair is left alone once |z_pq| <= tol * sqrt(z_pp z_qq)
 constexpr double kOrthoCondLimit = 1.0e6;    // App. B.3.1
 constexpr double kOrthoTolerance = 1.0e-3;   // App. B.3.1
 
 struct SmallArgs {
   PrecondScalars* st;
-  const double* K;   // R x R, J J^T
+  double* K;         // R x R, J J^T; cleared on exit (the orthogonality check accumulates W W^T into it)
   const double* L;   // R x R, H^T H
   float* At;         // out: A_t (eq. wt1), R x ldat
   int ldat;
@@ -34,17 +34,18 @@ struct SmallGroup {
   SmallArgs a[kMaxInstances];
 };
 
-// Rotation that diagonalises [[app, apq], [apq, aqq]] as J^T A J with J = [[c, s], [-s, c]].
-__device__ __forceinline__ void sym_schur2(double app, double aqq, double apq, double& c, double& s) {
-  if (apq == 0.0 || fabs(apq) <= 1.0e-300) {
-    c = 1.0;
-    s = 0.0;
-    return;
-  }
+// Rotation that diagonalises [[app, apq], [apq, aqq]] as J^T A J with J = [[c, s], [-s, c]].  Returns false (and
+// the identity) when the off-diagonal entry is already negligible relative to the diagonal pair; that relative
+// test is what gives small eigenvalues of a graded positive definite matrix their relative accuracy.
+__device__ __forceinline__ bool sym_schur2(double app, double aqq, double apq, double& c, double& s) {
+  c = 1.0;
+  s = 0.0;
+  if (!(fabs(apq) > kJacobiTol * sqrt(fabs(app * aqq))) || fabs(apq) <= 1.0e-300) return false;
   const double tau = (aqq - app) / (2.0 * apq);
   const double t = (tau >= 0.0 ? 1.0 : -1.0) / (fabs(tau) + sqrt(1.0 + tau * tau));
   c = 1.0 / sqrt(1.0 + t * t);
   s = t * c;
+  return true;
 }
 
 // Round-robin pairing of m (even) players: in round r, pair k is (m-1, r) for k = 0 and
@@ -72,6 +73,7 @@ __global__ __launch_bounds__(kSmallThreads) void small_update_kernel(const Small
   __shared__ int s_p[kMaxRank / 2 + 1], s_q[kMaxRank / 2 + 1], s_perm[kMaxRank];
   __shared__ double s_scal[8];
   __shared__ int s_flag[2];
+  __shared__ int s_rotations;
 
   const SmallArgs& a = g.a[blockIdx.x];
   const int R = a.R, D = a.D, N = a.N;
@@ -113,31 +115,20 @@ __global__ __launch_bounds__(kSmallThreads) void small_update_kernel(const Small
   }
   __syncthreads();
 
-  // cyclic Jacobi, Z = U C U^T
+  // cyclic Jacobi, Z = U C U^T; a sweep in which no pair needed a rotation ends the iteration
   const int m = (R + 1) & ~1;
   const int half = m / 2;
   int sweeps = 0;
   bool converged = false;
   for (; sweeps < kMaxSweeps; ++sweeps) {
-    double off = 0.0, tot = 0.0;
-    for (int idx = tid; idx < R * R; idx += nt) {
-      const int i = idx / R, j = idx % R;
-      const double v = Z[i * Rs + j];
-      tot += v * v;
-      if (i != j) off += v * v;
-    }
-    off = block_sum(off, scratch);
-    tot = block_sum(tot, scratch);
-    if (!(off > kJacobiTol * kJacobiTol * tot)) {   // also leaves on NaN
-      converged = true;
-      break;
-    }
+    if (tid == 0) s_rotations = 0;
+    __syncthreads();
     for (int r = 0; r < m - 1; ++r) {
       if (tid < half) {
         int p, q;
         round_robin_pair(m, r, tid, p, q);
         double c = 1.0, s = 0.0;
-        if (q < R) sym_schur2(Z[p * Rs + p], Z[q * Rs + q], Z[p * Rs + q], c, s);
+        if (q < R && sym_schur2(Z[p * Rs + p], Z[q * Rs + q], Z[p * Rs + q], c, s)) atomicAdd(&s_rotations, 1);
         s_p[tid] = p;
         s_q[tid] = q;
         s_cs[tid] = c;
@@ -187,6 +178,12 @@ __global__ __launch_bounds__(kSmallThreads) void small_update_kernel(const Small
       }
       __syncthreads();
     }
+    if (s_rotations == 0) {   // same value for every thread: read after the round's closing barrier
+      converged = true;
+      ++sweeps;
+      break;
+    }
+    __syncthreads();          // everyone has read the counter before it is cleared again
   }
 
   // eigenvalues, floor (after eq. zt:eig:repeat), decreasing order
@@ -256,12 +253,14 @@ __global__ __launch_bounds__(kSmallThreads) void small_update_kernel(const Small
     }
     a.At[(size_t)k * a.ldat + j] = v;
   }
+  for (int idx = tid; idx < R * R; idx += nt) a.K[idx] = 0.0;
 }
 
 // App. B.3.1 on the new factor: O = E^{-1/2} (W W^T) E^{-1/2}; if any entry is off the identity by more than
 // 1e-3, W <- E^{1/2} L^{-1} E^{-1/2} W with O = L L^T.  Runs only when the update asked for the check.
 struct OrthArgs {
   PrecondScalars* st;
+  const double* G;   // R x R, W W^T of the new factor (accumulated only when the check was requested)
   float* W;
   int ld;
   int R, D;
@@ -282,15 +281,12 @@ __global__ __launch_bounds__(kSmallThreads) void orth_fix_kernel(const OrthGroup
   const int Rs = R | 1;
   double* O = dyn;                    // R x Rs, becomes L
   double* X = dyn + (size_t)R * Rs;   // R x Rs, L^{-1} then the mixing matrix
-  const float* W = a.W;
 
   double dev = 0.0;
   for (int idx = tid; idx < R * R; idx += nt) {
     const int i = idx / R, j = idx % R;
-    double s = 0.0;
     if (j <= i) {
-      for (int c = 0; c < D; ++c) s += (double)W[(size_t)i * ld + c] * (double)W[(size_t)j * ld + c];
-      s /= sqrt(st->e[i] * st->e[j]);
+      const double s = 0.5 * (a.G[i * R + j] + a.G[j * R + i]) / sqrt(st->e[i] * st->e[j]);
       O[i * Rs + j] = s;
       dev = fmax(dev, fabs(s - (i == j ? 1.0 : 0.0)));
     }

@@ -140,7 +140,8 @@ def test_degenerate_first_minibatches(ngsgd):
 
 
 def test_forced_reorthogonalisation(ngsgd):
-    """A corrupted factor with a large rho drives eigenvalues of Z under their floor (App. B.3.1).
+    """A skewed factor with an ill-conditioned D_t makes cond(C_t) exceed 1e6, which triggers the check of
+    App. B.3.1, and the check then finds R R^T off the identity.
 
     With R R^T != I the efficient form of App. B.3 (which the GPU implements) is no longer the same map as the
     definitional form, so the reference here is the oracle's efficient-form routine, which follows the paper's
@@ -155,18 +156,20 @@ def test_forced_reorthogonalisation(ngsgd):
     for _ in range(3):
         warm.precondition(data(rng, N, D))
     R_bad = warm.R.copy()
-    R_bad[1] *= 1e-3
+    R_bad[1] *= 0.5
     R_bad[2] += 0.3 * R_bad[0]
-    rho_bad = 10.0 * warm.d.max()
+    d_bad = warm.d.copy()
+    d_bad[0] *= 1e5
+    rho_bad = warm.rho
     eff = OnlineNaturalGradientEfficient(D, R, **kw)
-    _, e = smoothing_and_scales(warm.d, rho_bad, 4.0, D)
-    eff.W, eff.d, eff.rho, eff.t = np.sqrt(e)[:, None] * R_bad, warm.d.copy(), rho_bad, warm.t
+    _, e = smoothing_and_scales(d_bad, rho_bad, 4.0, D)
+    eff.W, eff.d, eff.rho, eff.t = np.sqrt(e)[:, None] * R_bad, d_bad.copy(), rho_bad, warm.t
     pre = ngsgd.Preconditioner(D, R, max_batch=N, **kw)
-    pre.set_state(torch.from_numpy(R_bad).cuda(), torch.from_numpy(warm.d.copy()).cuda(), rho_bad, warm.t)
+    pre.set_state(torch.from_numpy(R_bad).cuda(), torch.from_numpy(d_bad.copy()).cuda(), rho_bad, warm.t)
     M = data(rng, N, D)
     expect, _, _ = eff.precondition(M)
     got, _, _ = gpu_call(torch, pre, M)
-    assert eff.last["floored"] and eff.last["reorthogonalised"]
+    assert eff.last["reorthogonalised"]
     assert rel(got, expect) < TOL
     W, d, rho, _ = pre.get_state()
     W = W.cpu().numpy().astype(np.float64)
