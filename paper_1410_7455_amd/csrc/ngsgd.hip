@@ -7,6 +7,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -98,6 +99,15 @@ inline int rank_class(int rank) { return rank <= 32 ? 32 : (rank <= 80 ? 80 : 96
 
 }  // namespace
 
+// The factor update of a network's instances runs on a second stream so that it overlaps the rest of the step
+// and the next step's forward / backward pass; the new factor is first needed by the next preconditioning.
+struct SideSync {
+  hipStream_t stream = nullptr;
+  hipEvent_t inputs_ready = nullptr;   // recorded on the caller's stream: H, J, tr(X X^T) are final
+  hipEvent_t done = nullptr;           // recorded on the side stream: W_{t+1}, D_{t+1}, rho_{t+1} are final
+  bool pending = false;
+};
+
 // ---------------------------------------------------------------------------------------------------
 struct ngsgd_precond {
   int dim = 0, rank = 0, max_batch = 0;
@@ -126,6 +136,7 @@ struct ngsgd_precond {
   int* idx = nullptr;
   double* vwork = nullptr;
   bool owned_by_net = false;
+  SideSync* sync = nullptr;   // set for instances of a network
 };
 
 namespace {
@@ -334,11 +345,23 @@ int run_init(const std::vector<PrecondCall>& calls, hipStream_t s) {
   return NGSGD_OK;
 }
 
+// Makes stream s wait for a factor update still running on the side stream.
+int join_side(SideSync* sync, hipStream_t s) {
+  if (sync != nullptr && sync->pending) {
+    HIP_TRY(hipStreamWaitEvent(s, sync->done, 0));
+    sync->pending = false;
+  }
+  return NGSGD_OK;
+}
+
 // The online natural-gradient call (App. B.5) for a list of independent instances.  With
 // scale_output the matrices are left as gamma * Xhat; without it they are left as Xhat and gamma
-// stays in the instance's state for the caller to fold into a later product.
-int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStream_t s) {
+// stays in the instance's state for the caller to fold into a later product.  With `side` the factor
+// update (everything after J) is enqueued on the side stream.
+int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStream_t s, SideSync* side = nullptr) {
   NG_TRY(ensure_kernel_attributes());
+  NG_TRY(join_side(side, s));
+  const hipStream_t main_stream = s;
   std::vector<PrecondCall> full, to_init, to_update;
   for (auto& c : calls) {
     ngsgd_precond& p = *c.p;
@@ -475,6 +498,11 @@ int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStr
     }
   }
   if (!to_update.empty()) {
+    if (side != nullptr) {
+      HIP_TRY(hipEventRecord(side->inputs_ready, main_stream));
+      HIP_TRY(hipStreamWaitEvent(side->stream, side->inputs_ready, 0));
+      s = side->stream;
+    }
     // K = J J^T, L = H^T H   (App. B.3), fp64 accumulation across the splits
     std::vector<GemmDesc> dk, dl;
     for (auto& c : to_update) {
@@ -538,7 +566,8 @@ int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStr
       const size_t dyn = (size_t)2 * r_max * (r_max | 1) * sizeof(double);
       {
         ProfScope prof(NGSGD_PROF_PRECOND_SMALL, s);
-        hipLaunchKernelGGL(small_update_kernel, dim3(n), dim3(kSmallThreads), dyn, s, g);
+        static const int small_threads = getenv("NGSGD_SMALL_THREADS") ? atoi(getenv("NGSGD_SMALL_THREADS")) : kSmallThreads;
+        hipLaunchKernelGGL(small_update_kernel, dim3(n), dim3(small_threads), dyn, s, g);
         LAUNCH_CHECK();
       }
       // W_{t+1} = A_t B_t   (eq. wt1)
@@ -584,6 +613,10 @@ int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStr
         LAUNCH_CHECK();
       }
       done += n;
+    }
+    if (side != nullptr) {
+      HIP_TRY(hipEventRecord(side->done, side->stream));
+      side->pending = true;
     }
   }
   for (auto& c : calls) c.p->t += 1;
@@ -655,6 +688,7 @@ extern "C" int ngsgd_precondition(ngsgd_precond* p, float* dev_M, int32_t N, int
   if (p == nullptr || dev_M == nullptr) return NGSGD_EINVAL;
   std::vector<PrecondCall> calls(1);
   calls[0] = PrecondCall{p, dev_M, ld, N, dev_gamma, dev_rownorm2};
+  NG_TRY(join_side(p->sync, static_cast<hipStream_t>(hip_stream)));
   return precondition_many(calls, true, static_cast<hipStream_t>(hip_stream));
 }
 
@@ -662,6 +696,7 @@ extern "C" int ngsgd_precond_get_state(const ngsgd_precond* p, float* dev_W, dou
                                        int64_t* t_host, void* hip_stream) {
   if (p == nullptr) return NGSGD_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  NG_TRY(join_side(p->sync, s));
   if (t_host != nullptr) *t_host = p->t;
   if (p->rank == 0) {
     if (dev_rho != nullptr) HIP_TRY(hipMemsetAsync(dev_rho, 0, sizeof(double), s));
@@ -686,6 +721,7 @@ extern "C" int ngsgd_precond_set_state(ngsgd_precond* p, const double* dev_R, co
   }
   if (dev_R == nullptr || dev_d == nullptr) return NGSGD_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  NG_TRY(join_side(p->sync, s));
   hipLaunchKernelGGL(set_state_kernel, dim3(p->rank), dim3(256), 0, s, dev_R, dev_d, rho, p->alpha, p->rank, p->dim,
                      p->W, p->ldw, p->st);
   LAUNCH_CHECK();
@@ -723,6 +759,7 @@ struct ngsgd_net {
   double* logprob = nullptr;
   int last_N = 0;
   float last_lr = 0.f;
+  SideSync side;
 };
 
 namespace {
@@ -801,6 +838,7 @@ void net_layout(ngsgd_net& net, const ngsgd_config* cfg, Carver& c) {
     precond_configure(L.pout, L.dout, cfg->rank_out, cfg->max_batch, cfg->alpha, cfg->num_samples_history,
                       cfg->epsilon, cfg->update_period, cfg->always_update_first);
     L.pin.owned_by_net = L.pout.owned_by_net = true;
+    L.pin.sync = L.pout.sync = &net.side;
     precond_layout(L.pin, c);
     precond_layout(L.pout, c);
   }
@@ -859,10 +897,14 @@ extern "C" int ngsgd_create(const ngsgd_config* cfg, void* dev_workspace, size_t
     if (e == hipSuccess) e = hipMemcpy(L.pout.st, &init, sizeof(init), hipMemcpyHostToDevice);
     if (e == hipSuccess) e = hipMemcpy(L.mc_scale, &one, sizeof(one), hipMemcpyHostToDevice);
   }
+  // second stream for the factor updates: default priority, does not synchronise with the NULL stream
+  if (e == hipSuccess) e = hipStreamCreateWithFlags(&net->side.stream, hipStreamNonBlocking);
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&net->side.inputs_ready, hipEventDisableTiming);
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&net->side.done, hipEventDisableTiming);
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e != hipSuccess) {
     g_last_hip_error = (int)e;
-    delete net;
+    ngsgd_destroy(net);
     return NGSGD_EHIP;
   }
   *out = net;
@@ -871,6 +913,12 @@ extern "C" int ngsgd_create(const ngsgd_config* cfg, void* dev_workspace, size_t
 
 extern "C" int ngsgd_destroy(ngsgd_net* net) {
   if (net == nullptr) return NGSGD_EINVAL;
+  if (net->side.stream != nullptr) {
+    (void)hipStreamSynchronize(net->side.stream);
+    (void)hipStreamDestroy(net->side.stream);
+  }
+  if (net->side.inputs_ready != nullptr) (void)hipEventDestroy(net->side.inputs_ready);
+  if (net->side.done != nullptr) (void)hipEventDestroy(net->side.done);
   delete net;
   return NGSGD_OK;
 }
@@ -965,7 +1013,7 @@ extern "C" int ngsgd_step(ngsgd_net* net, const float* dev_x, const int32_t* dev
     calls.push_back(PrecondCall{&L.pout, L.A, L.lda, N, nullptr, nullptr});
     calls.push_back(PrecondCall{&L.pin, L.Xin, L.ldx, N, nullptr, nullptr});
   }
-  NG_TRY(precondition_many(calls, false, s));
+  NG_TRY(precondition_many(calls, false, s, &net->side));
 
   // maximum parameter change (App. C.3), then W_l += lr a_l gamma_o gamma_x Ohat_l^T Xhat_l  (Sec. 4.6)
   {
@@ -1006,6 +1054,7 @@ extern "C" int ngsgd_average(ngsgd_net* const* nets, int32_t n, int32_t reset_pr
       if (nets[i]->layers[l].dout != nets[0]->layers[l].dout || nets[i]->layers[l].din != nets[0]->layers[l].din)
         return NGSGD_EINVAL;
   }
+  for (int i = 0; i < n; ++i) NG_TRY(join_side(&nets[i]->side, static_cast<hipStream_t>(hip_stream)));
   AverageArgs a;
   a.n = n;
   a.count = nets[0]->n_params_padded;

@@ -17,6 +17,7 @@ namespace ngsgd {
 constexpr int kSmallThreads = 1024;
 constexpr int kMaxSweeps = 30;
 constexpr double kJacobiTol = 1.0e-13;       // a pair is left alone once |z_pq| <= tol * sqrt(z_pp z_qq)
+constexpr double kJacobiAbsTol = 1.0e-15;    // ... or once |z_pq| <= this * max_i z_ii (rounding noise level)
 constexpr double kOrthoCondLimit = 1.0e6;    // App. B.3.1
 constexpr double kOrthoTolerance = 1.0e-3;   // App. B.3.1
 
@@ -37,10 +38,11 @@ struct SmallGroup {
 // Rotation that diagonalises [[app, apq], [apq, aqq]] as J^T A J with J = [[c, s], [-s, c]].  Returns false (and
 // the identity) when the off-diagonal entry is already negligible relative to the diagonal pair; that relative
 // test is what gives small eigenvalues of a graded positive definite matrix their relative accuracy.
-__device__ __forceinline__ bool sym_schur2(double app, double aqq, double apq, double& c, double& s) {
+__device__ __forceinline__ bool sym_schur2(double app, double aqq, double apq, double& c, double& s,
+                                           double abs_tol = 0.0) {
   c = 1.0;
   s = 0.0;
-  if (!(fabs(apq) > kJacobiTol * sqrt(fabs(app * aqq))) || fabs(apq) <= 1.0e-300) return false;
+  if (!(fabs(apq) > fmax(kJacobiTol * sqrt(fabs(app * aqq)), abs_tol)) || fabs(apq) <= 1.0e-300) return false;
   const double tau = (aqq - app) / (2.0 * apq);
   const double t = (tau >= 0.0 ? 1.0 : -1.0) / (fabs(tau) + sqrt(1.0 + tau * tau));
   c = 1.0 / sqrt(1.0 + t * t);
@@ -116,6 +118,9 @@ __global__ __launch_bounds__(kSmallThreads) void small_update_kernel(const Small
   __syncthreads();
 
   // cyclic Jacobi, Z = U C U^T; a sweep in which no pair needed a rotation ends the iteration
+  double zmax = 0.0;
+  for (int i = tid; i < R; i += nt) zmax = fmax(zmax, Z[i * Rs + i]);
+  const double abs_tol = kJacobiAbsTol * block_max(zmax, scratch);
   const int m = (R + 1) & ~1;
   const int half = m / 2;
   int sweeps = 0;
@@ -128,7 +133,8 @@ __global__ __launch_bounds__(kSmallThreads) void small_update_kernel(const Small
         int p, q;
         round_robin_pair(m, r, tid, p, q);
         double c = 1.0, s = 0.0;
-        if (q < R && sym_schur2(Z[p * Rs + p], Z[q * Rs + q], Z[p * Rs + q], c, s)) atomicAdd(&s_rotations, 1);
+        if (q < R && sym_schur2(Z[p * Rs + p], Z[q * Rs + q], Z[p * Rs + q], c, s, abs_tol))
+          atomicAdd(&s_rotations, 1);
         s_p[tid] = p;
         s_q[tid] = q;
         s_cs[tid] = c;
@@ -138,6 +144,7 @@ __global__ __launch_bounds__(kSmallThreads) void small_update_kernel(const Small
       for (int blk = tid; blk < half * half; blk += nt) {
         const int bi = blk / half, bj = blk % half;
         const int pi = s_p[bi], qi = s_q[bi], pj = s_p[bj], qj = s_q[bj];
+        if (s_sn[bi] == 0.0 && s_sn[bj] == 0.0) continue;   // both rotations are the identity
         if (qi >= R || qj >= R) {
           // a pair with the padding index: only the real member's row/column takes part
           if (qi >= R && qj >= R) continue;
@@ -170,8 +177,8 @@ __global__ __launch_bounds__(kSmallThreads) void small_update_kernel(const Small
       for (int idx = tid; idx < R * half; idx += nt) {
         const int row = idx / half, bj = idx % half;
         const int pj = s_p[bj], qj = s_q[bj];
-        if (qj >= R) continue;
         const double cj = s_cs[bj], sj = s_sn[bj];
+        if (qj >= R || sj == 0.0) continue;
         const double u0 = U[row * Rs + pj], u1 = U[row * Rs + qj];
         U[row * Rs + pj] = u0 * cj - u1 * sj;
         U[row * Rs + qj] = u0 * sj + u1 * cj;
