@@ -18,6 +18,11 @@ __device__ __forceinline__ double wave_sum(double v) {
   for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
   return v;
 }
+__device__ __forceinline__ double wave_max_d(double v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v = fmax(v, __shfl_xor(v, off));
+  return v;
+}
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off));
@@ -50,6 +55,18 @@ __device__ __forceinline__ double block_max(double v, double* scratch) {
 // ---- fills and copies ----------------------------------------------------------------------------
 __global__ void fill_u32_kernel(uint32_t* p, size_t n, uint32_t v) {
   for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
+}
+
+// Clears several buffers in one launch: grid (blocks, count).
+struct FillGroup {
+  int count;
+  uint32_t* ptr[kMaxInstances];
+  size_t n[kMaxInstances];
+};
+__global__ void fill_zero_group_kernel(const FillGroup g) {
+  uint32_t* p = g.ptr[blockIdx.y];
+  const size_t n = g.n[blockIdx.y];
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0u;
 }
 
 // out[n][0..D) = x[n][0..D), out[n][D] = 1, out[n][D+1..ldo) = 0   (input with the bias 1 appended, Sec. 4.4)
@@ -105,7 +122,23 @@ __global__ void tanh_backward_kernel(const float* __restrict__ dY, int ldd, int 
   }
 }
 
-// p-norm (p = 2) over groups of G adjacent columns, one wavefront per row:
+// Workgroup-wide float sum / max for 256-thread workgroups (4 wavefronts); `red` holds >= 4 floats.
+__device__ __forceinline__ float block256_sum(float v, float* red) {
+  v = wave_sum(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return red[0] + red[1] + red[2] + red[3];
+}
+__device__ __forceinline__ float block256_max(float v, float* red) {
+  v = wave_max(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  return fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+}
+
+// p-norm (p = 2) over groups of G adjacent columns, one 256-thread workgroup per row:
 //   y_j = sqrt(sum_k a_{Gj+k}^2);  with renorm: y <- y / max(rms(y), floor), sigma[n] = that divisor.
 // Writes Y[n][0..groups), Y[n][groups] = 1, padding zero.
 constexpr float kRenormFloor = 1.0e-20f;
@@ -114,89 +147,181 @@ __global__ __launch_bounds__(256) void pnorm_forward_kernel(const float* __restr
                                                             float* __restrict__ Y, int ldy,
                                                             float* __restrict__ sigma, int N, int groups, int G,
                                                             int renorm) {
-  const int lane = threadIdx.x & 63;
-  const int row = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-  if (row >= N) return;
+  __shared__ float red[4];
+  const int row = blockIdx.x;
   const float* a = A + (size_t)row * lda;
   float* y = Y + (size_t)row * ldy;
   float ss = 0.f;
-  for (int j = lane; j < groups; j += 64) {
+  // a thread keeps the (few) groups it computes in registers until the row's scale is known
+  constexpr int kMaxOwn = 8;   // groups per thread: rows of up to 2048 groups stay in registers
+  float own[kMaxOwn];
+#pragma unroll
+  for (int u = 0; u < kMaxOwn; ++u) {
+    const int j = threadIdx.x + u * 256;
     float s = 0.f;
-    for (int k = 0; k < G; ++k) {
-      const float v = a[j * G + k];
-      s += v * v;
+    if (j < groups) {
+      const float* g = a + (size_t)j * G;
+      if ((G & 1) == 0) {
+        for (int k = 0; k < G; k += 2) {
+          const float2 v = *reinterpret_cast<const float2*>(g + k);
+          s += v.x * v.x + v.y * v.y;
+        }
+      } else {
+        for (int k = 0; k < G; ++k) s += g[k] * g[k];
+      }
     }
-    ss += s;              // sum_j y_j^2
+    own[u] = sqrtf(s);
+    ss += s;
+  }
+  for (int j = threadIdx.x + kMaxOwn * 256; j < groups; j += 256) {   // very wide rows: through memory
+    float s = 0.f;
+    for (int k = 0; k < G; ++k) s += a[(size_t)j * G + k] * a[(size_t)j * G + k];
     y[j] = sqrtf(s);
+    ss += s;
   }
   float inv = 1.f;
   if (renorm) {
-    ss = wave_sum(ss);
+    ss = block256_sum(ss, red);
     const float sg = fmaxf(sqrtf(ss / (float)groups), kRenormFloor);
     inv = 1.f / sg;
-    if (lane == 0) sigma[row] = sg;
-    for (int j = lane; j < groups; j += 64) y[j] *= inv;   // same lane wrote y[j] above
+    if (threadIdx.x == 0) sigma[row] = sg;
+    for (int j = threadIdx.x + kMaxOwn * 256; j < groups; j += 256) y[j] *= inv;   // written by this thread above
   }
-  for (int c = groups + lane; c < ldy; c += 64) y[c] = c == groups ? 1.f : 0.f;
+#pragma unroll
+  for (int u = 0; u < kMaxOwn; ++u) {
+    const int j = threadIdx.x + u * 256;
+    if (j < groups) y[j] = own[u] * inv;
+  }
+  for (int c = groups + threadIdx.x; c < ldy; c += 256) y[c] = c == groups ? 1.f : 0.f;
 }
 
-// Backward through (renorm o p-norm), one wavefront per row, in place over the affine outputs:
+// Backward through (renorm o p-norm), one 256-thread workgroup per row, in place over the affine outputs:
 //   AO[n][Gj+k] <- dy_j * a_{Gj+k} / y_j   (0 where y_j = 0)
 // with dy = dYn, y = Yn without renorm; with renorm  y = Yn*sigma, dy = (dYn - Yn * mean_j(dYn_j Yn_j)) / sigma.
+// dYn arrives as n_slabs partial products (see slab_sum).  The per-group factor dy_j / y_j goes through LDS.
+constexpr int kPnormMaxGroupsLds = 4096;
+
 __global__ __launch_bounds__(256) void pnorm_backward_kernel(const float* __restrict__ dYn, int ldd, int n_slabs,
                                                              size_t slab_stride,
                                                              const float* __restrict__ Yn, int ldy,
                                                              const float* __restrict__ sigma,
                                                              float* __restrict__ AO, int lda, int N, int groups,
                                                              int G, int renorm) {
-  const int lane = threadIdx.x & 63;
-  const int row = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-  if (row >= N) return;
+  __shared__ float red[4];
+  __shared__ float s_f[kPnormMaxGroupsLds];   // first dy_j, then the factor dy_j / y_j
+  const int row = blockIdx.x;
   const float* dy = dYn + (size_t)row * ldd;
   const float* yn = Yn + (size_t)row * ldy;
   float* ao = AO + (size_t)row * lda;
+  float dot = 0.f;
+  for (int j = threadIdx.x; j < groups; j += 256) {
+    const float d = slab_sum(dy + j, n_slabs, slab_stride);
+    s_f[j] = d;
+    dot += d * yn[j];
+  }
   float proj = 0.f, sg = 1.f;
   if (renorm) {
-    float dot = 0.f;
-    for (int j = lane; j < groups; j += 64) dot += slab_sum(dy + j, n_slabs, slab_stride) * yn[j];
-    dot = wave_sum(dot);
+    dot = block256_sum(dot, red);
     sg = sigma[row];
     proj = sg > kRenormFloor ? dot / (float)groups : 0.f;
   }
   const float inv_sg = 1.f / sg;
-  for (int j = lane; j < groups; j += 64) {
+  for (int j = threadIdx.x; j < groups; j += 256) {   // each thread rewrites the entries it wrote above
     const float ynj = yn[j];
-    const float d = (slab_sum(dy + j, n_slabs, slab_stride) - ynj * proj) * inv_sg;
+    const float d = (s_f[j] - ynj * proj) * inv_sg;
     const float yj = ynj * sg;
-    const float f = yj > 0.f ? d / yj : 0.f;
-    for (int k = 0; k < G; ++k) ao[j * G + k] *= f;
+    s_f[j] = yj > 0.f ? d / yj : 0.f;
+  }
+  __syncthreads();
+  const int D = groups * G;
+  if ((G & 1) == 0 && (lda & 1) == 0) {
+    float2* ao2 = reinterpret_cast<float2*>(ao);
+    const int half_g = G / 2;
+    for (int c2 = threadIdx.x; c2 < D / 2; c2 += 256) {
+      const float f = s_f[c2 / half_g];
+      float2 v = ao2[c2];
+      v.x *= f;
+      v.y *= f;
+      ao2[c2] = v;
+    }
+  } else {
+    for (int c = threadIdx.x; c < D; c += 256) ao[c] *= s_f[c / G];
   }
 }
 
 // ---- log-softmax, objective and its derivative (Sec. 2) ------------------------------------------
-// One workgroup per row, in place: AO[n][c] <- [c == y_n] - softmax(a_n)_c;  rowobj[n] = log p(y_n | x_n).
+// One 256-thread workgroup per row, in place: AO[n][c] <- [c == y_n] - softmax(a_n)_c;
+// rowobj[n] = log p(y_n | x_n).  Rows of up to 256*4*kSoftmaxVec classes are read once and kept in registers.
+constexpr int kSoftmaxVec = 8;   // float4 per thread
+
 __global__ __launch_bounds__(256) void softmax_xent_kernel(float* __restrict__ AO, int ld,
                                                            const int32_t* __restrict__ labels, int N, int C,
                                                            double* __restrict__ rowobj) {
-  __shared__ double scratch[16];
+  __shared__ float red[4];
   const int row = blockIdx.x;
   float* a = AO + (size_t)row * ld;
-  float m = -INFINITY;
-  for (int c = threadIdx.x; c < C; c += blockDim.x) m = fmaxf(m, a[c]);
-  m = (float)block_max((double)m, scratch);
-  double s = 0.0;
-  for (int c = threadIdx.x; c < C; c += blockDim.x) s += (double)expf(a[c] - m);
-  s = block_sum(s, scratch);
-  const float lse = m + (float)log(s);
   const int y = labels[row];
   const bool valid = y >= 0 && y < C;        // an out-of-range label yields NaN, never an out-of-bounds access
-  __syncthreads();
-  if (threadIdx.x == 0) rowobj[row] = valid ? (double)a[y] - ((double)m + log(s)) : (double)NAN;
-  __syncthreads();
-  for (int c = threadIdx.x; c < C; c += blockDim.x) {
-    const float p = expf(a[c] - lse);
-    a[c] = (c == y ? 1.f : 0.f) - p;
+  if (C <= 256 * 4 * kSoftmaxVec) {
+    float4 v[kSoftmaxVec];
+    float m = -INFINITY;
+#pragma unroll
+    for (int u = 0; u < kSoftmaxVec; ++u) {
+      const int c = (threadIdx.x + u * 256) * 4;
+      float4 t = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+      if (c + 3 < C) {
+        t = *reinterpret_cast<const float4*>(a + c);
+      } else if (c < C) {
+        t.x = a[c];
+        if (c + 1 < C) t.y = a[c + 1];
+        if (c + 2 < C) t.z = a[c + 2];
+      }
+      v[u] = t;
+      m = fmaxf(fmaxf(m, fmaxf(t.x, t.y)), fmaxf(t.z, t.w));
+    }
+    m = block256_max(m, red);
+    float s = 0.f;
+#pragma unroll
+    for (int u = 0; u < kSoftmaxVec; ++u) {
+      v[u].x = expf(v[u].x - m);
+      v[u].y = expf(v[u].y - m);
+      v[u].z = expf(v[u].z - m);
+      v[u].w = expf(v[u].w - m);
+      s += (v[u].x + v[u].y) + (v[u].z + v[u].w);
+    }
+    s = block256_sum(s, red);
+    if (threadIdx.x == 0) rowobj[row] = valid ? (double)a[y] - ((double)m + log((double)s)) : (double)NAN;
+    __syncthreads();   // a[y] is read before any thread overwrites the row
+    const float inv = 1.f / s;
+#pragma unroll
+    for (int u = 0; u < kSoftmaxVec; ++u) {
+      const int c = (threadIdx.x + u * 256) * 4;
+      float4 o;
+      o.x = (c == y ? 1.f : 0.f) - v[u].x * inv;
+      o.y = (c + 1 == y ? 1.f : 0.f) - v[u].y * inv;
+      o.z = (c + 2 == y ? 1.f : 0.f) - v[u].z * inv;
+      o.w = (c + 3 == y ? 1.f : 0.f) - v[u].w * inv;
+      if (c + 3 < C) {
+        *reinterpret_cast<float4*>(a + c) = o;
+      } else if (c < C) {
+        a[c] = o.x;
+        if (c + 1 < C) a[c + 1] = o.y;
+        if (c + 2 < C) a[c + 2] = o.z;
+      }
+    }
+    return;
   }
+  // wider rows: three passes over memory
+  float m = -INFINITY;
+  for (int c = threadIdx.x; c < C; c += 256) m = fmaxf(m, a[c]);
+  m = block256_max(m, red);
+  float s = 0.f;
+  for (int c = threadIdx.x; c < C; c += 256) s += expf(a[c] - m);
+  s = block256_sum(s, red);
+  const float lse = m + logf(s);
+  if (threadIdx.x == 0) rowobj[row] = valid ? (double)a[y] - ((double)m + log((double)s)) : (double)NAN;
+  __syncthreads();
+  for (int c = threadIdx.x; c < C; c += 256) a[c] = (c == y ? 1.f : 0.f) - expf(a[c] - lse);
 }
 
 __global__ __launch_bounds__(256) void sum_double_kernel(const double* __restrict__ v, int n,
@@ -227,18 +352,35 @@ struct FinishGroup {
   FinishArgs a[kMaxInstances];
 };
 
-__global__ __launch_bounds__(256) void finish_apply_kernel(const FinishGroup g) {
+__global__ __launch_bounds__(1024) void finish_apply_kernel(const FinishGroup g) {
   __shared__ double scratch[16];
   const FinishArgs& a = g.a[blockIdx.x];
   double t = 0.0;
   for (int i = threadIdx.x; i < a.n_sumsq; i += blockDim.x) t += a.sumsq_part[i];
   const double tr_M = block_sum(t, scratch);
+  // four lanes share a row: each adds every fourth column tile (independent loads), then the quad is combined
+  const int part = threadIdx.x & 3;
+  const int N = a.N, nct = a.n_col_tiles;
+  const int rows_per_pass = blockDim.x >> 2;
   double ph = 0.0;
-  for (int r = threadIdx.x; r < a.N; r += blockDim.x) {
-    double p = 0.0;
-    for (int c = 0; c < a.n_col_tiles; ++c) p += (double)a.rownorm_part[(size_t)c * a.N + r];
-    a.prow[r] = p;
-    ph += p;
+  for (int r0 = 0; r0 < N; r0 += rows_per_pass) {
+    const int r = r0 + (threadIdx.x >> 2);
+    float p0 = 0.f, p1 = 0.f;
+    if (r < N) {
+      int c = part;
+      for (; c + 4 < nct; c += 8) {
+        p0 += a.rownorm_part[(size_t)c * N + r];
+        p1 += a.rownorm_part[(size_t)(c + 4) * N + r];
+      }
+      if (c < nct) p0 += a.rownorm_part[(size_t)c * N + r];
+    }
+    double p = (double)p0 + (double)p1;
+    p += __shfl_xor(p, 1);
+    p += __shfl_xor(p, 2);
+    if (r < N && part == 0) {
+      a.prow[r] = p;
+      ph += p;
+    }
   }
   const double tr_Mhat = block_sum(ph, scratch);
   const double gamma = tr_Mhat > 0.0 ? sqrt(tr_M / tr_Mhat) : 1.0;
@@ -248,8 +390,10 @@ __global__ __launch_bounds__(256) void finish_apply_kernel(const FinishGroup g) 
     a.st->tr_Mhat = tr_Mhat;
     if (a.gamma_out != nullptr) *a.gamma_out = (float)gamma;
   }
-  if (a.rownorm2_out != nullptr)
-    for (int r = threadIdx.x; r < a.N; r += blockDim.x) a.rownorm2_out[r] = (float)(gamma * gamma * a.prow[r]);
+  if (a.rownorm2_out != nullptr) {
+    __syncthreads();   // prow was written by other lanes
+    for (int r = threadIdx.x; r < N; r += blockDim.x) a.rownorm2_out[r] = (float)(gamma * gamma * a.prow[r]);
+  }
 }
 
 // Rank 0: no factor, the output is the input; only the row norms are produced.  One workgroup per row block.
@@ -270,15 +414,27 @@ __global__ __launch_bounds__(256) void rownorm_kernel(const float* __restrict__ 
   }
 }
 
-// B_t = J_t + (N (1 - eta) / eta) (D_t + rho_t I) W_t, written over J (eq. wt1).  Grid (col blocks, R).
+// B_t = J_t + (N (1 - eta) / eta) (D_t + rho_t I) W_t, written over J (eq. wt1).  Grid (col blocks, R, instance).
 // Must run while st still holds D_t and rho_t, i.e. before the R x R update kernel.
-__global__ void make_bt_kernel(float* __restrict__ J, const float* __restrict__ W, int ld, int D,
-                               const PrecondScalars* __restrict__ st, int N, double num_samples_history) {
+struct BtArgs {
+  float* J;
+  const float* W;
+  const PrecondScalars* st;
+  int ld, D, R, N;
+};
+struct BtGroup {
+  int count;
+  double num_samples_history;
+  BtArgs a[kMaxInstances];
+};
+__global__ void make_bt_kernel(const BtGroup g) {
+  const BtArgs& a = g.a[blockIdx.z];
   const int i = blockIdx.y;
-  const double eta = 1.0 - exp(-(double)N / num_samples_history);
-  const float f = (float)((double)N * (1.0 - eta) / eta * (st->d[i] + st->rho));
-  for (int c = blockIdx.x * blockDim.x + threadIdx.x; c < D; c += gridDim.x * blockDim.x)
-    J[(size_t)i * ld + c] += f * W[(size_t)i * ld + c];
+  if (i >= a.R) return;
+  const double eta = 1.0 - exp(-(double)a.N / g.num_samples_history);
+  const float f = (float)((double)a.N * (1.0 - eta) / eta * (a.st->d[i] + a.st->rho));
+  for (int c = blockIdx.x * blockDim.x + threadIdx.x; c < a.D; c += gridDim.x * blockDim.x)
+    a.J[(size_t)i * a.ld + c] += f * a.W[(size_t)i * a.ld + c];
 }
 
 // W = E^{1/2} R from a state given in definitional form (eq. beta2, etii, wt:def).  One workgroup per row.

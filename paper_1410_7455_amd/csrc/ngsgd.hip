@@ -135,6 +135,8 @@ struct ngsgd_precond {
   double* Vi[2] = {nullptr, nullptr};
   int* idx = nullptr;
   double* vwork = nullptr;
+  double2* rotlog = nullptr;      // Jacobi rotation log of the latest factor update
+  EigWork* eigwork = nullptr;
   bool owned_by_net = false;
   SideSync* sync = nullptr;   // set for instances of a network
 };
@@ -170,6 +172,12 @@ void precond_layout(ngsgd_precond& p, Carver& c) {
   p.Vi[1] = c.take<double>(nn);
   p.idx = c.take<int>(kMaxRank);
   p.vwork = c.take<double>((size_t)kMaxRank + D);
+  {
+    const int m = (R + 1) & ~1;
+    const size_t rounds = ((size_t)kMaxSweeps * (m - 1 > 0 ? m - 1 : 1) + kEigvecChunk - 1) / kEigvecChunk * kEigvecChunk;
+    p.rotlog = c.take<double2>((rounds + kEigvecChunk) * (m / 2));   // padded: the log is read in whole chunks
+    p.eigwork = c.take<EigWork>(1);
+  }
 }
 
 int precond_check_config(int dim, int rank, int max_batch, float alpha, float S, float eps, int period, int first) {
@@ -195,8 +203,8 @@ bool g_attr_done = false;
 int ensure_kernel_attributes() {
   if (g_attr_done) return NGSGD_OK;
   const int max_dyn = 2 * kMaxRank * (kMaxRank | 1) * (int)sizeof(double);
-  HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(small_update_kernel),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, max_dyn));
+  HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(eig_update_kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, max_dyn / 2));
   HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(orth_fix_kernel),
                               hipFuncAttributeMaxDynamicSharedMemorySize, max_dyn));
   g_attr_done = true;
@@ -388,14 +396,25 @@ int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStr
   }
   if (!to_init.empty()) NG_TRY(run_init(to_init, s));
 
-  // clear the accumulation buffers
-  {
+  // clear the accumulation buffers (H always; K, L when the factor is updated)
+  for (size_t done = 0; done < full.size();) {
     ProfScope prof(NGSGD_PROF_PRECOND_MISC, s);
-  for (auto& c : full) {
-    ngsgd_precond& p = *c.p;
-    const bool upd = p.t < p.always_update_first || p.t % p.update_period == 0;
-    NG_TRY(fill_zero(p.zero_region, upd ? p.zero_floats_all : (size_t)c.N * p.ldh, s));
-  }
+    FillGroup fg;
+    const int n = (int)std::min<size_t>(kMaxInstances, full.size() - done);
+    fg.count = n;
+    size_t n_max = 0;
+    for (int i = 0; i < n; ++i) {
+      const PrecondCall& c = full[done + i];
+      ngsgd_precond& p = *c.p;
+      const bool upd = p.t < p.always_update_first || p.t % p.update_period == 0;
+      fg.ptr[i] = reinterpret_cast<uint32_t*>(p.zero_region);
+      fg.n[i] = upd ? p.zero_floats_all : (size_t)c.N * p.ldh;
+      n_max = std::max(n_max, fg.n[i]);
+    }
+    const unsigned blocks = (unsigned)std::min<size_t>((n_max + 2047) / 2048, 64);
+    hipLaunchKernelGGL(fill_zero_group_kernel, dim3(blocks > 0 ? blocks : 1, n), dim3(256), 0, s, fg);
+    LAUNCH_CHECK();
+    done += n;
   }
   // H = X W^T   (eq. ht), tr(X X^T) partials
   for (int rc : {32, 80, 96}) {
@@ -484,7 +503,7 @@ int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStr
       a.gamma_out = c.gamma_out;
       a.rownorm2_out = c.rownorm2_out;
     }
-    hipLaunchKernelGGL(finish_apply_kernel, dim3(n), dim3(256), 0, s, g);
+    hipLaunchKernelGGL(finish_apply_kernel, dim3(n), dim3(1024), 0, s, g);
     LAUNCH_CHECK();
     done += n;
   }
@@ -531,14 +550,24 @@ int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStr
                                                                                                (int)dl.size(), s)));
     }
     // B_t over J (needs D_t, rho_t: before the R x R update)
-    {
+    for (size_t done = 0; done < to_update.size();) {
       ProfScope prof(NGSGD_PROF_PRECOND_MISC, s);
-      for (auto& c : to_update) {
+      BtGroup bg;
+      bg.num_samples_history = to_update[done].p->num_samples_history;
+      int n = 0, r_max = 0, d_max = 0;
+      while (n < kMaxInstances && done + n < to_update.size()) {
+        const PrecondCall& c = to_update[done + n];
         ngsgd_precond& p = *c.p;
-        hipLaunchKernelGGL(make_bt_kernel, dim3((p.dim + 1023) / 1024, p.rank), dim3(256), 0, s, p.J, p.W, p.ldw,
-                           p.dim, p.st, c.N, p.num_samples_history);
-        LAUNCH_CHECK();
+        if (p.num_samples_history != bg.num_samples_history) break;
+        bg.a[n] = BtArgs{p.J, p.W, p.st, p.ldw, p.dim, p.rank, c.N};
+        r_max = std::max(r_max, p.rank);
+        d_max = std::max(d_max, p.dim);
+        ++n;
       }
+      bg.count = n;
+      hipLaunchKernelGGL(make_bt_kernel, dim3((d_max + 1023) / 1024, r_max, n), dim3(256), 0, s, bg);
+      LAUNCH_CHECK();
+      done += n;
     }
     // Z_t, eigen-decomposition, rho_{t+1}, D_{t+1}, A_t
     for (size_t done = 0; done < to_update.size();) {
@@ -557,6 +586,7 @@ int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStr
         SmallArgs& a = g.a[n];
         a.st = p.st; a.K = p.K; a.L = p.L; a.At = p.At; a.ldat = p.ldh;
         a.R = p.rank; a.D = p.dim; a.N = c.N;
+        a.rotlog = p.rotlog; a.work = p.eigwork;
         OrthArgs& o = og.a[n];
         o.st = p.st; o.G = p.K; o.W = p.W; o.ld = p.ldw; o.R = p.rank; o.D = p.dim;
         r_max = std::max(r_max, p.rank);
@@ -566,8 +596,11 @@ int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStr
       const size_t dyn = (size_t)2 * r_max * (r_max | 1) * sizeof(double);
       {
         ProfScope prof(NGSGD_PROF_PRECOND_SMALL, s);
-        static const int small_threads = getenv("NGSGD_SMALL_THREADS") ? atoi(getenv("NGSGD_SMALL_THREADS")) : kSmallThreads;
-        hipLaunchKernelGGL(small_update_kernel, dim3(n), dim3(small_threads), dyn, s, g);
+        hipLaunchKernelGGL(eig_update_kernel, dim3(n), dim3(kEigThreads), dyn / 2, s, g);
+        LAUNCH_CHECK();
+        const int rows_per_block = kEigvecThreads / 64;
+        hipLaunchKernelGGL(eigvec_kernel, dim3(n, (r_max + rows_per_block - 1) / rows_per_block), dim3(kEigvecThreads),
+                           0, s, g);
         LAUNCH_CHECK();
       }
       // W_{t+1} = A_t B_t   (eq. wt1)
@@ -781,7 +814,7 @@ int net_check_config(const ngsgd_config* cfg) {
                                 cfg->epsilon, cfg->update_period, cfg->always_update_first));
     if (l < cfg->n_layers - 1) {
       if (cfg->nonlin[l] == NGSGD_PNORM) {
-        if (dout % cfg->pnorm_group) return NGSGD_EINVAL;
+        if (dout % cfg->pnorm_group || dout / cfg->pnorm_group > kPnormMaxGroupsLds) return NGSGD_EINVAL;
         din = dout / cfg->pnorm_group;
       } else if (cfg->nonlin[l] == NGSGD_TANH) {
         din = dout;
@@ -957,7 +990,7 @@ extern "C" int ngsgd_step(ngsgd_net* net, const float* dev_x, const int32_t* dev
         hipLaunchKernelGGL(tanh_forward_kernel, dim3((Nx.ldx + 1023) / 1024, N), dim3(256), 0, s, L.A, L.lda, Nx.Xin,
                            Nx.ldx, N, L.dout);
       } else {
-        hipLaunchKernelGGL(pnorm_forward_kernel, dim3((N + 3) / 4), dim3(256), 0, s, L.A, L.lda, Nx.Xin, Nx.ldx,
+        hipLaunchKernelGGL(pnorm_forward_kernel, dim3(N), dim3(256), 0, s, L.A, L.lda, Nx.Xin, Nx.ldx,
                            L.sigma, N, L.groups, net->pnorm_group, net->renorm);
       }
       LAUNCH_CHECK();
@@ -1001,7 +1034,7 @@ extern "C" int ngsgd_step(ngsgd_net* net, const float* dev_x, const int32_t* dev
       hipLaunchKernelGGL(tanh_backward_kernel, dim3((P.dout + 1023) / 1024, N), dim3(256), 0, s, net->dX, net->lddx,
                          n_slabs, slab, L.Xin, L.ldx, P.A, P.lda, N, P.dout);
     } else {
-      hipLaunchKernelGGL(pnorm_backward_kernel, dim3((N + 3) / 4), dim3(256), 0, s, net->dX, net->lddx, n_slabs, slab,
+      hipLaunchKernelGGL(pnorm_backward_kernel, dim3(N), dim3(256), 0, s, net->dX, net->lddx, n_slabs, slab,
                          L.Xin, L.ldx, P.sigma, P.A, P.lda, N, P.groups, net->pnorm_group, net->renorm);
     }
     LAUNCH_CHECK();

@@ -14,20 +14,37 @@
 
 namespace ngsgd {
 
-constexpr int kSmallThreads = 1024;
-constexpr int kMaxSweeps = 30;
+constexpr int kSmallThreads = 1024;          // orthogonality fix kernel
+constexpr int kEigThreads = 1024;            // R x R eigen-update kernel
+constexpr int kEigItems = (kMaxRank / 2 * (kMaxRank / 2 + 1) / 2 + kEigThreads - 1) / kEigThreads;   // blocks per thread
+constexpr int kEigvecThreads = 256;          // eigenvector kernel: 4 wavefronts, one row of U each
+constexpr int kEigvecChunk = 32;             // rounds of the rotation log staged in LDS at a time
+constexpr int kMaxSweeps = 20;
+constexpr int kMaxHalf = kMaxRank / 2;
+constexpr int kMaxRounds = kMaxSweeps * (kMaxRank - 1);
 constexpr double kJacobiTol = 1.0e-13;       // a pair is left alone once |z_pq| <= tol * sqrt(z_pp z_qq)
-constexpr double kJacobiAbsTol = 1.0e-15;    // ... or once |z_pq| <= this * max_i z_ii (rounding noise level)
+constexpr double kJacobiAbsTol = 1.0e-13;    // ... or once |z_pq| <= this * max_i z_ii (rounding noise level)
 constexpr double kOrthoCondLimit = 1.0e6;    // App. B.3.1
 constexpr double kOrthoTolerance = 1.0e-3;   // App. B.3.1
+
+// What the eigen-update kernel leaves for the eigenvector kernel (device memory, per instance).
+struct EigWork {
+  int n_rounds;                  // Jacobi rounds executed (rotation log length / half)
+  int pad;
+  int rank_of[kMaxRank];         // position of eigenpair i in decreasing-eigenvalue order
+  double colscale[kMaxRank];     // (eta/N) sqrt(e_{t+1,k} / c_i) for eigenpair i at position k
+  double rowscale[kMaxRank];     // e_{t,j}^{-1/2}
+};
 
 struct SmallArgs {
   PrecondScalars* st;
   double* K;         // R x R, J J^T; cleared on exit (the orthogonality check accumulates W W^T into it)
   const double* L;   // R x R, H^T H
-  float* At;         // out: A_t (eq. wt1), R x ldat
+  float* At;         // out: A_t (eq. wt1), R x ldat (written by the eigenvector kernel)
   int ldat;
   int R, D, N;
+  double2* rotlog;   // [kMaxRounds][half] (c, s) of every pair of every round
+  EigWork* work;
 };
 struct SmallGroup {
   int count;
@@ -35,14 +52,44 @@ struct SmallGroup {
   SmallArgs a[kMaxInstances];
 };
 
+__device__ __forceinline__ double fast_rsqrt(double x) {
+  double y = __builtin_amdgcn_rsq(x);
+  y = y * (1.5 - 0.5 * x * y * y);
+  y = y * (1.5 - 0.5 * x * y * y);
+  return y;
+}
+__device__ __forceinline__ double fast_rcp(double x) {
+  double r = __builtin_amdgcn_rcp(x);
+  r = r * (2.0 - x * r);
+  r = r * (2.0 - x * r);
+  return r;
+}
+
 // Rotation that diagonalises [[app, apq], [apq, aqq]] as J^T A J with J = [[c, s], [-s, c]].  Returns false (and
-// the identity) when the off-diagonal entry is already negligible relative to the diagonal pair; that relative
-// test is what gives small eigenvalues of a graded positive definite matrix their relative accuracy.
-__device__ __forceinline__ bool sym_schur2(double app, double aqq, double apq, double& c, double& s,
-                                           double abs_tol = 0.0) {
+// the identity) when the off-diagonal entry is already negligible: relative to the diagonal pair (that relative
+// test is what gives small eigenvalues of a graded positive definite matrix their relative accuracy) or in
+// absolute terms (abs_tol2 is the squared absolute threshold).  Division and square roots go through the
+// hardware reciprocal estimates plus Newton steps: the rotation sits on the critical path of every round.
+__device__ __forceinline__ bool jacobi_rotation(double app, double aqq, double apq, double abs_tol2, double& c,
+                                                double& s) {
   c = 1.0;
   s = 0.0;
-  if (!(fabs(apq) > fmax(kJacobiTol * sqrt(fabs(app * aqq)), abs_tol)) || fabs(apq) <= 1.0e-300) return false;
+  const double apq2 = apq * apq;
+  if (!(apq2 > kJacobiTol * kJacobiTol * fabs(app * aqq)) || !(apq2 > abs_tol2) || !(apq2 > 1.0e-290)) return false;
+  const double h = 0.5 * (aqq - app);
+  const double x = h * h + apq2;
+  const double r = x * fast_rsqrt(x);
+  const double t = apq * fast_rcp(h + (h >= 0.0 ? r : -r));
+  c = fast_rsqrt(1.0 + t * t);
+  s = t * c;
+  return true;
+}
+
+// Exact variant used by the (not latency critical) initialisation.
+__device__ __forceinline__ bool sym_schur2(double app, double aqq, double apq, double& c, double& s) {
+  c = 1.0;
+  s = 0.0;
+  if (!(fabs(apq) > kJacobiTol * sqrt(fabs(app * aqq))) || fabs(apq) <= 1.0e-300) return false;
   const double tau = (aqq - app) / (2.0 * apq);
   const double t = (tau >= 0.0 ? 1.0 : -1.0) / (fabs(tau) + sqrt(1.0 + tau * tau));
   c = 1.0 / sqrt(1.0 + t * t);
@@ -51,7 +98,7 @@ __device__ __forceinline__ bool sym_schur2(double app, double aqq, double apq, d
 }
 
 // Round-robin pairing of m (even) players: in round r, pair k is (m-1, r) for k = 0 and
-// ((r+k) mod (m-1), (r-k) mod (m-1)) otherwise; over rounds 0..m-2 every pair meets once.
+// ((r+k) mod (m-1), (r-k) mod (m-1)) otherwise; over rounds 0..m-2 every pair meets once.  Returned with p < q.
 __device__ __forceinline__ void round_robin_pair(int m, int r, int k, int& p, int& q) {
   if (k == 0) {
     p = r;
@@ -67,27 +114,50 @@ __device__ __forceinline__ void round_robin_pair(int m, int r, int k, int& p, in
   }
 }
 
-__global__ __launch_bounds__(kSmallThreads) void small_update_kernel(const SmallGroup g) {
-  extern __shared__ __attribute__((aligned(16))) double dyn[];
+// Players of pair k in round r of the round-robin schedule, unsorted: first (r+k) mod (m-1), second
+// (r-k) mod (m-1), except that pair 0's second is the fixed player m-1.  Tracked incrementally per thread.
+struct PairPlayers {
+  int first, second;
+  bool fixed;   // pair 0: `second` never moves
+  __device__ __forceinline__ void init(int m, int k) {
+    first = k;
+    second = m - 1 - k;
+    fixed = k == 0;
+  }
+  __device__ __forceinline__ void advance(int m) {
+    first = first + 1 == m - 1 ? 0 : first + 1;
+    if (!fixed) second = second + 1 == m - 1 ? 0 : second + 1;
+  }
+  __device__ __forceinline__ int p() const { return first < second ? first : second; }
+  __device__ __forceinline__ int q() const { return first < second ? second : first; }
+};
+
+// Z_t (eq. zt:compute), its eigenvalues by cyclic Jacobi, then rho_{t+1}, D_{t+1}, E_{t+1} (eq. rhodash2, dt1,
+// rhot1, beta2, etii).  One workgroup per instance.  Only Z is rotated here (upper triangle, in LDS): every
+// rotation is logged, and the eigenvector kernel replays the log on the rows of the identity.  A round is:
+// wave 0 computes the floor(R/2) rotations | barrier | every thread updates at most kEigItems 2x2 blocks whose
+// addresses it tracks in registers | barrier.
+__global__ __launch_bounds__(kEigThreads) void eig_update_kernel(const SmallGroup g) {
+  extern __shared__ __attribute__((aligned(16))) double dyn[];   // Z, R x Rs, entries (i <= j) are live
   __shared__ double scratch[16];
   __shared__ double s_d[kMaxRank], s_ise[kMaxRank], s_dr[kMaxRank], s_c[kMaxRank], s_enew[kMaxRank];
-  __shared__ double s_cs[kMaxRank / 2 + 1], s_sn[kMaxRank / 2 + 1];
-  __shared__ int s_p[kMaxRank / 2 + 1], s_q[kMaxRank / 2 + 1], s_perm[kMaxRank];
+  __shared__ double2 s_rot[kMaxHalf];
+  __shared__ int s_perm[kMaxRank];
   __shared__ double s_scal[8];
   __shared__ int s_flag[2];
-  __shared__ int s_rotations;
+  __shared__ int s_rotated;
 
   const SmallArgs& a = g.a[blockIdx.x];
   const int R = a.R, D = a.D, N = a.N;
-  const int tid = threadIdx.x, nt = blockDim.x;
-  const int Rs = R | 1;                       // odd row stride
+  const int tid = threadIdx.x;
+  constexpr int nt = kEigThreads;
+  const int Rs = R | 1;
   double* Z = dyn;
-  double* U = dyn + (size_t)R * Rs;
   PrecondScalars* st = a.st;
 
   const double eta = 1.0 - exp(-(double)N / g.num_samples_history);   // eq. eta:ns
   const double rho = st->rho;
-  if (tid < R) s_d[tid] = st->d[tid];
+  for (int i = tid; i < R; i += nt) s_d[i] = st->d[i];
   __syncthreads();
   if (tid == 0) {
     double sum_d = 0.0;
@@ -97,120 +167,133 @@ __global__ __launch_bounds__(kSmallThreads) void small_update_kernel(const Small
   }
   __syncthreads();
   const double sum_d = s_scal[0], beta = s_scal[1];
-  if (tid < R) {
-    const double e = 1.0 / (beta / s_d[tid] + 1.0);                   // eq. etii
-    s_ise[tid] = 1.0 / sqrt(e);
-    s_dr[tid] = s_d[tid] + rho;
+  for (int i = tid; i < R; i += nt) {
+    const double e = 1.0 / (beta / s_d[i] + 1.0);                     // eq. etii
+    s_ise[i] = 1.0 / sqrt(e);
+    s_dr[i] = s_d[i] + rho;
   }
   __syncthreads();
 
-  // Z_t from K_t and L_t (eq. zt:compute), symmetrised; U = I
+  // Z_t from K_t and L_t (eq. zt:compute), symmetrised
   const double ck = (eta / N) * (eta / N), cl = eta * (1.0 - eta) / N;
+  double zmax = 0.0;
   for (int idx = tid; idx < R * R; idx += nt) {
     const int i = idx / R, j = idx % R;
+    if (i > j) continue;
     const double kij = 0.5 * (a.K[i * R + j] + a.K[j * R + i]);
     const double lij = 0.5 * (a.L[i * R + j] + a.L[j * R + i]);
     double z = (ck * kij + cl * lij * (s_dr[i] + s_dr[j])) * s_ise[i] * s_ise[j];
-    if (i == j) z += (1.0 - eta) * (1.0 - eta) * s_dr[i] * s_dr[i];
+    if (i == j) {
+      z += (1.0 - eta) * (1.0 - eta) * s_dr[i] * s_dr[i];
+      zmax = fmax(zmax, z);
+    }
     Z[i * Rs + j] = z;
-    U[i * Rs + j] = i == j ? 1.0 : 0.0;
   }
-  __syncthreads();
+  zmax = block_max(zmax, scratch);
+  const double abs_tol = kJacobiAbsTol * zmax;
+  const double abs_tol2 = abs_tol * abs_tol;
 
-  // cyclic Jacobi, Z = U C U^T; a sweep in which no pair needed a rotation ends the iteration
-  double zmax = 0.0;
-  for (int i = tid; i < R; i += nt) zmax = fmax(zmax, Z[i * Rs + i]);
-  const double abs_tol = kJacobiAbsTol * block_max(zmax, scratch);
+  // the blocks (bi <= bj) this thread owns, and the players of their two pairs
   const int m = (R + 1) & ~1;
   const int half = m / 2;
-  int sweeps = 0;
+  const int n_blocks = half * (half + 1) / 2;
+  int blk_i[kEigItems], blk_j[kEigItems];
+  PairPlayers pli[kEigItems], plj[kEigItems];
+#pragma unroll
+  for (int it = 0; it < kEigItems; ++it) {
+    const int item = tid + it * nt;
+    int bj = 0, rem = item < n_blocks ? item : 0;
+    while (rem > bj) {   // item = bj (bj + 1) / 2 + bi
+      rem -= bj + 1;
+      ++bj;
+    }
+    blk_i[it] = rem;
+    blk_j[it] = bj;
+    pli[it].init(m, rem);
+    plj[it].init(m, bj);
+  }
+  PairPlayers mine;   // wave 0: the pair whose rotation this lane computes
+  mine.init(m, tid < half ? tid : 0);
+  if (tid == 0) s_rotated = 0;
+  __syncthreads();
+
+  // cyclic Jacobi; a sweep in which no pair needed a rotation ends the iteration
+  int sweeps = 0, rounds = 0;
   bool converged = false;
-  for (; sweeps < kMaxSweeps; ++sweeps) {
-    if (tid == 0) s_rotations = 0;
-    __syncthreads();
-    for (int r = 0; r < m - 1; ++r) {
+  for (; sweeps < kMaxSweeps && !converged; ++sweeps) {
+    for (int r = 0; r < m - 1; ++r, ++rounds) {
       if (tid < half) {
-        int p, q;
-        round_robin_pair(m, r, tid, p, q);
+        const int p = mine.p(), q = mine.q();
         double c = 1.0, s = 0.0;
-        if (q < R && sym_schur2(Z[p * Rs + p], Z[q * Rs + q], Z[p * Rs + q], c, s, abs_tol))
-          atomicAdd(&s_rotations, 1);
-        s_p[tid] = p;
-        s_q[tid] = q;
-        s_cs[tid] = c;
-        s_sn[tid] = s;
+        if (q < R && jacobi_rotation(Z[p * Rs + p], Z[q * Rs + q], Z[p * Rs + q], abs_tol2, c, s)) s_rotated = 1;
+        const double2 cs = make_double2(c, s);
+        s_rot[tid] = cs;
+        a.rotlog[(size_t)rounds * half + tid] = cs;
+        mine.advance(m);
       }
       __syncthreads();
-      for (int blk = tid; blk < half * half; blk += nt) {
-        const int bi = blk / half, bj = blk % half;
-        const int pi = s_p[bi], qi = s_q[bi], pj = s_p[bj], qj = s_q[bj];
-        if (s_sn[bi] == 0.0 && s_sn[bj] == 0.0) continue;   // both rotations are the identity
-        if (qi >= R || qj >= R) {
-          // a pair with the padding index: only the real member's row/column takes part
-          if (qi >= R && qj >= R) continue;
-          if (qi >= R) {        // row pi unchanged by the row rotation; apply column rotation of pair bj
-            const double cj = s_cs[bj], sj = s_sn[bj];
-            const double x0 = Z[pi * Rs + pj], x1 = Z[pi * Rs + qj];
-            Z[pi * Rs + pj] = x0 * cj - x1 * sj;
-            Z[pi * Rs + qj] = x0 * sj + x1 * cj;
-          } else {              // column pj unchanged; apply row rotation of pair bi
-            const double ci = s_cs[bi], si = s_sn[bi];
-            const double x0 = Z[pi * Rs + pj], x1 = Z[qi * Rs + pj];
-            Z[pi * Rs + pj] = ci * x0 - si * x1;
-            Z[qi * Rs + pj] = si * x0 + ci * x1;
-          }
+#pragma unroll
+      for (int it = 0; it < kEigItems; ++it) {
+        const int item = tid + it * nt;
+        const int bi = blk_i[it], bj = blk_j[it];
+        const int pi = pli[it].p(), qi = pli[it].q(), pj = plj[it].p(), qj = plj[it].q();
+        pli[it].advance(m);
+        plj[it].advance(m);
+        if (item >= n_blocks) continue;
+        const double2 ri = s_rot[bi], rj = s_rot[bj];
+        if (ri.y == 0.0 && rj.y == 0.0) continue;            // both rotations are the identity
+        const double ci = ri.x, si = ri.y, cj = rj.x, sj = rj.y;
+        if (bi == bj) {                                       // the rotated pair itself: (p,p), (q,q), (p,q)
+          if (qi >= R) continue;
+          const double app = Z[pi * Rs + pi], aqq = Z[qi * Rs + qi], apq = Z[pi * Rs + qi];
+          Z[pi * Rs + pi] = ci * ci * app - 2.0 * ci * si * apq + si * si * aqq;
+          Z[qi * Rs + qi] = si * si * app + 2.0 * ci * si * apq + ci * ci * aqq;
+          Z[pi * Rs + qi] = 0.0;
           continue;
         }
-        const double ci = s_cs[bi], si = s_sn[bi], cj = s_cs[bj], sj = s_sn[bj];
-        const double x00 = Z[pi * Rs + pj], x01 = Z[pi * Rs + qj];
-        const double x10 = Z[qi * Rs + pj], x11 = Z[qi * Rs + qj];
+        // canonical (row <= col) addresses of the four entries; a padding index (odd R) has no entries
+        const bool ri_ok = qi < R, rj_ok = qj < R;
+        const int a00 = pi < pj ? pi * Rs + pj : pj * Rs + pi;
+        const int a01 = pi < qj ? pi * Rs + qj : qj * Rs + pi;
+        const int a10 = qi < pj ? qi * Rs + pj : pj * Rs + qi;
+        const int a11 = qi < qj ? qi * Rs + qj : qj * Rs + qi;
+        const double x00 = Z[a00];
+        const double x01 = rj_ok ? Z[a01] : 0.0;
+        const double x10 = ri_ok ? Z[a10] : 0.0;
+        const double x11 = (ri_ok && rj_ok) ? Z[a11] : 0.0;
         const double y00 = ci * x00 - si * x10, y01 = ci * x01 - si * x11;
         const double y10 = si * x00 + ci * x10, y11 = si * x01 + ci * x11;
-        double b00 = y00 * cj - y01 * sj, b01 = y00 * sj + y01 * cj;
-        double b10 = y10 * cj - y11 * sj, b11 = y10 * sj + y11 * cj;
-        if (bi == bj) b01 = b10 = 0.0;      // the rotated pair itself is annihilated exactly
-        Z[pi * Rs + pj] = b00;
-        Z[pi * Rs + qj] = b01;
-        Z[qi * Rs + pj] = b10;
-        Z[qi * Rs + qj] = b11;
-      }
-      for (int idx = tid; idx < R * half; idx += nt) {
-        const int row = idx / half, bj = idx % half;
-        const int pj = s_p[bj], qj = s_q[bj];
-        const double cj = s_cs[bj], sj = s_sn[bj];
-        if (qj >= R || sj == 0.0) continue;
-        const double u0 = U[row * Rs + pj], u1 = U[row * Rs + qj];
-        U[row * Rs + pj] = u0 * cj - u1 * sj;
-        U[row * Rs + qj] = u0 * sj + u1 * cj;
+        Z[a00] = y00 * cj - y01 * sj;
+        if (rj_ok) Z[a01] = y00 * sj + y01 * cj;
+        if (ri_ok) Z[a10] = y10 * cj - y11 * sj;
+        if (ri_ok && rj_ok) Z[a11] = y10 * sj + y11 * cj;
       }
       __syncthreads();
     }
-    if (s_rotations == 0) {   // same value for every thread: read after the round's closing barrier
-      converged = true;
-      ++sweeps;
-      break;
-    }
-    __syncthreads();          // everyone has read the counter before it is cleared again
+    if (s_rotated == 0) converged = true;   // same value for every thread: read after the round's closing barrier
+    __syncthreads();                        // everyone has read the flag before it is cleared again
+    if (tid == 0) s_rotated = 0;
   }
 
   // eigenvalues, floor (after eq. zt:eig:repeat), decreasing order
   const double floor_c = (1.0 - eta) * (1.0 - eta) * rho * rho;
   if (tid == 0) s_flag[0] = 0;
   __syncthreads();
-  if (tid < R) {
-    double c = Z[tid * Rs + tid];
+  for (int i = tid; i < R; i += nt) {
+    double c = Z[i * Rs + i];
     if (!(c >= floor_c)) {
       c = floor_c;
-      atomicOr(&s_flag[0], 1);
+      s_flag[0] = 1;
     }
-    s_c[tid] = c;
+    s_c[i] = c;
   }
   __syncthreads();
-  if (tid < R) {
+  for (int i = tid; i < R; i += nt) {
     int rank = 0;
-    const double c = s_c[tid];
-    for (int j = 0; j < R; ++j) rank += (s_c[j] > c || (s_c[j] == c && j < tid)) ? 1 : 0;
-    s_perm[rank] = tid;   // s_perm[k] = index of the k-th largest eigenvalue
+    const double c = s_c[i];
+    for (int j = 0; j < R; ++j) rank += (s_c[j] > c || (s_c[j] == c && j < i)) ? 1 : 0;
+    s_perm[rank] = i;   // s_perm[k] = index of the k-th largest eigenvalue
+    a.work->rank_of[i] = rank;
   }
   __syncthreads();
   if (tid == 0) {
@@ -237,30 +320,95 @@ __global__ __launch_bounds__(kSmallThreads) void small_update_kernel(const Small
     st->sweeps = sweeps;
     st->rho = rho_new;
     st->beta = beta_new;
+    a.work->n_rounds = rounds;
   }
   __syncthreads();
   const double beta_new = s_scal[3];
-  double en = 0.0;
-  if (tid < R) {
-    const double dn = s_enew[tid];
-    en = 1.0 / (beta_new / dn + 1.0);
-    st->d[tid] = dn;
-    st->e[tid] = en;
-  }
-  __syncthreads();
-  if (tid < R) s_enew[tid] = en;   // from here on e_{t+1}
-  __syncthreads();
-  // A_t = (eta/N) E_{t+1}^{1/2} C_t^{-1/2} U_t^T E_t^{-1/2}   (eq. wt1), rows in decreasing-eigenvalue order
-  for (int idx = tid; idx < R * a.ldat; idx += nt) {
-    const int k = idx / a.ldat, j = idx % a.ldat;
-    float v = 0.f;
-    if (j < R) {
-      const int src = s_perm[k];
-      v = (float)((eta / N) * sqrt(s_enew[k] / s_c[src]) * U[j * Rs + src] * s_ise[j]);
-    }
-    a.At[(size_t)k * a.ldat + j] = v;
+  for (int k = tid; k < R; k += nt) {
+    const double dn = s_enew[k];
+    const double en = 1.0 / (beta_new / dn + 1.0);
+    st->d[k] = dn;
+    st->e[k] = en;
+    // A_t = (eta/N) E_{t+1}^{1/2} C_t^{-1/2} U_t^T E_t^{-1/2}  (eq. wt1): scale of row k / eigenpair s_perm[k]
+    a.work->colscale[s_perm[k]] = (eta / N) * sqrt(en / s_c[s_perm[k]]);
+    a.work->rowscale[k] = s_ise[k];
   }
   for (int idx = tid; idx < R * R; idx += nt) a.K[idx] = 0.0;
+}
+
+// U_t by replaying the rotation log on rows of the identity, then A_t (eq. wt1).  U <- U J only mixes two
+// columns, so rows are independent: each wavefront owns one row and keeps it in registers.  Lane k holds the two
+// columns that pair k rotates; between rounds the columns move to the neighbouring lanes exactly as the players
+// of the round-robin schedule do (the first lane's second player never moves).  The log is staged through LDS
+// in chunks of kEigvecChunk rounds, the next chunk being fetched while the current one is replayed.
+__global__ __launch_bounds__(kEigvecThreads) void eigvec_kernel(const SmallGroup g) {
+  __shared__ double2 s_log[2][kEigvecChunk * kMaxHalf];
+  const SmallArgs& a = g.a[blockIdx.x];
+  const int R = a.R;
+  const int m = (R + 1) & ~1, half = m / 2;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int row = blockIdx.y * (kEigvecThreads / 64) + wave;   // rows >= R idle along (they share the barriers)
+  const int n_rounds = a.work->n_rounds;
+  const bool active = lane < half;
+  // players held by this lane in round 0: first k, second m-1-k (lane 0: the fixed player m-1)
+  int tp = lane, bp = m - 1 - lane;
+  double top = (active && tp == row) ? 1.0 : 0.0;
+  double bot = (active && bp == row) ? 1.0 : 0.0;
+
+  constexpr int kLoads = (kEigvecChunk * kMaxHalf + kEigvecThreads - 1) / kEigvecThreads;
+  const int chunk_elems = kEigvecChunk * half;   // the log is padded to whole chunks
+  double2 stage[kLoads];
+#pragma unroll
+  for (int u = 0; u < kLoads; ++u) {
+    const int e = tid + u * kEigvecThreads;
+    if (e < chunk_elems) s_log[0][e] = a.rotlog[e];
+  }
+  __syncthreads();
+  for (int base = 0, buf = 0; base < n_rounds; base += kEigvecChunk, buf ^= 1) {
+    const bool more = base + kEigvecChunk < n_rounds;
+    if (more) {
+#pragma unroll
+      for (int u = 0; u < kLoads; ++u) {
+        const int e = tid + u * kEigvecThreads;
+        if (e < chunk_elems) stage[u] = a.rotlog[(size_t)(base + kEigvecChunk) * half + e];
+      }
+    }
+    const int len = min(kEigvecChunk, n_rounds - base);
+    const double2* lg = s_log[buf];
+    for (int rr = 0; rr < len; ++rr) {
+      const double2 cs = active ? lg[rr * half + lane] : make_double2(1.0, 0.0);
+      const double c = cs.x, s = cs.y;
+      const bool top_is_p = tp < bp;     // the logged rotation acts on (p, q) with p < q
+      const double up = top_is_p ? top : bot, uq = top_is_p ? bot : top;
+      const double np = up * c - uq * s, nq = up * s + uq * c;
+      top = top_is_p ? np : nq;
+      bot = top_is_p ? nq : np;
+      // players move: firsts shift one lane down (the last lane takes its own second), seconds shift one lane
+      // up (lane 1 takes lane 0's first); lane 0's second is fixed
+      if (m > 2) {
+        const double t_dn = __shfl_down(top, 1);
+        const double b_up = __shfl_up(bot, 1);
+        const double t0 = __shfl(top, 0);
+        top = lane == half - 1 ? bot : t_dn;
+        bot = lane == 0 ? bot : (lane == 1 ? t0 : b_up);
+        tp = tp + 1 == m - 1 ? 0 : tp + 1;
+        if (lane != 0) bp = bp + 1 == m - 1 ? 0 : bp + 1;
+      }
+    }
+    if (more) {
+#pragma unroll
+      for (int u = 0; u < kLoads; ++u) {
+        const int e = tid + u * kEigvecThreads;
+        if (e < chunk_elems) s_log[buf ^ 1][e] = stage[u];
+      }
+    }
+    __syncthreads();
+  }
+  if (!active || row >= R) return;
+  const int j = row;   // row of U = column of A_t
+  const double rs = a.work->rowscale[j];
+  if (tp < R) a.At[(size_t)a.work->rank_of[tp] * a.ldat + j] = (float)(a.work->colscale[tp] * top * rs);
+  if (bp < R) a.At[(size_t)a.work->rank_of[bp] * a.ldat + j] = (float)(a.work->colscale[bp] * bot * rs);
 }
 
 // App. B.3.1 on the new factor: O = E^{-1/2} (W W^T) E^{-1/2}; if any entry is off the identity by more than
