@@ -110,6 +110,12 @@ int ngsgd_precondition(ngsgd_precond* p, float* dev_M, int32_t N, int32_t ld, fl
 int ngsgd_precond_get_state(const ngsgd_precond* p, float* dev_W, double* dev_d, double* dev_rho,
                             int64_t* t_host, void* hip_stream);
 
+/* Diagnostics of the latest factor update, copied to HOST memory after waiting for the stream:
+ * flags (bit 0: orthogonality check still pending, 1: an eigenvalue of Z_t was floored, 2: the factor was
+ * re-orthogonalised (App. B.3.1), 3: the eigen-solver hit its sweep limit) and the Jacobi sweeps it used. */
+int ngsgd_precond_diagnostics(const ngsgd_precond* p, int32_t* flags_host, int32_t* sweeps_host,
+                              void* hip_stream);
+
 /* Installs a state given in the definitional form of App. B.1: dev_R (rank x dim doubles, dense,
  * orthonormal rows), dev_d (rank doubles > 0), rho > 0, and the call counter t >= 1.
  * W_t = E_t^{1/2} R_t is formed on the device (eq. beta2, etii, wt:def). */

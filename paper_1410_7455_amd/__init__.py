@@ -54,6 +54,7 @@ _SIGNATURES = {
     "ngsgd_precond_reset": (c_int, [c_void_p]),
     "ngsgd_precondition": (c_int, [c_void_p, c_void_p, c_int32, c_int32, c_void_p, c_void_p, c_void_p]),
     "ngsgd_precond_get_state": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, POINTER(c_int64), c_void_p]),
+    "ngsgd_precond_diagnostics": (c_int, [c_void_p, POINTER(c_int32), POINTER(c_int32), c_void_p]),
     "ngsgd_precond_set_state": (c_int, [c_void_p, c_void_p, c_void_p, c_double, c_int64, c_void_p]),
     "ngsgd_workspace_bytes": (c_int, [POINTER(ngsgd_config), POINTER(c_size_t)]),
     "ngsgd_create": (c_int, [POINTER(ngsgd_config), c_void_p, c_size_t, POINTER(c_void_p)]),
@@ -162,6 +163,13 @@ class Preconditioner:
                                                 _stream_ptr()), "ngsgd_precond_get_state")
         torch.cuda.synchronize()
         return W, d, float(rho.item()), t.value
+
+    def diagnostics(self):
+        """(flags, Jacobi sweeps) of the latest factor update; waits for the stream."""
+        flags, sweeps = c_int32(0), c_int32(0)
+        _check(self.lib.ngsgd_precond_diagnostics(self.handle, byref(flags), byref(sweeps), _stream_ptr()),
+               "ngsgd_precond_diagnostics")
+        return flags.value, sweeps.value
 
     def set_state(self, R, d, rho, t):
         """R: rank x dim float64 CUDA tensor with orthonormal rows, d: rank float64, rho > 0, t >= 1."""

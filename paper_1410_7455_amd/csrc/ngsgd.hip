@@ -203,8 +203,10 @@ bool g_attr_done = false;
 int ensure_kernel_attributes() {
   if (g_attr_done) return NGSGD_OK;
   const int max_dyn = 2 * kMaxRank * (kMaxRank | 1) * (int)sizeof(double);
-  HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(eig_update_kernel),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, max_dyn / 2));
+  HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(eig_update_kernel<1>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, max_dyn));
+  HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(eig_update_kernel<2>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, max_dyn));
   HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(orth_fix_kernel),
                               hipFuncAttributeMaxDynamicSharedMemorySize, max_dyn));
   g_attr_done = true;
@@ -596,8 +598,16 @@ int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStr
       const size_t dyn = (size_t)2 * r_max * (r_max | 1) * sizeof(double);
       {
         ProfScope prof(NGSGD_PROF_PRECOND_SMALL, s);
-        hipLaunchKernelGGL(eig_update_kernel, dim3(n), dim3(kEigThreads), dyn / 2, s, g);
-        LAUNCH_CHECK();
+        {
+          const int m_max = (r_max + 1) & ~1;
+          const size_t eig_dyn = (size_t)2 * m_max * (m_max | 1) * sizeof(double);
+          if ((m_max / 2) * (m_max / 2 + 1) / 2 <= kEigThreads) {
+            hipLaunchKernelGGL(eig_update_kernel<1>, dim3(n), dim3(kEigThreads), eig_dyn, s, g);
+          } else {
+            hipLaunchKernelGGL(eig_update_kernel<2>, dim3(n), dim3(kEigThreads), eig_dyn, s, g);
+          }
+          LAUNCH_CHECK();
+        }
         const int rows_per_block = kEigvecThreads / 64;
         hipLaunchKernelGGL(eigvec_kernel, dim3(n, (r_max + rows_per_block - 1) / rows_per_block), dim3(kEigvecThreads),
                            0, s, g);
@@ -742,6 +752,21 @@ extern "C" int ngsgd_precond_get_state(const ngsgd_precond* p, float* dev_W, dou
     HIP_TRY(hipMemcpyAsync(dev_d, p->st->d, (size_t)p->rank * sizeof(double), hipMemcpyDeviceToDevice, s));
   if (dev_rho != nullptr)
     HIP_TRY(hipMemcpyAsync(dev_rho, &p->st->rho, sizeof(double), hipMemcpyDeviceToDevice, s));
+  return NGSGD_OK;
+}
+
+extern "C" int ngsgd_precond_diagnostics(const ngsgd_precond* p, int32_t* flags_host, int32_t* sweeps_host,
+                                         void* hip_stream) {
+  if (p == nullptr) return NGSGD_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  NG_TRY(join_side(p->sync, s));
+  int v[2] = {0, 0};
+  if (p->rank > 0) {
+    HIP_TRY(hipMemcpyAsync(v, &p->st->flags, sizeof(v), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+  }
+  if (flags_host != nullptr) *flags_host = v[0];
+  if (sweeps_host != nullptr) *sweeps_host = v[1];
   return NGSGD_OK;
 }
 

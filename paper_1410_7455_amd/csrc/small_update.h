@@ -16,7 +16,7 @@ namespace ngsgd {
 
 constexpr int kSmallThreads = 1024;          // orthogonality fix kernel
 constexpr int kEigThreads = 1024;            // R x R eigen-update kernel
-constexpr int kEigItems = (kMaxRank / 2 * (kMaxRank / 2 + 1) / 2 + kEigThreads - 1) / kEigThreads;   // blocks per thread
+
 constexpr int kEigvecThreads = 256;          // eigenvector kernel: 4 wavefronts, one row of U each
 constexpr int kEigvecChunk = 32;             // rounds of the rotation log staged in LDS at a time
 constexpr int kMaxSweeps = 20;
@@ -114,33 +114,40 @@ __device__ __forceinline__ void round_robin_pair(int m, int r, int k, int& p, in
   }
 }
 
-// Players of pair k in round r of the round-robin schedule, unsorted: first (r+k) mod (m-1), second
-// (r-k) mod (m-1), except that pair 0's second is the fixed player m-1.  Tracked incrementally per thread.
-struct PairPlayers {
-  int first, second;
-  bool fixed;   // pair 0: `second` never moves
-  __device__ __forceinline__ void init(int m, int k) {
-    first = k;
-    second = m - 1 - k;
-    fixed = k == 0;
-  }
-  __device__ __forceinline__ void advance(int m) {
-    first = first + 1 == m - 1 ? 0 : first + 1;
-    if (!fixed) second = second + 1 == m - 1 ? 0 : second + 1;
-  }
-  __device__ __forceinline__ int p() const { return first < second ? first : second; }
-  __device__ __forceinline__ int q() const { return first < second ? second : first; }
-};
+// The Jacobi iteration works in "position space" (Brent-Luk): position 2k is the first and 2k+1 the second
+// member of pair k, rotations always act on (2k, 2k+1), and after every round the matrix is permuted so that the
+// next round's partners sit together again.  The permutation is the same every round,
+//   first_k -> first_{k-1} (k >= 1),  first_0 -> second_1,  second_k -> second_{k+1} (1 <= k < half-1),
+//   second_{half-1} -> first_{half-1},  second_0 stays,
+// which is the circle method of a round-robin tournament with `second_0` as the fixed player: over m-1 rounds
+// every two players meet once.  Because it is fixed, every thread reads and writes the same LDS addresses in
+// every round and needs no index arithmetic in the loop.
+__device__ __forceinline__ int next_position(int pos, int half) {
+  if (half == 1) return pos;
+  const int k = pos >> 1;
+  if ((pos & 1) == 0) return k >= 1 ? 2 * (k - 1) : 3;          // first members
+  if (k == 0) return 1;                                          // the fixed player
+  return k == half - 1 ? 2 * (half - 1) : 2 * (k + 1) + 1;       // second members
+}
+// Player standing at `pos` after `rounds` rounds; players m-1-k start as second members, m-1 is the fixed one.
+__device__ __forceinline__ int player_at(int pos, int rounds, int m) {
+  const int k = pos >> 1;
+  if (m == 2) return pos;
+  const int r = rounds % (m - 1);
+  if ((pos & 1) == 0) return (r + k) % (m - 1);
+  return k == 0 ? m - 1 : (r - k + (m - 1)) % (m - 1);
+}
 
 // Z_t (eq. zt:compute), its eigenvalues by cyclic Jacobi, then rho_{t+1}, D_{t+1}, E_{t+1} (eq. rhodash2, dt1,
-// rhot1, beta2, etii).  One workgroup per instance.  Only Z is rotated here (upper triangle, in LDS): every
-// rotation is logged, and the eigenvector kernel replays the log on the rows of the identity.  A round is:
-// wave 0 computes the floor(R/2) rotations | barrier | every thread updates at most kEigItems 2x2 blocks whose
-// addresses it tracks in registers | barrier.
+// rhot1, beta2, etii).  One workgroup per instance.  Only Z is rotated here (upper triangle in position space,
+// two LDS copies used alternately); every rotation is logged, and the eigenvector kernel replays the log on the
+// rows of the identity.  A round is: wave 0 computes the half rotations | barrier | every thread rotates its
+// 2x2 blocks from one copy into their next positions in the other copy | barrier.
+template <int ITEMS>
 __global__ __launch_bounds__(kEigThreads) void eig_update_kernel(const SmallGroup g) {
-  extern __shared__ __attribute__((aligned(16))) double dyn[];   // Z, R x Rs, entries (i <= j) are live
+  extern __shared__ __attribute__((aligned(16))) double dyn[];   // two copies of Z, m x ms, entries (a <= b) live
   __shared__ double scratch[16];
-  __shared__ double s_d[kMaxRank], s_ise[kMaxRank], s_dr[kMaxRank], s_c[kMaxRank], s_enew[kMaxRank];
+  __shared__ double s_d[kMaxRank], s_ise[kMaxRank], s_dr[kMaxRank], s_c[kMaxRank + 1], s_enew[kMaxRank];
   __shared__ double2 s_rot[kMaxHalf];
   __shared__ int s_perm[kMaxRank];
   __shared__ double s_scal[8];
@@ -151,8 +158,10 @@ __global__ __launch_bounds__(kEigThreads) void eig_update_kernel(const SmallGrou
   const int R = a.R, D = a.D, N = a.N;
   const int tid = threadIdx.x;
   constexpr int nt = kEigThreads;
-  const int Rs = R | 1;
-  double* Z = dyn;
+  const int m = (R + 1) & ~1;
+  const int half = m / 2;
+  const int ms = m;   // even row stride: the two entries (a, 2k), (a, 2k+1) of a block row are one aligned 16 bytes
+  const int zcopy = m * ms;   // offset of the second copy (offsets, not pointers: the accesses stay LDS instructions)
   PrecondScalars* st = a.st;
 
   const double eta = 1.0 - exp(-(double)N / g.num_samples_history);   // eq. eta:ns
@@ -174,99 +183,98 @@ __global__ __launch_bounds__(kEigThreads) void eig_update_kernel(const SmallGrou
   }
   __syncthreads();
 
-  // Z_t from K_t and L_t (eq. zt:compute), symmetrised
+  // Z_t from K_t and L_t (eq. zt:compute), symmetrised, laid out by position; the padding player of an odd R has
+  // an all-zero row and column and is never rotated
   const double ck = (eta / N) * (eta / N), cl = eta * (1.0 - eta) / N;
   double zmax = 0.0;
-  for (int idx = tid; idx < R * R; idx += nt) {
-    const int i = idx / R, j = idx % R;
-    if (i > j) continue;
-    const double kij = 0.5 * (a.K[i * R + j] + a.K[j * R + i]);
-    const double lij = 0.5 * (a.L[i * R + j] + a.L[j * R + i]);
-    double z = (ck * kij + cl * lij * (s_dr[i] + s_dr[j])) * s_ise[i] * s_ise[j];
-    if (i == j) {
-      z += (1.0 - eta) * (1.0 - eta) * s_dr[i] * s_dr[i];
-      zmax = fmax(zmax, z);
+  for (int idx = tid; idx < m * m; idx += nt) {
+    const int pa = idx / m, pb = idx % m;
+    if (pa > pb) continue;
+    const int i = player_at(pa, 0, m), j = player_at(pb, 0, m);
+    double z = 0.0;
+    if (i < R && j < R) {
+      const double kij = 0.5 * (a.K[i * R + j] + a.K[j * R + i]);
+      const double lij = 0.5 * (a.L[i * R + j] + a.L[j * R + i]);
+      z = (ck * kij + cl * lij * (s_dr[i] + s_dr[j])) * s_ise[i] * s_ise[j];
+      if (i == j) {
+        z += (1.0 - eta) * (1.0 - eta) * s_dr[i] * s_dr[i];
+        zmax = fmax(zmax, z);
+      }
     }
-    Z[i * Rs + j] = z;
+    dyn[pa * ms + pb] = z;
   }
   zmax = block_max(zmax, scratch);
   const double abs_tol = kJacobiAbsTol * zmax;
   const double abs_tol2 = abs_tol * abs_tol;
 
-  // the blocks (bi <= bj) this thread owns, and the players of their two pairs
-  const int m = (R + 1) & ~1;
-  const int half = m / 2;
+  // the blocks (bi <= bj) this thread owns, numbered row by row so that neighbouring lanes read neighbouring
+  // 16-byte pieces: fixed source rows (two double2 loads) and destination offsets of their four entries
   const int n_blocks = half * (half + 1) / 2;
-  int blk_i[kEigItems], blk_j[kEigItems];
-  PairPlayers pli[kEigItems], plj[kEigItems];
+  int blk_i[ITEMS], blk_j[ITEMS];
+  int src[ITEMS][2], dst[ITEMS][4];
 #pragma unroll
-  for (int it = 0; it < kEigItems; ++it) {
+  for (int it = 0; it < ITEMS; ++it) {
     const int item = tid + it * nt;
-    int bj = 0, rem = item < n_blocks ? item : 0;
-    while (rem > bj) {   // item = bj (bj + 1) / 2 + bi
-      rem -= bj + 1;
-      ++bj;
+    int bi = 0, rem = item < n_blocks ? item : 0;
+    while (rem >= half - bi) {   // row bi holds the blocks (bi, bi), (bi, bi+1), ..., (bi, half-1)
+      rem -= half - bi;
+      ++bi;
     }
-    blk_i[it] = rem;
+    const int bj = bi + rem;
+    blk_i[it] = bi;
     blk_j[it] = bj;
-    pli[it].init(m, rem);
-    plj[it].init(m, bj);
+    src[it][0] = (2 * bi) * ms + 2 * bj;
+    src[it][1] = (2 * bi + 1) * ms + 2 * bj;   // its first entry lies below the diagonal when bi == bj: ignored
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int na = next_position(2 * bi + (e >> 1), half), nb = next_position(2 * bj + (e & 1), half);
+      dst[it][e] = na <= nb ? na * ms + nb : nb * ms + na;
+    }
   }
-  PairPlayers mine;   // wave 0: the pair whose rotation this lane computes
-  mine.init(m, tid < half ? tid : 0);
+  const bool odd_pad = (R & 1) != 0;   // pair 0 then holds the padding player
   if (tid == 0) s_rotated = 0;
   __syncthreads();
 
   // cyclic Jacobi; a sweep in which no pair needed a rotation ends the iteration
-  int sweeps = 0, rounds = 0;
+  int sweeps = 0, rounds = 0, cur = 0;
   bool converged = false;
   for (; sweeps < kMaxSweeps && !converged; ++sweeps) {
-    for (int r = 0; r < m - 1; ++r, ++rounds) {
+    for (int r = 0; r < m - 1; ++r, ++rounds, cur ^= 1) {
+      const int co = cur ? zcopy : 0, no = cur ? 0 : zcopy;
       if (tid < half) {
-        const int p = mine.p(), q = mine.q();
+        const int pt = 2 * tid, pb = 2 * tid + 1;
         double c = 1.0, s = 0.0;
-        if (q < R && jacobi_rotation(Z[p * Rs + p], Z[q * Rs + q], Z[p * Rs + q], abs_tol2, c, s)) s_rotated = 1;
+        if (!(odd_pad && tid == 0) &&
+            jacobi_rotation(dyn[co + pt * ms + pt], dyn[co + pb * ms + pb], dyn[co + pt * ms + pb], abs_tol2, c, s))
+          s_rotated = 1;
         const double2 cs = make_double2(c, s);
         s_rot[tid] = cs;
         a.rotlog[(size_t)rounds * half + tid] = cs;
-        mine.advance(m);
       }
       __syncthreads();
 #pragma unroll
-      for (int it = 0; it < kEigItems; ++it) {
-        const int item = tid + it * nt;
+      for (int it = 0; it < ITEMS; ++it) {
+        if (ITEMS > 1 && tid + it * nt >= n_blocks) continue;
+        if (ITEMS == 1 && tid >= n_blocks) continue;
         const int bi = blk_i[it], bj = blk_j[it];
-        const int pi = pli[it].p(), qi = pli[it].q(), pj = plj[it].p(), qj = plj[it].q();
-        pli[it].advance(m);
-        plj[it].advance(m);
-        if (item >= n_blocks) continue;
         const double2 ri = s_rot[bi], rj = s_rot[bj];
-        if (ri.y == 0.0 && rj.y == 0.0) continue;            // both rotations are the identity
         const double ci = ri.x, si = ri.y, cj = rj.x, sj = rj.y;
-        if (bi == bj) {                                       // the rotated pair itself: (p,p), (q,q), (p,q)
-          if (qi >= R) continue;
-          const double app = Z[pi * Rs + pi], aqq = Z[qi * Rs + qi], apq = Z[pi * Rs + qi];
-          Z[pi * Rs + pi] = ci * ci * app - 2.0 * ci * si * apq + si * si * aqq;
-          Z[qi * Rs + qi] = si * si * app + 2.0 * ci * si * apq + ci * ci * aqq;
-          Z[pi * Rs + qi] = 0.0;
+        const double2 row0 = *reinterpret_cast<const double2*>(&dyn[co + src[it][0]]);
+        const double2 row1 = *reinterpret_cast<const double2*>(&dyn[co + src[it][1]]);
+        if (bi == bj) {   // the rotated pair itself: entries (t,t), (t,b), (b,b)
+          const double att = row0.x, atb = row0.y, abb = row1.y;
+          dyn[no + dst[it][0]] = ci * ci * att - 2.0 * ci * si * atb + si * si * abb;
+          dyn[no + dst[it][3]] = si * si * att + 2.0 * ci * si * atb + ci * ci * abb;
+          dyn[no + dst[it][1]] = si == 0.0 ? atb : 0.0;
           continue;
         }
-        // canonical (row <= col) addresses of the four entries; a padding index (odd R) has no entries
-        const bool ri_ok = qi < R, rj_ok = qj < R;
-        const int a00 = pi < pj ? pi * Rs + pj : pj * Rs + pi;
-        const int a01 = pi < qj ? pi * Rs + qj : qj * Rs + pi;
-        const int a10 = qi < pj ? qi * Rs + pj : pj * Rs + qi;
-        const int a11 = qi < qj ? qi * Rs + qj : qj * Rs + qi;
-        const double x00 = Z[a00];
-        const double x01 = rj_ok ? Z[a01] : 0.0;
-        const double x10 = ri_ok ? Z[a10] : 0.0;
-        const double x11 = (ri_ok && rj_ok) ? Z[a11] : 0.0;
+        const double x00 = row0.x, x01 = row0.y, x10 = row1.x, x11 = row1.y;
         const double y00 = ci * x00 - si * x10, y01 = ci * x01 - si * x11;
         const double y10 = si * x00 + ci * x10, y11 = si * x01 + ci * x11;
-        Z[a00] = y00 * cj - y01 * sj;
-        if (rj_ok) Z[a01] = y00 * sj + y01 * cj;
-        if (ri_ok) Z[a10] = y10 * cj - y11 * sj;
-        if (ri_ok && rj_ok) Z[a11] = y10 * sj + y11 * cj;
+        dyn[no + dst[it][0]] = y00 * cj - y01 * sj;
+        dyn[no + dst[it][1]] = y00 * sj + y01 * cj;
+        dyn[no + dst[it][2]] = y10 * cj - y11 * sj;
+        dyn[no + dst[it][3]] = y10 * sj + y11 * cj;
       }
       __syncthreads();
     }
@@ -275,12 +283,15 @@ __global__ __launch_bounds__(kEigThreads) void eig_update_kernel(const SmallGrou
     if (tid == 0) s_rotated = 0;
   }
 
-  // eigenvalues, floor (after eq. zt:eig:repeat), decreasing order
+  // eigenvalues (by player), floor (after eq. zt:eig:repeat), decreasing order
+  const int fo = cur ? zcopy : 0;
   const double floor_c = (1.0 - eta) * (1.0 - eta) * rho * rho;
   if (tid == 0) s_flag[0] = 0;
   __syncthreads();
-  for (int i = tid; i < R; i += nt) {
-    double c = Z[i * Rs + i];
+  for (int pos = tid; pos < m; pos += nt) {
+    const int i = player_at(pos, rounds, m);
+    if (i >= R) continue;
+    double c = dyn[fo + pos * ms + pos];
     if (!(c >= floor_c)) {
       c = floor_c;
       s_flag[0] = 1;
@@ -378,11 +389,10 @@ __global__ __launch_bounds__(kEigvecThreads) void eigvec_kernel(const SmallGroup
     for (int rr = 0; rr < len; ++rr) {
       const double2 cs = active ? lg[rr * half + lane] : make_double2(1.0, 0.0);
       const double c = cs.x, s = cs.y;
-      const bool top_is_p = tp < bp;     // the logged rotation acts on (p, q) with p < q
-      const double up = top_is_p ? top : bot, uq = top_is_p ? bot : top;
-      const double np = up * c - uq * s, nq = up * s + uq * c;
-      top = top_is_p ? np : nq;
-      bot = top_is_p ? nq : np;
+      // the logged rotation acts on (first, second) of the pair
+      const double nt_ = top * c - bot * s, nb_ = top * s + bot * c;
+      top = nt_;
+      bot = nb_;
       // players move: firsts shift one lane down (the last lane takes its own second), seconds shift one lane
       // up (lane 1 takes lane 0's first); lane 0's second is fixed
       if (m > 2) {
