@@ -203,9 +203,11 @@ bool g_attr_done = false;
 int ensure_kernel_attributes() {
   if (g_attr_done) return NGSGD_OK;
   const int max_dyn = 2 * kMaxRank * (kMaxRank | 1) * (int)sizeof(double);
-  HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(eig_update_kernel<1>),
+  HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(eig_update_kernel<1, kEigThreads>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, max_dyn));
-  HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(eig_update_kernel<2>),
+  HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(eig_update_kernel<2, kEigThreads>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, max_dyn));
+  HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(eig_update_kernel<kEigMaxItems, kEigThreads>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, max_dyn));
   HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(orth_fix_kernel),
                               hipFuncAttributeMaxDynamicSharedMemorySize, max_dyn));
@@ -600,11 +602,15 @@ int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStr
         ProfScope prof(NGSGD_PROF_PRECOND_SMALL, s);
         {
           const int m_max = (r_max + 1) & ~1;
-          const size_t eig_dyn = (size_t)2 * m_max * (m_max | 1) * sizeof(double);
-          if ((m_max / 2) * (m_max / 2 + 1) / 2 <= kEigThreads) {
-            hipLaunchKernelGGL(eig_update_kernel<1>, dim3(n), dim3(kEigThreads), eig_dyn, s, g);
+          const int n_blocks = (m_max / 2) * (m_max / 2 + 1) / 2;   // 2x2 blocks of the upper triangle
+          const size_t eig_dyn = (size_t)2 * 4 * n_blocks * sizeof(double);   // two copies of four planes
+          const int items = (n_blocks + kEigThreads - 1) / kEigThreads;
+          if (items <= 1) {
+            hipLaunchKernelGGL((eig_update_kernel<1, kEigThreads>), dim3(n), dim3(kEigThreads), eig_dyn, s, g);
+          } else if (items == 2) {
+            hipLaunchKernelGGL((eig_update_kernel<2, kEigThreads>), dim3(n), dim3(kEigThreads), eig_dyn, s, g);
           } else {
-            hipLaunchKernelGGL(eig_update_kernel<2>, dim3(n), dim3(kEigThreads), eig_dyn, s, g);
+            hipLaunchKernelGGL((eig_update_kernel<kEigMaxItems, kEigThreads>), dim3(n), dim3(kEigThreads), eig_dyn, s, g);
           }
           LAUNCH_CHECK();
         }

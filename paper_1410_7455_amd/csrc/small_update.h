@@ -15,15 +15,26 @@
 namespace ngsgd {
 
 constexpr int kSmallThreads = 1024;          // orthogonality fix kernel
-constexpr int kEigThreads = 1024;            // R x R eigen-update kernel
+#ifndef NGSGD_EIG_NT
+#define NGSGD_EIG_NT 1024
+#endif
+constexpr int kEigThreads = NGSGD_EIG_NT;    // R x R eigen-update kernel
+// most 2x2 blocks of the upper triangle one thread may own
+constexpr int kEigMaxItems = ((kMaxRank / 2) * (kMaxRank / 2 + 1) / 2 + kEigThreads - 1) / kEigThreads;
 
 constexpr int kEigvecThreads = 256;          // eigenvector kernel: 4 wavefronts, one row of U each
 constexpr int kEigvecChunk = 32;             // rounds of the rotation log staged in LDS at a time
 constexpr int kMaxSweeps = 20;
+#ifndef NGSGD_EIG_BLOCK_DELAY
+#define NGSGD_EIG_BLOCK_DELAY 2
+#endif
+constexpr int kEigBlockDelay = NGSGD_EIG_BLOCK_DELAY;   // in units of 64 clocks
 constexpr int kMaxHalf = kMaxRank / 2;
 constexpr int kMaxRounds = kMaxSweeps * (kMaxRank - 1);
 constexpr double kJacobiTol = 1.0e-13;       // a pair is left alone once |z_pq| <= tol * sqrt(z_pp z_qq)
 constexpr double kJacobiAbsTol = 1.0e-13;    // ... or once |z_pq| <= this * max_i z_ii (rounding noise level)
+constexpr double kJacobiLargeTol = 1.0e-6;   // a sweep without a rotated entry above this (same measure) ...
+constexpr double kJacobiLargeAbs = 1.0e3;    // ... and above this many absolute thresholds is the last
 constexpr double kOrthoCondLimit = 1.0e6;    // App. B.3.1
 constexpr double kOrthoTolerance = 1.0e-3;   // App. B.3.1
 
@@ -52,36 +63,44 @@ struct SmallGroup {
   SmallArgs a[kMaxInstances];
 };
 
-__device__ __forceinline__ double fast_rsqrt(double x) {
-  double y = __builtin_amdgcn_rsq(x);
-  y = y * (1.5 - 0.5 * x * y * y);
-  y = y * (1.5 - 0.5 * x * y * y);
-  return y;
-}
-__device__ __forceinline__ double fast_rcp(double x) {
-  double r = __builtin_amdgcn_rcp(x);
-  r = r * (2.0 - x * r);
-  r = r * (2.0 - x * r);
-  return r;
+// Coupled Newton (Goldschmidt) iteration from the hardware estimate: on return g = sqrt(x), h = 1 / (2 sqrt(x)).
+// Two dependent operations per step instead of the three of the plain Newton step for 1/sqrt.
+__device__ __forceinline__ void sqrt_pair(double x, double& g, double& h) {
+  const double y = __builtin_amdgcn_rsq(x);
+  g = x * y;
+  h = 0.5 * y;
+#pragma unroll
+  for (int it = 0; it < 2; ++it) {
+    const double e = fma(-g, h, 0.5);
+    g = fma(g, e, g);
+    h = fma(h, e, h);
+  }
 }
 
-// Rotation that diagonalises [[app, apq], [apq, aqq]] as J^T A J with J = [[c, s], [-s, c]].  Returns false (and
-// the identity) when the off-diagonal entry is already negligible: relative to the diagonal pair (that relative
-// test is what gives small eigenvalues of a graded positive definite matrix their relative accuracy) or in
-// absolute terms (abs_tol2 is the squared absolute threshold).  Division and square roots go through the
-// hardware reciprocal estimates plus Newton steps: the rotation sits on the critical path of every round.
+// Rotation that diagonalises [[app, apq], [apq, aqq]] as J^T A J with J = [[c, s], [-s, c]] (the inner rotation,
+// c >= 1/sqrt 2).  Returns false (and the identity) when the off-diagonal entry is already negligible: relative
+// to the diagonal pair (that relative test is what gives small eigenvalues of a graded positive definite matrix
+// their relative accuracy) or in absolute terms (abs_tol2 is the squared absolute threshold).  `large` reports
+// whether the entry was above kJacobiLargeTol relative to the pair and well above the absolute noise threshold:
+// Jacobi converges quadratically, so a sweep whose rotations were all smaller than that leaves entries of the order
+// of their square and needs no further sweep.  With
+// h = (aqq - app) / 2 and r = sqrt(h^2 + apq^2):  c^2 = (1 + |h| / r) / 2,  s = sign(h) apq / (2 r c).  Written
+// this way the rotation costs two reciprocal square roots in sequence and no division: it sits on the critical
+// path of every round.
 __device__ __forceinline__ bool jacobi_rotation(double app, double aqq, double apq, double abs_tol2, double& c,
-                                                double& s) {
+                                                double& s, bool& large) {
   c = 1.0;
   s = 0.0;
-  const double apq2 = apq * apq;
-  if (!(apq2 > kJacobiTol * kJacobiTol * fabs(app * aqq)) || !(apq2 > abs_tol2) || !(apq2 > 1.0e-290)) return false;
+  large = false;
+  const double apq2 = apq * apq, scale2 = fabs(app * aqq);
+  if (!(apq2 > kJacobiTol * kJacobiTol * scale2) || !(apq2 > abs_tol2) || !(apq2 > 1.0e-290)) return false;
+  large = apq2 > kJacobiLargeTol * kJacobiLargeTol * scale2 && apq2 > kJacobiLargeAbs * kJacobiLargeAbs * abs_tol2;
   const double h = 0.5 * (aqq - app);
-  const double x = h * h + apq2;
-  const double r = x * fast_rsqrt(x);
-  const double t = apq * fast_rcp(h + (h >= 0.0 ? r : -r));
-  c = fast_rsqrt(1.0 + t * t);
-  s = t * c;
+  double r, half_rinv, half_cinv;
+  sqrt_pair(fma(h, h, apq2), r, half_rinv);
+  const double sa = (h >= 0.0 ? apq : -apq) * half_rinv;   // sign(h) apq / (2 r)
+  sqrt_pair(fma(fabs(h), half_rinv, 0.5), c, half_cinv);
+  s = sa * (half_cinv + half_cinv);
   return true;
 }
 
@@ -143,25 +162,23 @@ __device__ __forceinline__ int player_at(int pos, int rounds, int m) {
 // two LDS copies used alternately); every rotation is logged, and the eigenvector kernel replays the log on the
 // rows of the identity.  A round is: wave 0 computes the half rotations | barrier | every thread rotates its
 // 2x2 blocks from one copy into their next positions in the other copy | barrier.
-template <int ITEMS>
-__global__ __launch_bounds__(kEigThreads) void eig_update_kernel(const SmallGroup g) {
-  extern __shared__ __attribute__((aligned(16))) double dyn[];   // two copies of Z, m x ms, entries (a <= b) live
+template <int ITEMS, int NT>
+__global__ __launch_bounds__(NT) void eig_update_kernel(const SmallGroup g) {
+  extern __shared__ __attribute__((aligned(16))) double dyn[];   // two copies of Z (upper triangle, four planes)
   __shared__ double scratch[16];
   __shared__ double s_d[kMaxRank], s_ise[kMaxRank], s_dr[kMaxRank], s_c[kMaxRank + 1], s_enew[kMaxRank];
-  __shared__ double2 s_rot[kMaxHalf];
+  __shared__ double s_rc[2][kMaxHalf], s_rs[2][kMaxHalf];   // (c, s) of the pairs, this round's and the next's
   __shared__ int s_perm[kMaxRank];
   __shared__ double s_scal[8];
   __shared__ int s_flag[2];
-  __shared__ int s_rotated;
+  __shared__ int s_rotated[2];
 
   const SmallArgs& a = g.a[blockIdx.x];
   const int R = a.R, D = a.D, N = a.N;
   const int tid = threadIdx.x;
-  constexpr int nt = kEigThreads;
+  constexpr int nt = NT;
   const int m = (R + 1) & ~1;
   const int half = m / 2;
-  const int ms = m;   // even row stride: the two entries (a, 2k), (a, 2k+1) of a block row are one aligned 16 bytes
-  const int zcopy = m * ms;   // offset of the second copy (offsets, not pointers: the accesses stay LDS instructions)
   PrecondScalars* st = a.st;
 
   const double eta = 1.0 - exp(-(double)N / g.num_samples_history);   // eq. eta:ns
@@ -183,8 +200,21 @@ __global__ __launch_bounds__(kEigThreads) void eig_update_kernel(const SmallGrou
   }
   __syncthreads();
 
-  // Z_t from K_t and L_t (eq. zt:compute), symmetrised, laid out by position; the padding player of an odd R has
-  // an all-zero row and column and is never rotated
+  // Z_t from K_t and L_t (eq. zt:compute), symmetrised, laid out by position in four planes: plane 2a+b holds the
+  // entry (2 bi + a, 2 bj + b) of every 2x2 block bi <= bj, blocks numbered row by row, so that lane t of the block
+  // update reads element t of each plane (conflict-free 8-byte reads).  The padding player of an odd R has an
+  // all-zero row and column and is never rotated.
+  const int n_blocks = half * (half + 1) / 2;
+  const int np = n_blocks;        // plane stride
+  const int zcopy = 4 * np;       // offset of the second copy (offsets, not pointers: accesses stay LDS instructions)
+  auto tri = [half](int bi) { return bi * half - bi * (bi - 1) / 2; };   // number of the block (bi, bi)
+  auto place = [&](int pa, int pb) {   // LDS offset of the entry at positions (pa, pb) within a copy
+    const int lo = pa < pb ? pa : pb, hi = pa < pb ? pb : pa;
+    const int bi = lo >> 1, bj = hi >> 1;
+    return (2 * (lo & 1) + (hi & 1)) * np + tri(bi) + bj - bi;
+  };
+  for (int idx = tid; idx < 2 * zcopy; idx += nt) dyn[idx] = 0.0;
+  __syncthreads();
   const double ck = (eta / N) * (eta / N), cl = eta * (1.0 - eta) / N;
   double zmax = 0.0;
   for (int idx = tid; idx < m * m; idx += nt) {
@@ -201,17 +231,15 @@ __global__ __launch_bounds__(kEigThreads) void eig_update_kernel(const SmallGrou
         zmax = fmax(zmax, z);
       }
     }
-    dyn[pa * ms + pb] = z;
+    dyn[place(pa, pb)] = z;
   }
   zmax = block_max(zmax, scratch);
   const double abs_tol = kJacobiAbsTol * zmax;
   const double abs_tol2 = abs_tol * abs_tol;
 
-  // the blocks (bi <= bj) this thread owns, numbered row by row so that neighbouring lanes read neighbouring
-  // 16-byte pieces: fixed source rows (two double2 loads) and destination offsets of their four entries
-  const int n_blocks = half * (half + 1) / 2;
+  // the blocks this thread owns and the (fixed) destinations of their four entries
   int blk_i[ITEMS], blk_j[ITEMS];
-  int src[ITEMS][2], dst[ITEMS][4];
+  int dst[ITEMS][4];
 #pragma unroll
   for (int it = 0; it < ITEMS; ++it) {
     const int item = tid + it * nt;
@@ -223,52 +251,115 @@ __global__ __launch_bounds__(kEigThreads) void eig_update_kernel(const SmallGrou
     const int bj = bi + rem;
     blk_i[it] = bi;
     blk_j[it] = bj;
-    src[it][0] = (2 * bi) * ms + 2 * bj;
-    src[it][1] = (2 * bi + 1) * ms + 2 * bj;   // its first entry lies below the diagonal when bi == bj: ignored
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const int na = next_position(2 * bi + (e >> 1), half), nb = next_position(2 * bj + (e & 1), half);
-      dst[it][e] = na <= nb ? na * ms + nb : nb * ms + na;
-    }
+    for (int e = 0; e < 4; ++e)
+      dst[it][e] = place(next_position(2 * bi + (e >> 1), half), next_position(2 * bj + (e & 1), half));
   }
   const bool odd_pad = (R & 1) != 0;   // pair 0 then holds the padding player
-  if (tid == 0) s_rotated = 0;
+
+  // Rotation lanes (the last wavefront): while the 2x2 blocks of round r are being rotated, lane k of this wave
+  // prepares pair k's rotation for round r+1.  The pair that will stand at (2k, 2k+1) is made of member A (the
+  // later column) and member B (the earlier row) of the present layout; the lane recomputes their two diagonal
+  // entries and their common entry after this round's rotations from the old copy, so a round needs one barrier.
+  const int rot_k = tid - (nt - 64);
+  const bool rot_lane = rot_k >= 0 && rot_k < half;
+  int rz_blk = 0, rz_da = 0, rz_db = 0, rz_pa = 0, rz_pb = 0;
+  bool rz_sa0 = true, rz_sb0 = true;
+  if (rot_lane && half >= 2) {
+    const int k = rot_k;
+    const int pa = k < half - 1 ? k + 1 : half - 1, sa = k < half - 1 ? 0 : 1;   // first member of the new pair
+    const int pb = k >= 2 ? k - 1 : 0, sb = k == 1 ? 0 : 1;                       // second member (pb < pa)
+    rz_pa = pa;
+    rz_pb = pb;
+    rz_sa0 = sa == 0;
+    rz_sb0 = sb == 0;
+    rz_blk = tri(pb) + pa - pb;
+    rz_da = tri(pa);
+    rz_db = tri(pb);
+  }
+  double2* __restrict__ rotlog = a.rotlog;
+  if (tid >= nt - 64) __builtin_amdgcn_s_setprio(3);   // the rotation wave's dependent chain bounds the round
+  if (tid < 2) s_rotated[tid] = 0;
+  __syncthreads();
+  if (rot_lane) {   // rotations of the very first round
+    const int t = tri(rot_k);
+    double c = 1.0, s = 0.0;
+    bool large = false;
+    if (!(odd_pad && rot_k == 0)) jacobi_rotation(dyn[t], dyn[3 * np + t], dyn[np + t], abs_tol2, c, s, large);
+    if (large) s_rotated[0] = 1;
+    s_rc[0][rot_k] = c;
+    s_rs[0][rot_k] = s;
+    rotlog[rot_k] = make_double2(c, s);
+  }
   __syncthreads();
 
-  // cyclic Jacobi; a sweep in which no pair needed a rotation ends the iteration
+  // cyclic Jacobi; a sweep in which no pair needed a large rotation ends the iteration
   int sweeps = 0, rounds = 0, cur = 0;
   bool converged = false;
+#ifdef NGSGD_EIG_TIMING
+  long long tm_rot = 0, tm_blk = 0, tm_bar = 0, tm_ld = 0, tm_ch = 0;
+  const long long tm_start = clock64();
+#endif
   for (; sweeps < kMaxSweeps && !converged; ++sweeps) {
     for (int r = 0; r < m - 1; ++r, ++rounds, cur ^= 1) {
       const int co = cur ? zcopy : 0, no = cur ? 0 : zcopy;
-      if (tid < half) {
-        const int pt = 2 * tid, pb = 2 * tid + 1;
+      const double* rc = s_rc[cur];
+      const double* rs = s_rs[cur];
+#ifdef NGSGD_EIG_TIMING
+      const long long tA = clock64();
+#endif
+      if (rot_lane) {
         double c = 1.0, s = 0.0;
-        if (!(odd_pad && tid == 0) &&
-            jacobi_rotation(dyn[co + pt * ms + pt], dyn[co + pb * ms + pb], dyn[co + pt * ms + pb], abs_tol2, c, s))
-          s_rotated = 1;
-        const double2 cs = make_double2(c, s);
-        s_rot[tid] = cs;
-        a.rotlog[(size_t)rounds * half + tid] = cs;
+        if (half >= 2 && !(odd_pad && rot_k == 0)) {
+          const double ci = rc[rz_pb], si = rs[rz_pb], cj = rc[rz_pa], sj = rs[rz_pa];
+          const double x00 = dyn[co + rz_blk], x01 = dyn[co + np + rz_blk];
+          const double x10 = dyn[co + 2 * np + rz_blk], x11 = dyn[co + 3 * np + rz_blk];
+          const double da_tt = dyn[co + rz_da], da_tb = dyn[co + np + rz_da], da_bb = dyn[co + 3 * np + rz_da];
+          const double db_tt = dyn[co + rz_db], db_tb = dyn[co + np + rz_db], db_bb = dyn[co + 3 * np + rz_db];
+          __builtin_amdgcn_sched_barrier(0);   // all reads are in flight before the first use
+#ifdef NGSGD_EIG_TIMING
+          asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+          const long long tL = clock64();
+          tm_ld += tL - tA;
+#endif
+          // a first member takes (c, -s) of its pair's rotation, a second member (s, c)
+          const double r0 = rz_sb0 ? ci : si, r1 = rz_sb0 ? -si : ci;
+          const double q0 = rz_sa0 ? cj : sj, q1 = rz_sa0 ? -sj : cj;
+          const double zab = q0 * (r0 * x00 + r1 * x10) + q1 * (r0 * x01 + r1 * x11);
+          const double zaa = q0 * q0 * da_tt + 2.0 * q0 * q1 * da_tb + q1 * q1 * da_bb;
+          const double zbb = r0 * r0 * db_tt + 2.0 * r0 * r1 * db_tb + r1 * r1 * db_bb;
+          // whether this rotation belongs to the present sweep or opens the next one
+          bool large = false;
+          jacobi_rotation(zaa, zbb, zab, abs_tol2, c, s, large);
+          if (large) s_rotated[(sweeps + (r == m - 2 ? 1 : 0)) & 1] = 1;
+        }
+#ifdef NGSGD_EIG_TIMING
+        asm volatile("" :: "v"(c), "v"(s) : "memory");
+        const long long tS = clock64();
+        tm_ch += tS - tA;
+#endif
+        s_rc[cur ^ 1][rot_k] = c;
+        s_rs[cur ^ 1][rot_k] = s;
+        rotlog[(size_t)(rounds + 1) * half + rot_k] = make_double2(c, s);
       }
-      __syncthreads();
+#ifdef NGSGD_EIG_TIMING
+      const long long tB = clock64();
+#endif
+      // the other waves hold back for a moment so that the rotation wave's few reads are not queued behind theirs
+      if (tid < nt - 64) __builtin_amdgcn_s_sleep(kEigBlockDelay);
 #pragma unroll
       for (int it = 0; it < ITEMS; ++it) {
-        if (ITEMS > 1 && tid + it * nt >= n_blocks) continue;
-        if (ITEMS == 1 && tid >= n_blocks) continue;
+        const int t = tid + it * nt;
+        if (t >= n_blocks) continue;
         const int bi = blk_i[it], bj = blk_j[it];
-        const double2 ri = s_rot[bi], rj = s_rot[bj];
-        const double ci = ri.x, si = ri.y, cj = rj.x, sj = rj.y;
-        const double2 row0 = *reinterpret_cast<const double2*>(&dyn[co + src[it][0]]);
-        const double2 row1 = *reinterpret_cast<const double2*>(&dyn[co + src[it][1]]);
+        const double ci = rc[bi], si = rs[bi], cj = rc[bj], sj = rs[bj];
+        const double x00 = dyn[co + t], x01 = dyn[co + np + t], x10 = dyn[co + 2 * np + t], x11 = dyn[co + 3 * np + t];
         if (bi == bj) {   // the rotated pair itself: entries (t,t), (t,b), (b,b)
-          const double att = row0.x, atb = row0.y, abb = row1.y;
-          dyn[no + dst[it][0]] = ci * ci * att - 2.0 * ci * si * atb + si * si * abb;
-          dyn[no + dst[it][3]] = si * si * att + 2.0 * ci * si * atb + ci * ci * abb;
-          dyn[no + dst[it][1]] = si == 0.0 ? atb : 0.0;
+          dyn[no + dst[it][0]] = ci * ci * x00 - 2.0 * ci * si * x01 + si * si * x11;
+          dyn[no + dst[it][3]] = si * si * x00 + 2.0 * ci * si * x01 + ci * ci * x11;
+          dyn[no + dst[it][1]] = si == 0.0 ? x01 : 0.0;
           continue;
         }
-        const double x00 = row0.x, x01 = row0.y, x10 = row1.x, x11 = row1.y;
         const double y00 = ci * x00 - si * x10, y01 = ci * x01 - si * x11;
         const double y10 = si * x00 + ci * x10, y11 = si * x01 + ci * x11;
         dyn[no + dst[it][0]] = y00 * cj - y01 * sj;
@@ -276,13 +367,25 @@ __global__ __launch_bounds__(kEigThreads) void eig_update_kernel(const SmallGrou
         dyn[no + dst[it][2]] = y10 * cj - y11 * sj;
         dyn[no + dst[it][3]] = y10 * sj + y11 * cj;
       }
+#ifdef NGSGD_EIG_TIMING
+      const long long tC = clock64();
+#endif
       __syncthreads();
+#ifdef NGSGD_EIG_TIMING
+      const long long tD = clock64();
+      tm_rot += tB - tA; tm_blk += tC - tB; tm_bar += tD - tC;
+#endif
     }
-    if (s_rotated == 0) converged = true;   // same value for every thread: read after the round's closing barrier
-    __syncthreads();                        // everyone has read the flag before it is cleared again
-    if (tid == 0) s_rotated = 0;
+    if (s_rotated[sweeps & 1] == 0) converged = true;   // same value for every thread: read after the barrier
+    __syncthreads();                                    // everyone has read the flag before it is cleared again
+    if (tid == 0) s_rotated[sweeps & 1] = 0;
   }
 
+#ifdef NGSGD_EIG_TIMING
+  if ((tid & 63) == 0 && R >= 64)
+    printf("eig R=%d wave %d rounds %d total %lld rot %lld blk %lld bar %lld ld %lld ch %lld\n", R, tid >> 6, rounds,
+           (long long)(clock64() - tm_start), tm_rot, tm_blk, tm_bar, tm_ld, tm_ch);
+#endif
   // eigenvalues (by player), floor (after eq. zt:eig:repeat), decreasing order
   const int fo = cur ? zcopy : 0;
   const double floor_c = (1.0 - eta) * (1.0 - eta) * rho * rho;
@@ -291,7 +394,7 @@ __global__ __launch_bounds__(kEigThreads) void eig_update_kernel(const SmallGrou
   for (int pos = tid; pos < m; pos += nt) {
     const int i = player_at(pos, rounds, m);
     if (i >= R) continue;
-    double c = dyn[fo + pos * ms + pos];
+    double c = dyn[fo + place(pos, pos)];
     if (!(c >= floor_c)) {
       c = floor_c;
       s_flag[0] = 1;
@@ -347,6 +450,21 @@ __global__ __launch_bounds__(kEigThreads) void eig_update_kernel(const SmallGrou
   for (int idx = tid; idx < R * R; idx += nt) a.K[idx] = 0.0;
 }
 
+// Whole-wavefront shifts by one lane through the DPP path of the vector ALU (no LDS traffic): lane i receives the
+// value of lane i-1 (up) or i+1 (down); the lane without a source keeps its own value.
+__device__ __forceinline__ double wave_shift_up(double x) {
+  int lo = __double2loint(x), hi = __double2hiint(x);
+  lo = __builtin_amdgcn_update_dpp(lo, lo, 0x138, 0xf, 0xf, false);   // wave_shr:1
+  hi = __builtin_amdgcn_update_dpp(hi, hi, 0x138, 0xf, 0xf, false);
+  return __hiloint2double(hi, lo);
+}
+__device__ __forceinline__ double wave_shift_down(double x) {
+  int lo = __double2loint(x), hi = __double2hiint(x);
+  lo = __builtin_amdgcn_update_dpp(lo, lo, 0x130, 0xf, 0xf, false);   // wave_shl:1
+  hi = __builtin_amdgcn_update_dpp(hi, hi, 0x130, 0xf, 0xf, false);
+  return __hiloint2double(hi, lo);
+}
+
 // U_t by replaying the rotation log on rows of the identity, then A_t (eq. wt1).  U <- U J only mixes two
 // columns, so rows are independent: each wavefront owns one row and keeps it in registers.  Lane k holds the two
 // columns that pair k rotates; between rounds the columns move to the neighbouring lanes exactly as the players
@@ -361,60 +479,71 @@ __global__ __launch_bounds__(kEigvecThreads) void eigvec_kernel(const SmallGroup
   const int row = blockIdx.y * (kEigvecThreads / 64) + wave;   // rows >= R idle along (they share the barriers)
   const int n_rounds = a.work->n_rounds;
   const bool active = lane < half;
+  // Lanes beyond the last pair replay the last pair's rotations on zeros: nothing of theirs reaches an active
+  // lane (a lane takes from its lower neighbour, and the last active lane takes its own second member).
+  const int ll = active ? lane : half - 1;
   // players held by this lane in round 0: first k, second m-1-k (lane 0: the fixed player m-1)
-  int tp = lane, bp = m - 1 - lane;
-  double top = (active && tp == row) ? 1.0 : 0.0;
-  double bot = (active && bp == row) ? 1.0 : 0.0;
+  double top = (active && lane == row) ? 1.0 : 0.0;
+  double bot = (active && m - 1 - lane == row) ? 1.0 : 0.0;
+  const bool last_lane = lane == half - 1, lane0 = lane == 0, lane1 = lane == 1;
 
+  // the log is padded to whole chunks, and one chunk beyond the last round is allocated: staging needs no guards
   constexpr int kLoads = (kEigvecChunk * kMaxHalf + kEigvecThreads - 1) / kEigvecThreads;
-  const int chunk_elems = kEigvecChunk * half;   // the log is padded to whole chunks
-  double2 stage[kLoads];
+  const int chunk_elems = kEigvecChunk * half;
+  const double2* __restrict__ rotlog = a.rotlog;
+  int src[kLoads];
 #pragma unroll
-  for (int u = 0; u < kLoads; ++u) {
-    const int e = tid + u * kEigvecThreads;
-    if (e < chunk_elems) s_log[0][e] = a.rotlog[e];
-  }
+  for (int u = 0; u < kLoads; ++u) src[u] = min(tid + u * kEigvecThreads, chunk_elems - 1);
+  double stage_c[kLoads], stage_s[kLoads];   // plain scalars: they must stay in registers
+#pragma unroll
+  for (int u = 0; u < kLoads; ++u) s_log[0][src[u]] = rotlog[src[u]];
   __syncthreads();
   for (int base = 0, buf = 0; base < n_rounds; base += kEigvecChunk, buf ^= 1) {
     const bool more = base + kEigvecChunk < n_rounds;
-    if (more) {
+    if (more) {   // in flight while this chunk is replayed
 #pragma unroll
       for (int u = 0; u < kLoads; ++u) {
-        const int e = tid + u * kEigvecThreads;
-        if (e < chunk_elems) stage[u] = a.rotlog[(size_t)(base + kEigvecChunk) * half + e];
+        const double2 v = rotlog[(size_t)(base + kEigvecChunk) * half + src[u]];
+        stage_c[u] = v.x;
+        stage_s[u] = v.y;
       }
     }
     const int len = min(kEigvecChunk, n_rounds - base);
-    const double2* lg = s_log[buf];
-    for (int rr = 0; rr < len; ++rr) {
-      const double2 cs = active ? lg[rr * half + lane] : make_double2(1.0, 0.0);
-      const double c = cs.x, s = cs.y;
+    const double2* lg = s_log[buf] + ll;
+    auto replay = [&](double2 cs) {
       // the logged rotation acts on (first, second) of the pair
-      const double nt_ = top * c - bot * s, nb_ = top * s + bot * c;
-      top = nt_;
-      bot = nb_;
-      // players move: firsts shift one lane down (the last lane takes its own second), seconds shift one lane
-      // up (lane 1 takes lane 0's first); lane 0's second is fixed
+      const double nt_ = top * cs.x - bot * cs.y, nb_ = top * cs.y + bot * cs.x;
       if (m > 2) {
-        const double t_dn = __shfl_down(top, 1);
-        const double b_up = __shfl_up(bot, 1);
-        const double t0 = __shfl(top, 0);
-        top = lane == half - 1 ? bot : t_dn;
-        bot = lane == 0 ? bot : (lane == 1 ? t0 : b_up);
-        tp = tp + 1 == m - 1 ? 0 : tp + 1;
-        if (lane != 0) bp = bp + 1 == m - 1 ? 0 : bp + 1;
+        // players move: firsts shift one lane down (the last lane takes its own second), seconds shift one lane
+        // up (lane 1 takes lane 0's first); lane 0's second is fixed
+        const double t_dn = wave_shift_down(nt_);
+        const double b_up = wave_shift_up(nb_);
+        const double t_up = wave_shift_up(nt_);
+        top = last_lane ? nb_ : t_dn;
+        bot = lane0 ? nb_ : (lane1 ? t_up : b_up);
+      } else {
+        top = nt_;
+        bot = nb_;
       }
+    };
+    int rr = 0;
+    for (; rr + 4 <= len; rr += 4) {   // four rotations fetched ahead of their use
+      const double2 c0 = lg[(rr + 0) * half], c1 = lg[(rr + 1) * half], c2 = lg[(rr + 2) * half], c3 = lg[(rr + 3) * half];
+      replay(c0);
+      replay(c1);
+      replay(c2);
+      replay(c3);
     }
+    for (; rr < len; ++rr) replay(lg[rr * half]);
     if (more) {
 #pragma unroll
-      for (int u = 0; u < kLoads; ++u) {
-        const int e = tid + u * kEigvecThreads;
-        if (e < chunk_elems) s_log[buf ^ 1][e] = stage[u];
-      }
+      for (int u = 0; u < kLoads; ++u) s_log[buf ^ 1][src[u]] = make_double2(stage_c[u], stage_s[u]);
     }
     __syncthreads();
   }
   if (!active || row >= R) return;
+  // the players standing at this lane's two positions after n_rounds rounds
+  const int tp = player_at(2 * lane, n_rounds, m), bp = player_at(2 * lane + 1, n_rounds, m);
   const int j = row;   // row of U = column of A_t
   const double rs = a.work->rowscale[j];
   if (tp < R) a.At[(size_t)a.work->rank_of[tp] * a.ldat + j] = (float)(a.work->colscale[tp] * top * rs);
