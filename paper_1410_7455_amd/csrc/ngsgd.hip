@@ -103,7 +103,8 @@ inline int rank_class(int rank) { return rank <= 32 ? 32 : (rank <= 80 ? 80 : 96
 // and the next step's forward / backward pass; the new factor is first needed by the next preconditioning.
 struct SideSync {
   hipStream_t stream = nullptr;
-  hipEvent_t inputs_ready = nullptr;   // recorded on the caller's stream: H, J, tr(X X^T) are final
+  hipEvent_t inputs_ready = nullptr;   // recorded on the caller's stream: H, J and the partial sums of tr(X X^T) are final
+  hipEvent_t outputs_done = nullptr;   // recorded on the caller's stream: the last reader of W_t (Xhat) has been enqueued
   hipEvent_t done = nullptr;           // recorded on the side stream: W_{t+1}, D_{t+1}, rho_{t+1} are final
   bool pending = false;
 };
@@ -210,6 +211,8 @@ int ensure_kernel_attributes() {
   HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(eig_update_kernel<kEigMaxItems, kEigThreads>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, max_dyn));
   HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(orth_fix_kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, max_dyn));
+  HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(orth_apply_kernel),
                               hipFuncAttributeMaxDynamicSharedMemorySize, max_dyn));
   g_attr_done = true;
   return NGSGD_OK;
@@ -366,6 +369,14 @@ int join_side(SideSync* sync, hipStream_t s) {
   return NGSGD_OK;
 }
 
+// Split-K factor of the H = X W^T product of an N x D input (bounded by the room for its sum-of-squares partials).
+int h_splits(int N, int D) {
+  const int tiles_m = (N + 63) / 64, ksteps = (D + BK - 1) / BK;
+  int splits = choose_splits(tiles_m, ksteps);
+  while (splits > 1 && splits * tiles_m > kSumsqMax) --splits;
+  return splits;
+}
+
 // The online natural-gradient call (App. B.5) for a list of independent instances.  With
 // scale_output the matrices are left as gamma * Xhat; without it they are left as Xhat and gamma
 // stays in the instance's state for the caller to fold into a later product.  With `side` the factor
@@ -432,10 +443,7 @@ int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStr
       g.C = p.H; g.ldc = p.ldh;
       g.M = c.N; g.N = p.rank; g.K = p.dim;
       g.sumsq = p.sumsq_part;
-      const int tiles_m = (c.N + 63) / 64, ksteps = (p.dim + BK - 1) / BK;
-      int splits = choose_splits(tiles_m, ksteps);
-      while (splits > 1 && splits * tiles_m > kSumsqMax) --splits;
-      g.splits = splits;
+      g.splits = h_splits(c.N, p.dim);
       d.push_back(g);
     }
     if (d.empty()) continue;
@@ -462,6 +470,13 @@ int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStr
     HIP_TRY(by_rank_class(rc, [&] { return launch_j<32>(d.data(), (int)d.size(), s); },
                           [&] { return launch_j<80>(d.data(), (int)d.size(), s); },
                           [&] { return launch_j<96>(d.data(), (int)d.size(), s); }));
+  }
+  // The factor update needs only H, J and the partial sums of tr(X X^T): with a side stream it starts here and
+  // overlaps the rest of this call; it must not replace W_t before Xhat has read it (second event below).
+  const bool on_side = side != nullptr && !to_update.empty();
+  if (on_side) {
+    HIP_TRY(hipEventRecord(side->inputs_ready, main_stream));
+    HIP_TRY(hipStreamWaitEvent(side->stream, side->inputs_ready, 0));
   }
   // Xhat = X - H W   (eq. hatxt:compute:2), row-norm partials (eq. pi)
   {
@@ -493,12 +508,7 @@ int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStr
       a.sumsq_part = p.sumsq_part;
       GemmDesc hd;
       hd.M = c.N; hd.N = p.rank; hd.K = p.dim;
-      {
-        const int tiles_m = (c.N + 63) / 64, ksteps = (p.dim + BK - 1) / BK;
-        int splits = choose_splits(tiles_m, ksteps);
-        while (splits > 1 && splits * tiles_m > kSumsqMax) --splits;
-        hd.splits = splits;
-      }
+      hd.splits = h_splits(c.N, p.dim);
       a.n_sumsq = planned_sumsq_partials<64, 32, BK>(hd);   // independent of the tile width
       a.rownorm_part = p.rownorm_part;
       a.n_col_tiles = (p.dim + 63) / 64;
@@ -521,9 +531,8 @@ int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStr
     }
   }
   if (!to_update.empty()) {
-    if (side != nullptr) {
-      HIP_TRY(hipEventRecord(side->inputs_ready, main_stream));
-      HIP_TRY(hipStreamWaitEvent(side->stream, side->inputs_ready, 0));
+    if (on_side) {
+      HIP_TRY(hipEventRecord(side->outputs_done, main_stream));
       s = side->stream;
     }
     // K = J J^T, L = H^T H   (App. B.3), fp64 accumulation across the splits
@@ -591,13 +600,20 @@ int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStr
         a.st = p.st; a.K = p.K; a.L = p.L; a.At = p.At; a.ldat = p.ldh;
         a.R = p.rank; a.D = p.dim; a.N = c.N;
         a.rotlog = p.rotlog; a.work = p.eigwork;
+        a.sumsq_part = p.sumsq_part;
+        {
+          GemmDesc hd;
+          hd.M = c.N; hd.N = p.rank; hd.K = p.dim;
+          hd.splits = h_splits(c.N, p.dim);
+          a.n_sumsq = planned_sumsq_partials<64, 32, BK>(hd);   // independent of the tile width
+        }
         OrthArgs& o = og.a[n];
         o.st = p.st; o.G = p.K; o.W = p.W; o.ld = p.ldw; o.R = p.rank; o.D = p.dim;
         r_max = std::max(r_max, p.rank);
         ++n;
       }
       g.count = og.count = n;
-      const size_t dyn = (size_t)2 * r_max * (r_max | 1) * sizeof(double);
+      const size_t dyn = (size_t)r_max * (r_max | 1) * sizeof(double);
       {
         ProfScope prof(NGSGD_PROF_PRECOND_SMALL, s);
         {
@@ -619,7 +635,8 @@ int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStr
                            0, s, g);
         LAUNCH_CHECK();
       }
-      // W_{t+1} = A_t B_t   (eq. wt1)
+      // W_{t+1} = A_t B_t   (eq. wt1), once nothing reads W_t any more
+      if (on_side) HIP_TRY(hipStreamWaitEvent(side->stream, side->outputs_done, 0));
       for (int rc : {32, 80, 96}) {
         std::vector<GemmDesc> d;
         for (int i = 0; i < n; ++i) {
@@ -659,6 +676,12 @@ int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStr
         HIP_TRY((launch_gemm_group<64, 64, BK, 2, 2, true, true, EPI_ATOMIC_F64, false, 0, true>(dg.data(),
                                                                                                (int)dg.size(), s)));
         hipLaunchKernelGGL(orth_fix_kernel, dim3(n), dim3(kSmallThreads), dyn, s, og);
+        LAUNCH_CHECK();
+        int d_max = 0;
+        for (int i = 0; i < n; ++i) d_max = std::max(d_max, to_update[done + i].p->dim);
+        const size_t apply_dyn = ((size_t)r_max * r_max + (size_t)r_max * kOrthApplyThreads) * sizeof(double);
+        hipLaunchKernelGGL(orth_apply_kernel, dim3((d_max + kOrthApplyThreads - 1) / kOrthApplyThreads, n),
+                           dim3(kOrthApplyThreads), apply_dyn, s, og);
         LAUNCH_CHECK();
       }
       done += n;
@@ -964,6 +987,7 @@ extern "C" int ngsgd_create(const ngsgd_config* cfg, void* dev_workspace, size_t
   // second stream for the factor updates: default priority, does not synchronise with the NULL stream
   if (e == hipSuccess) e = hipStreamCreateWithFlags(&net->side.stream, hipStreamNonBlocking);
   if (e == hipSuccess) e = hipEventCreateWithFlags(&net->side.inputs_ready, hipEventDisableTiming);
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&net->side.outputs_done, hipEventDisableTiming);
   if (e == hipSuccess) e = hipEventCreateWithFlags(&net->side.done, hipEventDisableTiming);
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e != hipSuccess) {
@@ -982,6 +1006,7 @@ extern "C" int ngsgd_destroy(ngsgd_net* net) {
     (void)hipStreamDestroy(net->side.stream);
   }
   if (net->side.inputs_ready != nullptr) (void)hipEventDestroy(net->side.inputs_ready);
+  if (net->side.outputs_done != nullptr) (void)hipEventDestroy(net->side.outputs_done);
   if (net->side.done != nullptr) (void)hipEventDestroy(net->side.done);
   delete net;
   return NGSGD_OK;

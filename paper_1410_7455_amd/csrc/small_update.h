@@ -54,6 +54,8 @@ struct SmallArgs {
   float* At;         // out: A_t (eq. wt1), R x ldat (written by the eigenvector kernel)
   int ldat;
   int R, D, N;
+  const double* sumsq_part;   // partial sums of tr(X X^T) left by the H product
+  int n_sumsq;
   double2* rotlog;   // [kMaxRounds][half] (c, s) of every pair of every round
   EigWork* work;
 };
@@ -183,6 +185,9 @@ __global__ __launch_bounds__(NT) void eig_update_kernel(const SmallGroup g) {
 
   const double eta = 1.0 - exp(-(double)N / g.num_samples_history);   // eq. eta:ns
   const double rho = st->rho;
+  double tr_part = 0.0;   // tr(X X^T), summed here: the kernel that finishes the output may still be running
+  for (int i = tid; i < a.n_sumsq; i += nt) tr_part += a.sumsq_part[i];
+  const double tr_M = block_sum(tr_part, scratch);
   for (int i = tid; i < R; i += nt) s_d[i] = st->d[i];
   __syncthreads();
   if (tid == 0) {
@@ -414,7 +419,7 @@ __global__ __launch_bounds__(NT) void eig_update_kernel(const SmallGroup g) {
     double sum_sqrt = 0.0;
     for (int i = 0; i < R; ++i) sum_sqrt += sqrt(s_c[i]);
     // eq. rhodash2, dt1, rhot1
-    const double rho_dash = ((eta / N) * st->tr_M + (1.0 - eta) * ((double)D * rho + sum_d) - sum_sqrt) / (double)(D - R);
+    const double rho_dash = ((eta / N) * tr_M + (1.0 - eta) * ((double)D * rho + sum_d) - sum_sqrt) / (double)(D - R);
     const double rho_new = fmax(g.epsilon, rho_dash);
     double sum_dn = 0.0;
     for (int k = 0; k < R; ++k) {
@@ -554,7 +559,8 @@ __global__ __launch_bounds__(kEigvecThreads) void eigvec_kernel(const SmallGroup
 // 1e-3, W <- E^{1/2} L^{-1} E^{-1/2} W with O = L L^T.  Runs only when the update asked for the check.
 struct OrthArgs {
   PrecondScalars* st;
-  const double* G;   // R x R, W W^T of the new factor (accumulated only when the check was requested)
+  double* G;         // R x R, W W^T of the new factor (accumulated only when the check was requested); on return
+                     // the Cholesky factor L when the fix is needed
   float* W;
   int ld;
   int R, D;
@@ -570,11 +576,10 @@ __global__ __launch_bounds__(kSmallThreads) void orth_fix_kernel(const OrthGroup
   const OrthArgs& a = g.a[blockIdx.x];
   PrecondScalars* st = a.st;
   if (!(st->flags & kFlagOrthCheck)) return;   // uniform over the workgroup
-  const int R = a.R, D = a.D, ld = a.ld;
+  const int R = a.R;
   const int tid = threadIdx.x, nt = blockDim.x;
   const int Rs = R | 1;
   double* O = dyn;                    // R x Rs, becomes L
-  double* X = dyn + (size_t)R * Rs;   // R x Rs, L^{-1} then the mixing matrix
 
   double dev = 0.0;
   for (int idx = tid; idx < R * R; idx += nt) {
@@ -592,46 +597,59 @@ __global__ __launch_bounds__(kSmallThreads) void orth_fix_kernel(const OrthGroup
     return;
   }
   __syncthreads();
-  // Cholesky O = L L^T in place (lower triangle), one column at a time
+  // Cholesky O = L L^T in place (lower triangle), right-looking: scale column j, then every thread takes its
+  // share of the rank-1 update of the trailing triangle
   for (int j = 0; j < R; ++j) {
-    if (tid == 0) {
-      double s = O[j * Rs + j];
-      for (int k = 0; k < j; ++k) s -= O[j * Rs + k] * O[j * Rs + k];
-      O[j * Rs + j] = sqrt(fmax(s, 1.0e-300));
-    }
+    const double pivot = sqrt(fmax(O[j * Rs + j], 1.0e-300));
+    __syncthreads();   // everyone has read the old diagonal entry
+    for (int i = j + tid; i < R; i += nt) O[i * Rs + j] = i == j ? pivot : O[i * Rs + j] / pivot;
     __syncthreads();
-    for (int i = j + 1 + tid; i < R; i += nt) {
-      double s = O[i * Rs + j];
-      for (int k = 0; k < j; ++k) s -= O[i * Rs + k] * O[j * Rs + k];
-      O[i * Rs + j] = s / O[j * Rs + j];
+    const int rem = R - j - 1;   // trailing rows / columns j+1 .. R-1
+    for (int idx = tid; idx < rem * rem; idx += nt) {
+      const int i = j + 1 + idx / rem, k = j + 1 + idx % rem;
+      if (k <= i) O[i * Rs + k] -= O[i * Rs + j] * O[k * Rs + j];
     }
     __syncthreads();
   }
-  // X = L^{-1} by forward substitution, one column per thread
-  for (int c = tid; c < R; c += nt) {
-    for (int i = 0; i < R; ++i) {
-      double s = i == c ? 1.0 : 0.0;
-      for (int k = c; k < i; ++k) s -= O[i * Rs + k] * X[k * Rs + c];
-      X[i * Rs + c] = i < c ? 0.0 : s / O[i * Rs + i];
-    }
-  }
-  __syncthreads();
-  for (int idx = tid; idx < R * R; idx += nt) {
-    const int i = idx / R, j = idx % R;
-    X[i * Rs + j] *= sqrt(st->e[i] / st->e[j]);
-  }
-  __syncthreads();
-  // W <- X W, X lower triangular: rows from last to first so the product can be formed in place
-  float* Wm = a.W;
-  for (int c = tid; c < D; c += nt) {
-    for (int i = R - 1; i >= 0; --i) {
-      double s = 0.0;
-      for (int k = 0; k <= i; ++k) s += X[i * Rs + k] * (double)Wm[(size_t)k * ld + c];
-      Wm[(size_t)i * ld + c] = (float)s;
-    }
-  }
-  __syncthreads();
+  // hand L to the kernel that applies the fix; G is not needed any more
+  for (int idx = tid; idx < R * R; idx += nt) a.G[idx] = idx % R <= idx / R ? O[(idx / R) * Rs + idx % R] : 0.0;
   if (tid == 0) st->flags = (st->flags & ~kFlagOrthCheck) | kFlagReorth;
+}
+
+// W <- E^{1/2} L^{-1} E^{-1/2} W for the instances whose check asked for it (kFlagReorth), L as left in G by
+// orth_fix_kernel: every column of W is one forward substitution.  Grid (column blocks, instance), one column
+// per thread, L and the columns staged through LDS.
+constexpr int kOrthApplyThreads = 64;
+__global__ __launch_bounds__(kOrthApplyThreads) void orth_apply_kernel(const OrthGroup g) {
+  extern __shared__ __attribute__((aligned(16))) double dyn[];
+  const OrthArgs& a = g.a[blockIdx.y];
+  if (!(a.st->flags & kFlagReorth)) return;   // uniform over the workgroup
+  const int R = a.R, D = a.D, ld = a.ld;
+  const int c0 = blockIdx.x * kOrthApplyThreads;
+  if (c0 >= D) return;
+  const int tid = threadIdx.x;
+  double* L = dyn;                          // R x R
+  double* Y = dyn + (size_t)R * R;          // R x kOrthApplyThreads: E^{-1/2} W on entry, the solution on exit
+  for (int idx = tid; idx < R * R; idx += kOrthApplyThreads) L[idx] = a.G[idx];
+  const int c = c0 + tid;
+  for (int k = 0; k < R; ++k)
+    Y[k * kOrthApplyThreads + tid] = c < D ? (double)a.W[(size_t)k * ld + c] / sqrt(a.st->e[k]) : 0.0;
+  __syncthreads();
+  if (c >= D) return;
+  for (int i = 0; i < R; ++i) {
+    double s0 = Y[i * kOrthApplyThreads + tid], s1 = 0.0, s2 = 0.0, s3 = 0.0;
+    int k = 0;
+    for (; k + 4 <= i; k += 4) {
+      s0 -= L[i * R + k] * Y[k * kOrthApplyThreads + tid];
+      s1 -= L[i * R + k + 1] * Y[(k + 1) * kOrthApplyThreads + tid];
+      s2 -= L[i * R + k + 2] * Y[(k + 2) * kOrthApplyThreads + tid];
+      s3 -= L[i * R + k + 3] * Y[(k + 3) * kOrthApplyThreads + tid];
+    }
+    for (; k < i; ++k) s0 -= L[i * R + k] * Y[k * kOrthApplyThreads + tid];
+    const double y = ((s0 + s1) + (s2 + s3)) / L[i * R + i];
+    Y[i * kOrthApplyThreads + tid] = y;   // only this thread reads its column
+    a.W[(size_t)i * ld + c] = (float)(sqrt(a.st->e[i]) * y);
+  }
 }
 
 }  // namespace ngsgd
