@@ -19,6 +19,8 @@
 namespace ngsgd {
 
 constexpr int kMaxGroup = 16;
+constexpr int kPrefetch = 2;   // K-blocks in flight from memory per workgroup
+constexpr int kXcds = 8;   // accelerator dies (XCDs) of the MI355X, each with a private L2
 
 enum Epilogue : int {
   EPI_STORE = 0,        // C = alpha*acc + beta*C
@@ -67,6 +69,13 @@ __device__ __forceinline__ void mfma_k4(doublex4& c, const float4& a, const floa
   c = __builtin_amdgcn_mfma_f64_16x16x4f64((double)a.z, (double)b.z, c, 0, 0, 0);
   c = __builtin_amdgcn_mfma_f64_16x16x4f64((double)a.w, (double)b.w, c, 0, 0, 0);
 }
+__device__ __forceinline__ float pick4(const float4& v, int q) { return q == 0 ? v.x : (q == 1 ? v.y : (q == 2 ? v.z : v.w)); }
+__device__ __forceinline__ void mfma_k1(floatx4& c, const float4& a, const float4& b, int q) {
+  c = __builtin_amdgcn_mfma_f32_16x16x4f32(pick4(a, q), pick4(b, q), c, 0, 0, 0);
+}
+__device__ __forceinline__ void mfma_k1(doublex4& c, const float4& a, const float4& b, int q) {
+  c = __builtin_amdgcn_mfma_f64_16x16x4f64((double)pick4(a, q), (double)pick4(b, q), c, 0, 0, 0);
+}
 template <bool ACC64>
 struct AccType {
   using type = floatx4;
@@ -84,30 +93,36 @@ struct StageKC {
   static constexpr int TOTAL = ROWS * F4_PER_ROW;
   static constexpr int ITER = (TOTAL + NT - 1) / NT;
   static constexpr int LDS_FLOATS = ROWS * (BK + 4);
-  float4 reg[ITER];
+  floatx4 reg[ITER];
+  int keep[ITER];   // bit c set: component c of the piece lies inside the operand
 
+  // Branch-free: rows and k beyond the operand are read from a clamped (valid) address and zeroed by selects, so
+  // the loads are straight-line code and the compiler can keep several K-blocks in flight with exact wait counts.
+  // Relies on ld being a multiple of 4 that covers the K extent (every float4 of a row lies inside the row).
   __device__ __forceinline__ void load(const float* __restrict__ base, int ld, int row0, int rows_total,
                                        int k0, int k_end, int tid) {
 #pragma unroll
     for (int i = 0; i < ITER; ++i) {
-      const int f = tid + i * NT;
-      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (TOTAL % NT == 0 || f < TOTAL) {
-        const int r = f / F4_PER_ROW;
-        const int gk = k0 + (f % F4_PER_ROW) * 4;
-        const int gr = row0 + r;
-        if (gr < rows_total && gk < k_end) {
-          const float* p = base + (size_t)gr * ld + gk;
-          if (gk + 3 < k_end) {
-            v = *reinterpret_cast<const float4*>(p);
-          } else {
-            v.x = p[0];
-            if (gk + 1 < k_end) v.y = p[1];
-            if (gk + 2 < k_end) v.z = p[2];
-          }
-        }
-      }
-      reg[i] = v;
+      const int f = min(tid + i * NT, TOTAL - 1);   // surplus lanes repeat the last piece (never stored)
+      const int r = f / F4_PER_ROW;
+      const int gk = k0 + (f % F4_PER_ROW) * 4;
+      const int gr = row0 + r;
+      const bool row_ok = gr < rows_total;
+      const int gk_c = min(gk, (k_end - 1) & ~3);
+      reg[i] = *reinterpret_cast<const floatx4*>(base + (size_t)min(gr, rows_total - 1) * ld + gk_c);
+      const int left = (row_ok && (TOTAL % NT == 0 || tid + i * NT < TOTAL)) ? k_end - gk : 0;   // valid components
+      keep[i] = left >= 4 ? 15 : (left <= 0 ? 0 : (1 << left) - 1);
+    }
+  }
+  // Zeroes the components that lie outside the operand; called when the data is consumed (not at the load: a use
+  // of the loaded value would make the wave wait for it there and then).
+  __device__ __forceinline__ void mask() {
+#pragma unroll
+    for (int i = 0; i < ITER; ++i) {
+      reg[i].x = (keep[i] & 1) ? reg[i].x : 0.f;
+      reg[i].y = (keep[i] & 2) ? reg[i].y : 0.f;
+      reg[i].z = (keep[i] & 4) ? reg[i].z : 0.f;
+      reg[i].w = (keep[i] & 8) ? reg[i].w : 0.f;
     }
   }
   __device__ __forceinline__ void store(float* lds, int tid) const {
@@ -117,7 +132,7 @@ struct StageKC {
       if (TOTAL % NT == 0 || f < TOTAL) {
         const int r = f / F4_PER_ROW;
         const int kq = (f % F4_PER_ROW) * 4;
-        *reinterpret_cast<float4*>(&lds[r * (BK + 4) + kq]) = reg[i];
+        *reinterpret_cast<floatx4*>(&lds[r * (BK + 4) + kq]) = reg[i];
       }
     }
   }
@@ -141,30 +156,32 @@ struct StageRC {
   static constexpr int TOTAL = BK * F4_PER_K;
   static constexpr int ITER = (TOTAL + NT - 1) / NT;
   static constexpr int LDS_FLOATS = BK * (ROWS + 4);
-  float4 reg[ITER];
+  floatx4 reg[ITER];
+  int keep[ITER];
 
+  // Branch-free like the K-contiguous loader; relies on ld being a multiple of 4 that covers the row extent.
   __device__ __forceinline__ void load(const float* __restrict__ base, int ld, int row0, int rows_total,
                                        int k0, int k_end, int tid) {
 #pragma unroll
     for (int i = 0; i < ITER; ++i) {
-      const int f = tid + i * NT;
-      float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (TOTAL % NT == 0 || f < TOTAL) {
-        const int k = f / F4_PER_K;
-        const int gr = row0 + (f % F4_PER_K) * 4;
-        const int gk = k0 + k;
-        if (gk < k_end && gr < rows_total) {
-          const float* p = base + (size_t)gk * ld + gr;
-          if (gr + 3 < rows_total) {
-            v = *reinterpret_cast<const float4*>(p);
-          } else {
-            v.x = p[0];
-            if (gr + 1 < rows_total) v.y = p[1];
-            if (gr + 2 < rows_total) v.z = p[2];
-          }
-        }
-      }
-      reg[i] = v;
+      const int f = min(tid + i * NT, TOTAL - 1);
+      const int k = f / F4_PER_K;
+      const int gr = row0 + (f % F4_PER_K) * 4;
+      const int gk = k0 + k;
+      const bool k_ok = gk < k_end;
+      const int gr_c = min(gr, (rows_total - 1) & ~3);
+      reg[i] = *reinterpret_cast<const floatx4*>(base + (size_t)min(gk, k_end - 1) * ld + gr_c);
+      const int left = (k_ok && (TOTAL % NT == 0 || tid + i * NT < TOTAL)) ? rows_total - gr : 0;   // valid components
+      keep[i] = left >= 4 ? 15 : (left <= 0 ? 0 : (1 << left) - 1);
+    }
+  }
+  __device__ __forceinline__ void mask() {
+#pragma unroll
+    for (int i = 0; i < ITER; ++i) {
+      reg[i].x = (keep[i] & 1) ? reg[i].x : 0.f;
+      reg[i].y = (keep[i] & 2) ? reg[i].y : 0.f;
+      reg[i].z = (keep[i] & 4) ? reg[i].z : 0.f;
+      reg[i].w = (keep[i] & 8) ? reg[i].w : 0.f;
     }
   }
   __device__ __forceinline__ void store(float* lds, int tid) const {
@@ -174,7 +191,7 @@ struct StageRC {
       if (TOTAL % NT == 0 || f < TOTAL) {
         const int k = f / F4_PER_K;
         const int r4 = (f % F4_PER_K) * 4;
-        *reinterpret_cast<float4*>(&lds[k * (ROWS + 4) + r4]) = reg[i];
+        *reinterpret_cast<floatx4*>(&lds[k * (ROWS + 4) + r4]) = reg[i];
       }
     }
   }
@@ -220,7 +237,7 @@ __device__ __forceinline__ float group16_sum(float v) {
 // L hold nearly parallel rows while the factor is still turning towards the data, and the weak directions then
 // sit in differences that fp32 accumulation wipes out.
 template <int BM, int BN, int BK, int WGM, int WGN, bool A_KC, bool B_KC, int EPI, bool SUMSQ_A, int ACC_CHUNK = 0,
-          bool ACC64 = false>
+          bool ACC64 = false, int PF = kPrefetch>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmGroup g) {
   using acc_t = typename AccType<ACC64>::type;
   constexpr int NT = WGM * WGN * 64;
@@ -241,12 +258,17 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmGroup g) 
   const int wm = wave / WGN, wn = wave % WGN;
   const int r16 = lane & 15, g4 = lane >> 4;
 
+  // Workgroups go to the eight accelerator dies round-robin by their index, and each die has its own L2: give
+  // every die one contiguous eighth of the unit list, so that the workgroups sharing an L2 share operand panels.
+  const int per_xcd = (g.total_tiles + kXcds - 1) / kXcds;
+  const int unit = ((int)blockIdx.x % kXcds) * per_xcd + (int)blockIdx.x / kXcds;
+  if (unit >= g.total_tiles) return;   // the grid is rounded up to a multiple of the die count
   int pi = 0;
   for (int i = 1; i < g.count; ++i)
-    if ((int)blockIdx.x >= g.p[i].tile_begin) pi = i;
+    if (unit >= g.p[i].tile_begin) pi = i;
   const GemmProblem& P = g.p[pi];
   if (P.gate != nullptr && ((*P.gate) & P.gate_mask) == 0) return;   // uniform over the workgroup
-  int local = blockIdx.x - P.tile_begin;
+  int local = unit - P.tile_begin;
   const int tn = local % P.tiles_n;
   local /= P.tiles_n;
   const int tm = local % P.tiles_m;
@@ -269,55 +291,92 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmGroup g) 
       if (ACC_CHUNK > 0) total[i][j] = acc_t{0, 0, 0, 0};
     }
 
-  StageA sa;
-  StageB sb;
   float ssq = 0.f;
   const int nk = (k_end - k_begin + BK - 1) / BK;
+  auto fold_chunk = [&](const int i, const bool more) {
+    if (ACC_CHUNK > 0 && ((i + 1) % (ACC_CHUNK > 0 ? ACC_CHUNK : 1) == 0 || !more)) {
+#pragma unroll
+      for (int ti = 0; ti < TM; ++ti)
+#pragma unroll
+        for (int tj = 0; tj < TN; ++tj) {
+          total[ti][tj] += acc[ti][tj];
+          acc[ti][tj] = acc_t{0, 0, 0, 0};
+        }
+    }
+  };
+  // Software pipeline: K-block i is multiplied out of LDS buffer i & 1 while block i+1 waits in registers to be
+  // written to the other buffer and blocks i+2 .. i+PF are still on their way from memory.  A workgroup that is
+  // alone on its compute unit (the layer GEMMs of one minibatch give only one or two per unit) has nobody to hide
+  // its memory latency behind; PF blocks in flight cover it.  Register set u holds block i+1 for i = u (mod PF).
+  StageA sa[PF];
+  StageB sb[PF];
   if (nk > 0) {
-    sa.load(P.A, P.lda, m0, M, k_begin, k_end, tid);
-    sb.load(P.B, P.ldb, n0, N, k_begin, k_end, tid);
-    if (SUMSQ_A) ssq += sa.sumsq();
-    sa.store(As, tid);
-    sb.store(Bs, tid);
+    sa[0].load(P.A, P.lda, m0, M, k_begin, k_end, tid);
+    sb[0].load(P.B, P.ldb, n0, N, k_begin, k_end, tid);
+    sa[0].mask();
+    sb[0].mask();
+    if (SUMSQ_A) ssq += sa[0].sumsq();
+    sa[0].store(As, tid);
+    sb[0].store(Bs, tid);
+#pragma unroll
+    for (int u = 0; u < PF; ++u) {
+      if (1 + u < nk) {
+        sa[u].load(P.A, P.lda, m0, M, k_begin + (1 + u) * BK, k_end, tid);
+        sb[u].load(P.B, P.ldb, n0, N, k_begin + (1 + u) * BK, k_end, tid);
+      }
+    }
   }
   __syncthreads();
-  for (int it = 0; it < nk; ++it) {
-    const int cur = it & 1;
-    const bool more = it + 1 < nk;
-    if (more) {
-      const int k0 = k_begin + (it + 1) * BK;
-      sa.load(P.A, P.lda, m0, M, k0, k_end, tid);
-      sb.load(P.B, P.ldb, n0, N, k0, k_end, tid);
-      if (SUMSQ_A) ssq += sa.sumsq();
-    }
+  // one K-block: multiply block i out of LDS, then pass block i+1 from register set u to LDS and refill the set
+  auto block_step = [&](const int i, const int u, const bool steady) {
+    const int cur = i & 1;
+    const bool more = steady || i + 1 < nk;
     const float* a_lds = As + cur * StageA::LDS_FLOATS;
     const float* b_lds = Bs + cur * StageB::LDS_FLOATS;
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
       float4 af[TM], bf[TN];
 #pragma unroll
-      for (int i = 0; i < TM; ++i) af[i] = StageA::frag(a_lds, wm * WM + i * 16 + r16, kk, g4);
+      for (int ti = 0; ti < TM; ++ti) af[ti] = StageA::frag(a_lds, wm * WM + ti * 16 + r16, kk, g4);
 #pragma unroll
-      for (int j = 0; j < TN; ++j) bf[j] = StageB::frag(b_lds, wn * WN + j * 16 + r16, kk, g4);
+      for (int tj = 0; tj < TN; ++tj) bf[tj] = StageB::frag(b_lds, wn * WN + tj * 16 + r16, kk, g4);
+      // one k value at a time over all TM x TN accumulators: consecutive MFMAs are independent, so a wave
+      // that is alone on its SIMD still issues them back to back
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+      for (int kq = 0; kq < 4; ++kq)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) mfma_k4(acc[i][j], af[i], bf[j]);
+        for (int ti = 0; ti < TM; ++ti)
+#pragma unroll
+          for (int tj = 0; tj < TN; ++tj) mfma_k1(acc[ti][tj], af[ti], bf[tj], kq);
     }
-    if (ACC_CHUNK > 0 && ((it + 1) % (ACC_CHUNK > 0 ? ACC_CHUNK : 1) == 0 || !more)) {
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          total[i][j] += acc[i][j];
-          acc[i][j] = acc_t{0, 0, 0, 0};
-        }
-    }
+    fold_chunk(i, more);
+    // nothing below may move above the products: touching the prefetched registers makes the wave wait for them
+    __builtin_amdgcn_sched_barrier(0);
     if (more) {
-      sa.store(As + (cur ^ 1) * StageA::LDS_FLOATS, tid);
-      sb.store(Bs + (cur ^ 1) * StageB::LDS_FLOATS, tid);
+      sa[u].mask();
+      sb[u].mask();
+      if (SUMSQ_A) ssq += sa[u].sumsq();   // here, not at the load: the data has had PF blocks' time to arrive
+      sa[u].store(As + (cur ^ 1) * StageA::LDS_FLOATS, tid);
+      sb[u].store(Bs + (cur ^ 1) * StageB::LDS_FLOATS, tid);
+      if (steady || i + 1 + PF < nk) {
+        const int k0 = k_begin + (i + 1 + PF) * BK;
+        sa[u].load(P.A, P.lda, m0, M, k0, k_end, tid);
+        sb[u].load(P.B, P.ldb, n0, N, k0, k_end, tid);
+      }
     }
     __syncthreads();
+  };
+  int it = 0;
+  // steady state: every block of the trip has a successor to store and a block PF ahead to fetch, so the body is
+  // straight-line code with a fixed number of loads in flight
+  for (; it + 2 * PF < nk; it += PF) {
+#pragma unroll
+    for (int u = 0; u < PF; ++u) block_step(it + u, u, true);
+  }
+  for (; it < nk; it += PF) {
+#pragma unroll
+    for (int u = 0; u < PF; ++u)
+      if (it + u < nk) block_step(it + u, u, false);   // uniform over the workgroup
   }
   if (ACC_CHUNK > 0) {
 #pragma unroll
@@ -446,7 +505,7 @@ inline void plan_tiles(const GemmDesc& d, GemmProblem& p) {
 }
 
 template <int BM, int BN, int BK, int WGM, int WGN, bool A_KC, bool B_KC, int EPI, bool SUMSQ_A, int ACC_CHUNK = 0,
-          bool ACC64 = false>
+          bool ACC64 = false, int PF = kPrefetch>
 inline hipError_t launch_gemm_group(const GemmDesc* descs, int count, hipStream_t stream) {
   int done = 0;
   while (done < count) {
@@ -461,8 +520,8 @@ inline hipError_t launch_gemm_group(const GemmDesc* descs, int count, hipStream_
     }
     grp.total_tiles = total;
     if (total > 0) {
-      hipLaunchKernelGGL((gemm_kernel<BM, BN, BK, WGM, WGN, A_KC, B_KC, EPI, SUMSQ_A, ACC_CHUNK, ACC64>),
-                         dim3(total),
+      hipLaunchKernelGGL((gemm_kernel<BM, BN, BK, WGM, WGN, A_KC, B_KC, EPI, SUMSQ_A, ACC_CHUNK, ACC64, PF>),
+                         dim3((total + kXcds - 1) / kXcds * kXcds),
                          dim3(WGM * WGN * 64), 0, stream, grp);
       hipError_t e = hipGetLastError();
       if (e != hipSuccess) return e;

@@ -238,43 +238,71 @@ inline int choose_splits(int tiles, int ksteps) {
 constexpr int BK = 16;
 
 enum LayerGemm { GEMM_FWD, GEMM_BWD, GEMM_UPD };
-constexpr int kBwdAccChunk = 8;     // K-blocks per MFMA chain in the backward GEMM
+constexpr int LBK = 32;             // K-block of the layer GEMMs
+constexpr int kBwdAccChunk = 4;     // K-blocks per MFMA chain in the backward GEMM (128 products per chain)
 constexpr int kMaxBwdSplits = 8;    // split-K slabs of the backward GEMM, summed by the nonlinearity's backward kernel
 
-inline bool layer_gemm_is_big(const GemmDesc* d, int n) {
-  long long big_tiles = 0;
-  for (int i = 0; i < n; ++i) big_tiles += (long long)((d[i].M + 127) / 128) * ((d[i].N + 127) / 128);
-  return big_tiles >= 400;
+// Tile shapes of the layer GEMMs.  The products of a minibatch step are small next to the chip (a few hundred
+// 64x64 tiles for 256 compute units), so what decides the time is how evenly the tiles fill it: every shape is
+// priced as (rounds of 256 workgroups) x (tile area), and the cheapest is taken.
+enum LayerTile { TILE_64x64, TILE_64x48, TILE_64x80, TILE_64x96, TILE_32x96, TILE_128x128, TILE_COUNT };
+constexpr int kTileBM[TILE_COUNT] = {64, 64, 64, 64, 32, 128};
+constexpr int kTileBN[TILE_COUNT] = {64, 48, 80, 96, 96, 128};
+constexpr int kComputeUnits = 256;
+
+inline LayerTile pick_layer_tile(const GemmDesc* d, int n) {
+  LayerTile best = TILE_64x64;
+  double best_cost = 0.0;
+  for (int t = 0; t < TILE_COUNT; ++t) {
+    long long tiles = 0;
+    for (int i = 0; i < n; ++i)
+      tiles += (long long)((d[i].M + kTileBM[t] - 1) / kTileBM[t]) * ((d[i].N + kTileBN[t] - 1) / kTileBN[t]) *
+               std::max(1, d[i].splits);
+    const double rounds = (double)((tiles + kComputeUnits - 1) / kComputeUnits);
+    const double area = (double)kTileBM[t] * kTileBN[t];
+    // a large tile does more work per byte staged (it wins once the rounds are many); among equals, more and
+    // smaller workgroups overlap each other's start-up better
+    const double cost = rounds * area * (t == TILE_128x128 ? 0.8 : 1.0) * (1.0 + 0.02 * area / 4096.0);
+    if (t == 0 || cost < best_cost) {
+      best_cost = cost;
+      best = (LayerTile)t;
+    }
+  }
+  return best;
 }
 
-// layer GEMMs: 128x128 tiles when they already fill the chip, 64x64 otherwise
+template <bool A_KC, bool B_KC, int CHUNK>
+hipError_t launch_layer_tile(LayerTile t, const GemmDesc* d, int n, hipStream_t s) {
+  switch (t) {
+    case TILE_64x48: return launch_gemm_group<64, 48, LBK, 4, 1, A_KC, B_KC, EPI_STORE, false, CHUNK>(d, n, s);
+    case TILE_64x80: return launch_gemm_group<64, 80, LBK, 4, 1, A_KC, B_KC, EPI_STORE, false, CHUNK>(d, n, s);
+    case TILE_64x96: return launch_gemm_group<64, 96, LBK, 2, 2, A_KC, B_KC, EPI_STORE, false, CHUNK>(d, n, s);
+    case TILE_32x96: return launch_gemm_group<32, 96, LBK, 2, 2, A_KC, B_KC, EPI_STORE, false, CHUNK>(d, n, s);
+    case TILE_128x128: return launch_gemm_group<128, 128, LBK, 2, 2, A_KC, B_KC, EPI_STORE, false, CHUNK>(d, n, s);
+    default: return launch_gemm_group<64, 64, LBK, 2, 2, A_KC, B_KC, EPI_STORE, false, CHUNK>(d, n, s);
+  }
+}
+
 int launch_layer_gemms(LayerGemm kind, const GemmDesc* d, int n, hipStream_t s) {
   ProfScope prof(kind == GEMM_FWD ? NGSGD_PROF_GEMM_FWD : (kind == GEMM_BWD ? NGSGD_PROF_GEMM_BWD : NGSGD_PROF_GEMM_UPD),
                  s);
-  const bool big = layer_gemm_is_big(d, n);
+  const LayerTile t = pick_layer_tile(d, n);
   hipError_t e = hipSuccess;
   switch (kind) {
-    case GEMM_FWD:
-      e = big ? launch_gemm_group<128, 128, BK, 2, 2, true, true, EPI_STORE, false>(d, n, s)
-              : launch_gemm_group<64, 64, BK, 2, 2, true, true, EPI_STORE, false>(d, n, s);
-      break;
-    case GEMM_BWD:   // long K (the layer's output dimension): two-level accumulation
-      e = big ? launch_gemm_group<128, 128, BK, 2, 2, true, false, EPI_STORE, false, kBwdAccChunk>(d, n, s)
-              : launch_gemm_group<64, 64, BK, 2, 2, true, false, EPI_STORE, false, kBwdAccChunk>(d, n, s);
-      break;
-    case GEMM_UPD:
-      e = big ? launch_gemm_group<128, 128, BK, 2, 2, false, false, EPI_STORE, false>(d, n, s)
-              : launch_gemm_group<64, 64, BK, 2, 2, false, false, EPI_STORE, false>(d, n, s);
-      break;
+    case GEMM_FWD: e = launch_layer_tile<true, true, 0>(t, d, n, s); break;
+    case GEMM_BWD: e = launch_layer_tile<true, false, kBwdAccChunk>(t, d, n, s); break;   // long K: two-level sums
+    case GEMM_UPD: e = launch_layer_tile<false, false, 0>(t, d, n, s); break;
   }
   HIP_TRY(e);
   return NGSGD_OK;
 }
 
-// H = X W^T (split over D, float atomics) with the sum of squares of X as a by-product
+// H = X W^T (split over D, float atomics) with the sum of squares of X as a by-product; two-level accumulation
+// (MFMA chains of 64 products) keeps the rounding error of a long split at the level of a short one
+constexpr int kHAccChunk = 4;
 template <int RC>
 hipError_t launch_h(const GemmDesc* d, int n, hipStream_t s) {
-  return launch_gemm_group<64, RC, BK, 4, 1, true, true, EPI_ATOMIC_F32, true>(d, n, s);
+  return launch_gemm_group<64, RC, BK, 4, 1, true, true, EPI_ATOMIC_F32, true, kHAccChunk>(d, n, s);
 }
 // J = H^T X, accumulated in fp64 and rounded once to fp32; narrow column tiles instead of a split over the rows
 template <int RC>
@@ -370,9 +398,13 @@ int join_side(SideSync* sync, hipStream_t s) {
 }
 
 // Split-K factor of the H = X W^T product of an N x D input (bounded by the room for its sum-of-squares partials).
-int h_splits(int N, int D) {
+// `group` is the number of instances that share the launch: the split only has to fill the chip once for all of
+// them, and a split shorter than kMinSplitSteps K-blocks would spend its time in the atomic epilogue.
+constexpr int kMinSplitSteps = 12;
+int h_splits(int N, int D, int group) {
   const int tiles_m = (N + 63) / 64, ksteps = (D + BK - 1) / BK;
-  int splits = choose_splits(tiles_m, ksteps);
+  int splits = choose_splits(tiles_m * (group > 0 ? group : 1), ksteps);
+  splits = std::min(splits, std::max(1, ksteps / kMinSplitSteps));
   while (splits > 1 && splits * tiles_m > kSumsqMax) --splits;
   return splits;
 }
@@ -432,6 +464,9 @@ int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStr
     done += n;
   }
   // H = X W^T   (eq. ht), tr(X X^T) partials
+  int class_count[3] = {0, 0, 0};   // instances per rank class (they share a launch)
+  for (auto& c : full) class_count[c.p->ldh == 32 ? 0 : (c.p->ldh == 80 ? 1 : 2)] += 1;
+  auto group_of = [&](const ngsgd_precond& p) { return class_count[p.ldh == 32 ? 0 : (p.ldh == 80 ? 1 : 2)]; };
   for (int rc : {32, 80, 96}) {
     std::vector<GemmDesc> d;
     for (auto& c : full) {
@@ -443,7 +478,7 @@ int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStr
       g.C = p.H; g.ldc = p.ldh;
       g.M = c.N; g.N = p.rank; g.K = p.dim;
       g.sumsq = p.sumsq_part;
-      g.splits = h_splits(c.N, p.dim);
+      g.splits = h_splits(c.N, p.dim, group_of(p));
       d.push_back(g);
     }
     if (d.empty()) continue;
@@ -508,7 +543,7 @@ int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStr
       a.sumsq_part = p.sumsq_part;
       GemmDesc hd;
       hd.M = c.N; hd.N = p.rank; hd.K = p.dim;
-      hd.splits = h_splits(c.N, p.dim);
+      hd.splits = h_splits(c.N, p.dim, group_of(p));
       a.n_sumsq = planned_sumsq_partials<64, 32, BK>(hd);   // independent of the tile width
       a.rownorm_part = p.rownorm_part;
       a.n_col_tiles = (p.dim + 63) / 64;
@@ -604,7 +639,7 @@ int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStr
         {
           GemmDesc hd;
           hd.M = c.N; hd.N = p.rank; hd.K = p.dim;
-          hd.splits = h_splits(c.N, p.dim);
+          hd.splits = h_splits(c.N, p.dim, group_of(p));
           a.n_sumsq = planned_sumsq_partials<64, 32, BK>(hd);   // independent of the tile width
         }
         OrthArgs& o = og.a[n];
@@ -1075,15 +1110,9 @@ extern "C" int ngsgd_step(ngsgd_net* net, const float* dev_x, const int32_t* dev
     // few output tiles and a long K: split K into slabs that the nonlinearity's backward kernel sums
     const size_t slab = (size_t)net->max_batch * net->lddx;
     g.c_split_stride = (long long)slab;
-    int n_slabs;
-    if (layer_gemm_is_big(&g, 1)) {
-      g.splits = 1;
-      n_slabs = 1;
-    } else {
-      const int tiles = ((N + 63) / 64) * ((L.din + 63) / 64);
-      g.splits = std::min(kMaxBwdSplits, choose_splits(tiles, (L.dout + BK - 1) / BK));
-      n_slabs = planned_splits<64, 64, BK>(g);
-    }
+    const int tiles = ((N + 63) / 64) * ((L.din + 63) / 64);
+    g.splits = std::min(kMaxBwdSplits, choose_splits(tiles, (L.dout + LBK - 1) / LBK));
+    const int n_slabs = planned_splits<64, 64, LBK>(g);   // depends on the K-block only, not on the tile shape
     NG_TRY(launch_layer_gemms(GEMM_BWD, &g, 1, s));
     ProfScope prof(NGSGD_PROF_ELEMENTWISE, s);
     if (P.nonlin == NGSGD_TANH) {
