@@ -140,6 +140,8 @@ struct ngsgd_precond {
   EigWork* eigwork = nullptr;
   bool owned_by_net = false;
   SideSync* sync = nullptr;   // set for instances of a network
+  int last_N = 0;             // rows of the latest call
+  int n_sumsq = 0;            // partial sums of tr(X X^T) its H product left in sumsq_part
 };
 
 namespace {
@@ -409,20 +411,30 @@ int h_splits(int N, int D, int group) {
   return splits;
 }
 
-// The online natural-gradient call (App. B.5) for a list of independent instances.  With
-// scale_output the matrices are left as gamma * Xhat; without it they are left as Xhat and gamma
-// stays in the instance's state for the caller to fold into a later product.  With `side` the factor
-// update (everything after J) is enqueued on the side stream.
-int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStream_t s, SideSync* side = nullptr) {
-  NG_TRY(ensure_kernel_attributes());
-  NG_TRY(join_side(side, s));
-  const hipStream_t main_stream = s;
-  std::vector<PrecondCall> full, to_init, to_update;
+// The online natural-gradient call (App. B.5) for a list of independent instances, in two phases.
+//
+// precond_apply: everything that touches the N x D matrices (initialisation on the first call, H, J when the
+// factor is going to be updated, Xhat, gamma).  With scale_output the matrices are left as gamma * Xhat; without
+// it they are left as Xhat and gamma stays in the instance's state for the caller to fold into a later product.
+// The instances whose factor is due for an update are appended to `to_update`.
+//
+// precond_factor_update: the R x R work and the new factor for those instances (App. B.3); it reads only what
+// the first phase left in the instances' buffers, so it can run on another stream while the caller goes on.
+int precond_validate(const std::vector<PrecondCall>& calls) {
   for (auto& c : calls) {
-    ngsgd_precond& p = *c.p;
+    const ngsgd_precond& p = *c.p;
     if (c.N < 1 || c.N > p.max_batch || c.ld < p.dim || (c.ld & 3) || !aligned16(c.M)) return NGSGD_EINVAL;
     if (p.rank > 0 && p.t == 0 && c.N <= p.rank) return NGSGD_EINVAL;
   }
+  return NGSGD_OK;
+}
+
+// With `side`, two events are recorded on s for a factor update that runs on the side stream: inputs_ready once
+// H, J and the partial sums of tr(X X^T) are final, outputs_done once the last reader of W_t has been enqueued.
+int precond_apply(std::vector<PrecondCall>& calls, bool scale_output, hipStream_t s, SideSync* side,
+                  std::vector<PrecondCall>& to_update_out) {
+  const hipStream_t main_stream = s;
+  std::vector<PrecondCall> full, to_init, to_update;
   for (auto& c : calls) {
     ngsgd_precond& p = *c.p;
     if (p.rank == 0) {
@@ -479,6 +491,11 @@ int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStr
       g.M = c.N; g.N = p.rank; g.K = p.dim;
       g.sumsq = p.sumsq_part;
       g.splits = h_splits(c.N, p.dim, group_of(p));
+      p.last_N = c.N;
+      {
+        GemmDesc hd = g;
+        p.n_sumsq = planned_sumsq_partials<64, 32, BK>(hd);   // independent of the tile width
+      }
       d.push_back(g);
     }
     if (d.empty()) continue;
@@ -509,10 +526,7 @@ int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStr
   // The factor update needs only H, J and the partial sums of tr(X X^T): with a side stream it starts here and
   // overlaps the rest of this call; it must not replace W_t before Xhat has read it (second event below).
   const bool on_side = side != nullptr && !to_update.empty();
-  if (on_side) {
-    HIP_TRY(hipEventRecord(side->inputs_ready, main_stream));
-    HIP_TRY(hipStreamWaitEvent(side->stream, side->inputs_ready, 0));
-  }
+  if (on_side) HIP_TRY(hipEventRecord(side->inputs_ready, main_stream));
   // Xhat = X - H W   (eq. hatxt:compute:2), row-norm partials (eq. pi)
   {
     std::vector<GemmDesc> d;
@@ -541,10 +555,7 @@ int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStr
       FinishArgs& a = g.a[i];
       a.st = p.st;
       a.sumsq_part = p.sumsq_part;
-      GemmDesc hd;
-      hd.M = c.N; hd.N = p.rank; hd.K = p.dim;
-      hd.splits = h_splits(c.N, p.dim, group_of(p));
-      a.n_sumsq = planned_sumsq_partials<64, 32, BK>(hd);   // independent of the tile width
+      a.n_sumsq = p.n_sumsq;
       a.rownorm_part = p.rownorm_part;
       a.n_col_tiles = (p.dim + 63) / 64;
       a.N = c.N;
@@ -565,11 +576,20 @@ int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStr
       LAUNCH_CHECK();
     }
   }
-  if (!to_update.empty()) {
-    if (on_side) {
-      HIP_TRY(hipEventRecord(side->outputs_done, main_stream));
-      s = side->stream;
-    }
+  if (on_side) HIP_TRY(hipEventRecord(side->outputs_done, main_stream));
+  to_update_out.insert(to_update_out.end(), to_update.begin(), to_update.end());
+  return NGSGD_OK;
+}
+
+// With `side` the work is enqueued on the side stream behind the two events of precond_apply; without it, on s.
+int precond_factor_update(std::vector<PrecondCall>& to_update, hipStream_t s, SideSync* side) {
+  if (to_update.empty()) return NGSGD_OK;
+  const bool on_side = side != nullptr;
+  if (on_side) {
+    HIP_TRY(hipStreamWaitEvent(side->stream, side->inputs_ready, 0));
+    s = side->stream;
+  }
+  {
     // K = J J^T, L = H^T H   (App. B.3), fp64 accumulation across the splits
     std::vector<GemmDesc> dk, dl;
     for (auto& c : to_update) {
@@ -586,8 +606,8 @@ int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStr
       h.A = p.H; h.lda = p.ldh;
       h.B = p.H; h.ldb = p.ldh;
       h.C = p.L; h.ldc = p.rank;
-      h.M = p.rank; h.N = p.rank; h.K = c.N;
-      h.splits = choose_splits(tiles * (int)to_update.size(), (c.N + BK - 1) / BK);
+      h.M = p.rank; h.N = p.rank; h.K = p.last_N;
+      h.splits = choose_splits(tiles * (int)to_update.size(), (p.last_N + BK - 1) / BK);
       dl.push_back(h);
     }
     {
@@ -607,7 +627,7 @@ int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStr
         const PrecondCall& c = to_update[done + n];
         ngsgd_precond& p = *c.p;
         if (p.num_samples_history != bg.num_samples_history) break;
-        bg.a[n] = BtArgs{p.J, p.W, p.st, p.ldw, p.dim, p.rank, c.N};
+        bg.a[n] = BtArgs{p.J, p.W, p.st, p.ldw, p.dim, p.rank, p.last_N};
         r_max = std::max(r_max, p.rank);
         d_max = std::max(d_max, p.dim);
         ++n;
@@ -633,15 +653,10 @@ int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStr
         if (p.alpha != g.alpha || p.epsilon != g.epsilon || p.num_samples_history != g.num_samples_history) break;
         SmallArgs& a = g.a[n];
         a.st = p.st; a.K = p.K; a.L = p.L; a.At = p.At; a.ldat = p.ldh;
-        a.R = p.rank; a.D = p.dim; a.N = c.N;
+        a.R = p.rank; a.D = p.dim; a.N = p.last_N;
         a.rotlog = p.rotlog; a.work = p.eigwork;
         a.sumsq_part = p.sumsq_part;
-        {
-          GemmDesc hd;
-          hd.M = c.N; hd.N = p.rank; hd.K = p.dim;
-          hd.splits = h_splits(c.N, p.dim, group_of(p));
-          a.n_sumsq = planned_sumsq_partials<64, 32, BK>(hd);   // independent of the tile width
-        }
+        a.n_sumsq = p.n_sumsq;
         OrthArgs& o = og.a[n];
         o.st = p.st; o.G = p.K; o.W = p.W; o.ld = p.ldw; o.R = p.rank; o.D = p.dim;
         r_max = std::max(r_max, p.rank);
@@ -721,11 +736,22 @@ int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStr
       }
       done += n;
     }
-    if (side != nullptr) {
+    if (on_side) {
       HIP_TRY(hipEventRecord(side->done, side->stream));
       side->pending = true;
     }
   }
+  return NGSGD_OK;
+}
+
+// Both phases for one list of instances; with `side` the second phase overlaps whatever the caller enqueues next.
+int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStream_t s, SideSync* side = nullptr) {
+  NG_TRY(ensure_kernel_attributes());
+  NG_TRY(precond_validate(calls));
+  NG_TRY(join_side(side, s));
+  std::vector<PrecondCall> to_update;
+  NG_TRY(precond_apply(calls, scale_output, s, side, to_update));
+  NG_TRY(precond_factor_update(to_update, s, side));
   for (auto& c : calls) c.p->t += 1;
   return NGSGD_OK;
 }
@@ -1125,7 +1151,8 @@ extern "C" int ngsgd_step(ngsgd_net* net, const float* dev_x, const int32_t* dev
     LAUNCH_CHECK();
   }
 
-  // natural gradient: both matrices of every layer (Sec. 4.6; 2I instances)
+  // natural gradient: both matrices of every layer (Sec. 4.6; 2I instances), one grouped call; the factor updates
+  // overlap the rest of this step and the next step's forward and backward passes on the side stream
   std::vector<PrecondCall> calls;
   for (auto& L : Ls) {
     calls.push_back(PrecondCall{&L.pout, L.A, L.lda, N, nullptr, nullptr});
