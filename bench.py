@@ -203,6 +203,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-precond", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 256 MiB device-to-device copy (the known-size reference for scaling "
+                         "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py measures one GPU: this build has no multi-GPU path (replicas only exchange parameters "
@@ -214,6 +217,13 @@ def main():
         sys.exit(1)
     torch.cuda.set_device(0)
     spec, ms_per_step, frames_per_s, roofline, breakdown, final_logp = run_step_bench(args)
+    if args.calibrate_copy:
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     precond = None if args.no_precond else run_precond_bench()
     cpu = None if args.no_cpu_baseline else run_cpu_baseline()
     result = {

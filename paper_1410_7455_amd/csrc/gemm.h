@@ -268,11 +268,20 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmGroup g) 
     if (unit >= g.p[i].tile_begin) pi = i;
   const GemmProblem& P = g.p[pi];
   if (P.gate != nullptr && ((*P.gate) & P.gate_mask) == 0) return;   // uniform over the workgroup
+  // Within a split the tiles are numbered along the shorter side of the tile grid first: a die's contiguous run of
+  // units then covers a compact patch, all of the small operand's panels but only its own share of the large one's.
   int local = unit - P.tile_begin;
-  const int tn = local % P.tiles_n;
-  local /= P.tiles_n;
-  const int tm = local % P.tiles_m;
-  const int split = local / P.tiles_m;
+  const int per_split = P.tiles_m * P.tiles_n;
+  const int split = local / per_split;
+  local -= split * per_split;
+  int tm, tn;
+  if (P.tiles_m <= P.tiles_n) {
+    tm = local % P.tiles_m;
+    tn = local / P.tiles_m;
+  } else {
+    tn = local % P.tiles_n;
+    tm = local / P.tiles_n;
+  }
   const int m0 = tm * BM, n0 = tn * BN;
   const int k_begin = split * P.k_per_split;
   const int k_end = min(P.K, k_begin + P.k_per_split);

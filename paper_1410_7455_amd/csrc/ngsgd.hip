@@ -246,7 +246,7 @@ constexpr int kMaxBwdSplits = 8;    // split-K slabs of the backward GEMM, summe
 
 // Tile shapes of the layer GEMMs.  The products of a minibatch step are small next to the chip (a few hundred
 // 64x64 tiles for 256 compute units), so what decides the time is how evenly the tiles fill it: every shape is
-// priced as (rounds of 256 workgroups) x (tile area), and the cheapest is taken.
+// priced as (rounds of 512 workgroups) x (tile area), and the cheapest is taken (the first listed among equals).
 enum LayerTile { TILE_64x64, TILE_64x48, TILE_64x80, TILE_64x96, TILE_32x96, TILE_128x128, TILE_COUNT };
 constexpr int kTileBM[TILE_COUNT] = {64, 64, 64, 64, 32, 128};
 constexpr int kTileBN[TILE_COUNT] = {64, 48, 80, 96, 96, 128};
@@ -260,11 +260,12 @@ inline LayerTile pick_layer_tile(const GemmDesc* d, int n) {
     for (int i = 0; i < n; ++i)
       tiles += (long long)((d[i].M + kTileBM[t] - 1) / kTileBM[t]) * ((d[i].N + kTileBN[t] - 1) / kTileBN[t]) *
                std::max(1, d[i].splits);
-    const double rounds = (double)((tiles + kComputeUnits - 1) / kComputeUnits);
+    // two workgroups per compute unit make a round: one alone leaves the matrix unit idle while it waits on LDS
+    // and memory, two overlap each other
+    const double rounds = (double)((tiles + 2 * kComputeUnits - 1) / (2 * kComputeUnits));
     const double area = (double)kTileBM[t] * kTileBN[t];
-    // a large tile does more work per byte staged (it wins once the rounds are many); among equals, more and
-    // smaller workgroups overlap each other's start-up better
-    const double cost = rounds * area * (t == TILE_128x128 ? 0.8 : 1.0) * (1.0 + 0.02 * area / 4096.0);
+    // a large tile does more work per byte staged: it wins once the rounds are many
+    const double cost = rounds * area * (t == TILE_128x128 ? 0.8 : 1.0);
     if (t == 0 || cost < best_cost) {
       best_cost = cost;
       best = (LayerTile)t;
