@@ -203,6 +203,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-precond", action="store_true")
+    ap.add_argument("--precond-only", action="store_true",
+                    help="run only the preconditioner microbenchmark (BASELINE configs[2]); used for its profile")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device-to-device copy (the known-size reference for scaling "
                          "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -216,6 +218,9 @@ def main():
         log("bench.py needs a GPU")
         sys.exit(1)
     torch.cuda.set_device(0)
+    if args.precond_only:
+        print(json.dumps({"precondition_roofline": run_precond_bench()}), flush=True)
+        return
     spec, ms_per_step, frames_per_s, roofline, breakdown, final_logp = run_step_bench(args)
     if args.calibrate_copy:
         src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")

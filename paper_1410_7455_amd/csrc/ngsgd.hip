@@ -310,7 +310,8 @@ hipError_t launch_h(const GemmDesc* d, int n, hipStream_t s) {
 // J = H^T X, accumulated in fp64 and rounded once to fp32; narrow column tiles instead of a split over the rows
 template <int RC>
 hipError_t launch_j(const GemmDesc* d, int n, hipStream_t s) {
-  return launch_gemm_group<RC, 32, BK, 1, 2, false, false, EPI_STORE, false, 0, true>(d, n, s);
+  if (RC == 32) return launch_gemm_group<32, 32, 32, 2, 2, false, false, EPI_STORE, false, 0, true>(d, n, s);
+  return launch_gemm_group<RC, 64, 32, 1, 4, false, false, EPI_STORE, false, 0, true>(d, n, s);
 }
 // W_{t+1} = A_t B_t
 template <int RC>
