@@ -155,6 +155,18 @@ def test_c1_full_size_first_steps(ngsgd):
     print("c1 worst errors, step by step", worst)
 
 
+def test_c3_wide_tanh_first_steps(ngsgd):
+    """BASELINE configs[3] at full size (440 -> 6 x tanh 2048 -> 8000, minibatch 1024, ranks 20 / 80): the tanh
+    kernels, 2049-wide inputs and an 8000-way softmax (the widest row the softmax kernel keeps in registers)."""
+    spec = workloads.c3_wide_tanh()
+    ora, gpu = make_pair(ngsgd, spec)
+    worst = run_and_compare(ngsgd, spec, ora, gpu, 2, ambiguous_first={(spec.n_layers - 1, ngsgd.NGSGD_SIDE_OUTPUT)})
+    print("c3 worst errors, free running", worst)
+    sync_from_oracle(ngsgd, spec, ora, gpu)
+    worst = run_and_compare(ngsgd, spec, ora, gpu, 3, first_step=2, sync_every_step=True)
+    print("c3 worst errors, step by step", worst)
+
+
 def test_step_argument_errors(ngsgd):
     import torch
     spec = workloads.c0_tiny()

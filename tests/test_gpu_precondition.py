@@ -226,4 +226,8 @@ def test_c2_full_size_shapes(ngsgd, which):
         assert rel(got, expect) < TOL, f"step {step}"
         assert g_g == pytest.approx(g_o, rel=1e-4)
         assert rel(rn_g, rn_o) < 2e-4
+        # the device-side eigen-solver reports what it did: it must have converged within its sweep budget
+        flags, sweeps = pre.diagnostics()
+        assert flags & 8 == 0, f"step {step}: the Jacobi iteration did not converge (flags {flags})"
+        assert 1 <= sweeps <= 20
     compare_states(torch, pre, ora, rng)
