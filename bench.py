@@ -37,6 +37,17 @@ def gemm_flops_per_step(spec, n):
     return dict(gemm_fwd=fwd, gemm_bwd=bwd, gemm_upd=fwd)
 
 
+def gemm_bytes_per_step(spec, n):
+    """Operands read once and the result written once (the update also reads the weights it adds to)."""
+    fwd = sum(4.0 * (n * (spec.in_dims[l] + 1) + (spec.in_dims[l] + 1) * spec.dims[l + 1] + n * spec.dims[l + 1])
+              for l in range(spec.n_layers))
+    bwd = sum(4.0 * (n * spec.dims[l + 1] + spec.in_dims[l] * spec.dims[l + 1] + n * spec.in_dims[l])
+              for l in range(1, spec.n_layers))
+    upd = sum(4.0 * (n * spec.dims[l + 1] + n * (spec.in_dims[l] + 1) + 2 * (spec.in_dims[l] + 1) * spec.dims[l + 1])
+              for l in range(spec.n_layers))
+    return dict(gemm_fwd=fwd, gemm_bwd=bwd, gemm_upd=upd)
+
+
 def precond_flops(n, d, r, update):
     f = 2.0 * n * d * r * 2            # H and Xhat
     if update:
@@ -48,6 +59,31 @@ def precond_flops(n, d, r, update):
 def precond_bytes(n, d, r, update):
     # read X once, write Xbar once, read W (and write it when the factor is updated)
     return 4.0 * (2.0 * n * d + (2.0 if update else 1.0) * r * d)
+
+
+def measured_traffic_per_launch(category):
+    """HBM bytes per launch of a layer-GEMM category, from the committed rocprofv3 --pmc summary (FETCH_SIZE and
+    WRITE_SIZE runs of this file, scaled by a plain copy of known size; see the summary for the commands).
+    None when the summary is missing or does not list the kernels."""
+    import re
+    # template arguments after the tile shape: A K-contiguous, B K-contiguous, epilogue, sum of squares, chunk, fp64
+    pattern = {"gemm_fwd": r"gemm_kernel<\d+, \d+, 32, \d, \d, true, true, 0, false, 0, false",
+               "gemm_bwd": r"gemm_kernel<\d+, \d+, 32, \d, \d, true, false, 0, false, 4, false",
+               "gemm_upd": r"gemm_kernel<\d+, \d+, 32, \d, \d, false, false, 0, false, 0, false"}.get(category)
+    path = os.path.join(ROOT, "profiles", "step_c1_pnorm_hbm_traffic.txt")
+    if pattern is None or not os.path.exists(path):
+        return None
+    calls = total = 0.0
+    for line in open(path):
+        if re.search(pattern, line):
+            cols = line.split()
+            try:
+                n, read_mb, write_mb = float(cols[-5]), float(cols[-2]), float(cols[-1])
+            except (ValueError, IndexError):
+                continue
+            calls += n
+            total += n * (read_mb + write_mb) * 1e6
+    return total / calls if calls > 0 else None
 
 
 def run_step_bench(args):
@@ -117,7 +153,9 @@ def run_step_bench(args):
     ms, cnt = prof[dominant]
     achieved = flops[dominant] * args.steps / (ms * 1e-3) / 1e12
     roofline = dict(bound="mfma", kernel=dominant, achieved=achieved, peak=PEAK_MFMA_F32_TFLOPS, unit="TFLOP/s",
-                    frac=achieved / PEAK_MFMA_F32_TFLOPS, traffic=None,
+                    frac=achieved / PEAK_MFMA_F32_TFLOPS, traffic=measured_traffic_per_launch(dominant),
+                    traffic_unit="bytes of HBM traffic per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, from profiles/)",
+                    algorithmic_bytes_per_launch=gemm_bytes_per_step(spec, n)[dominant] * args.steps / cnt,
                     flops_per_launch=flops[dominant] * args.steps / cnt, avg_launch_us=ms * 1e3 / cnt,
                     all_gemms_tflops=sum(flops.values()) * args.steps /
                     (sum(prof[k][0] for k in flops) * 1e-3) / 1e12)
@@ -168,6 +206,76 @@ def run_precond_bench(calls=200):
     return out
 
 
+def run_replica_bench(replicas=8, rounds=2, steps_per_round=200):
+    """BASELINE configs[4] in small: `replicas` copies of the configs[1] network resident on the one GPU, each
+    stepping on its own HIP stream over its own data shard, parameters averaged on the device between rounds
+    (which also resets the preconditioners, as the paper's re-spawned jobs do).  A single step leaves much of the
+    chip idle (a few hundred tiles for 256 compute units); independent replicas fill it."""
+    import torch
+
+    import paper_1410_7455_amd as ng
+    import workloads
+
+    spec = workloads.c1_pnorm()
+    n = spec.minibatch
+    nets, streams, pools, logps = [], [], [], []
+    weights = workloads.initial_weights(spec)
+    for r in range(replicas):
+        net = ng.Network(spec.dims, spec.nonlin, n, spec.pnorm_group, spec.rank_in, spec.rank_out, spec.alpha,
+                         spec.num_samples_history, spec.epsilon, spec.update_period, renorm=True,
+                         max_change_per_sample=0.075)
+        for l, w in enumerate(weights):
+            net.set_params(l, torch.from_numpy(w).cuda())
+        nets.append(net)
+        streams.append(torch.cuda.Stream())
+        logps.append(torch.zeros(1, dtype=torch.float64, device="cuda"))
+        pool = []
+        for t in range(4):
+            x, y = workloads.minibatch(spec, t, replica=r)
+            pool.append((torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda()))
+        pools.append(pool)
+    torch.cuda.synchronize()
+
+    def steps_on_streams(steps, t0):
+        for t in range(t0, t0 + steps):
+            for r in range(replicas):
+                with torch.cuda.stream(streams[r]):
+                    nets[r].step(*pools[r][t % 4], spec.lr, logps[r])
+        torch.cuda.synchronize()
+
+    steps_on_streams(12, 0)               # first initialisation of all factors: not timed
+    t_steady = t_avg = t_reinit = 0.0
+    step_no = 12
+    t_begin = time.perf_counter()
+    for k in range(rounds):
+        t0 = time.perf_counter()
+        steps_on_streams(steps_per_round, step_no)
+        t1 = time.perf_counter()
+        ng.average(nets, reset_preconditioners=True)
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        steps_on_streams(1, step_no + steps_per_round)   # rebuilds every factor from this minibatch (App. B.3.2)
+        t3 = time.perf_counter()
+        step_no += steps_per_round + 1
+        t_steady += t1 - t0
+        t_avg += t2 - t1
+        t_reinit += t3 - t2
+    elapsed = time.perf_counter() - t_begin
+    steady = n * replicas * rounds * steps_per_round / t_steady
+    overall = n * replicas * rounds * (steps_per_round + 1) / elapsed
+    last = [float(l.item()) / n for l in logps]
+    log(f"[bench] {replicas} interleaved replicas: {steady:,.0f} frames/s aggregate between averaging points "
+        f"({rounds} x {steps_per_round} steps each), averaging {t_avg * 1e3 / rounds:.2f} ms, re-initialisation step "
+        f"{t_reinit * 1e3 / rounds:.1f} ms, {overall:,.0f} frames/s overall; last mean log-probs "
+        f"{min(last):.3f} .. {max(last):.3f}")
+    return dict(workload="configs[4] shape: replicas of configs[1] interleaved on HIP streams, on-device averaging "
+                         "with preconditioner reset between rounds",
+                replicas=replicas, rounds=rounds, steps_per_round=steps_per_round, value=steady, unit="frames/s",
+                ms_per_replica_step=t_steady * 1e3 / (replicas * rounds * steps_per_round),
+                averaging_ms=t_avg * 1e3 / rounds, reinitialisation_step_ms=t_reinit * 1e3 / rounds,
+                overall_frames_per_s=overall)
+
+
 def run_cpu_baseline(max_steps=20, budget_s=25.0):
     """The float64 oracle as it stands, timed on the host cores on a bounded sample of the same workload."""
     import workloads
@@ -203,6 +311,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-precond", action="store_true")
+    ap.add_argument("--no-replicas", action="store_true")
     ap.add_argument("--precond-only", action="store_true",
                     help="run only the preconditioner microbenchmark (BASELINE configs[2]); used for its profile")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -230,6 +339,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     precond = None if args.no_precond else run_precond_bench()
+    replica = None if args.no_replicas else run_replica_bench()
     cpu = None if args.no_cpu_baseline else run_cpu_baseline()
     result = {
         "metric": "NG-SGD training frames/sec (p-norm DNN, mb 512) + precondition % roofline",
@@ -255,6 +365,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "precondition_roofline": precond,
+        "replica_interleaving": replica,
         "breakdown": breakdown,
     }
     print(json.dumps(result), flush=True)
