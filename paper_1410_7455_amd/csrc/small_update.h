@@ -15,20 +15,13 @@
 namespace ngsgd {
 
 constexpr int kSmallThreads = 1024;          // orthogonality fix kernel
-#ifndef NGSGD_EIG_NT
-#define NGSGD_EIG_NT 1024
-#endif
-constexpr int kEigThreads = NGSGD_EIG_NT;    // R x R eigen-update kernel
+constexpr int kEigThreads = 1024;            // R x R eigen-update kernel
 // most 2x2 blocks of the upper triangle one thread may own
 constexpr int kEigMaxItems = ((kMaxRank / 2) * (kMaxRank / 2 + 1) / 2 + kEigThreads - 1) / kEigThreads;
 
 constexpr int kEigvecThreads = 256;          // eigenvector kernel: 4 wavefronts, one row of U each
 constexpr int kEigvecChunk = 32;             // rounds of the rotation log staged in LDS at a time
 constexpr int kMaxSweeps = 20;
-#ifndef NGSGD_EIG_BLOCK_DELAY
-#define NGSGD_EIG_BLOCK_DELAY 2
-#endif
-constexpr int kEigBlockDelay = NGSGD_EIG_BLOCK_DELAY;   // in units of 64 clocks
 constexpr int kMaxHalf = kMaxRank / 2;
 constexpr int kMaxRounds = kMaxSweeps * (kMaxRank - 1);
 constexpr double kJacobiTol = 1.0e-13;       // a pair is left alone once |z_pq| <= tol * sqrt(z_pp z_qq)
@@ -301,18 +294,11 @@ __global__ __launch_bounds__(NT) void eig_update_kernel(const SmallGroup g) {
   // cyclic Jacobi; a sweep in which no pair needed a large rotation ends the iteration
   int sweeps = 0, rounds = 0, cur = 0;
   bool converged = false;
-#ifdef NGSGD_EIG_TIMING
-  long long tm_rot = 0, tm_blk = 0, tm_bar = 0, tm_ld = 0, tm_ch = 0;
-  const long long tm_start = clock64();
-#endif
   for (; sweeps < kMaxSweeps && !converged; ++sweeps) {
     for (int r = 0; r < m - 1; ++r, ++rounds, cur ^= 1) {
       const int co = cur ? zcopy : 0, no = cur ? 0 : zcopy;
       const double* rc = s_rc[cur];
       const double* rs = s_rs[cur];
-#ifdef NGSGD_EIG_TIMING
-      const long long tA = clock64();
-#endif
       if (rot_lane) {
         double c = 1.0, s = 0.0;
         if (half >= 2 && !(odd_pad && rot_k == 0)) {
@@ -322,11 +308,6 @@ __global__ __launch_bounds__(NT) void eig_update_kernel(const SmallGroup g) {
           const double da_tt = dyn[co + rz_da], da_tb = dyn[co + np + rz_da], da_bb = dyn[co + 3 * np + rz_da];
           const double db_tt = dyn[co + rz_db], db_tb = dyn[co + np + rz_db], db_bb = dyn[co + 3 * np + rz_db];
           __builtin_amdgcn_sched_barrier(0);   // all reads are in flight before the first use
-#ifdef NGSGD_EIG_TIMING
-          asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-          const long long tL = clock64();
-          tm_ld += tL - tA;
-#endif
           // a first member takes (c, -s) of its pair's rotation, a second member (s, c)
           const double r0 = rz_sb0 ? ci : si, r1 = rz_sb0 ? -si : ci;
           const double q0 = rz_sa0 ? cj : sj, q1 = rz_sa0 ? -sj : cj;
@@ -338,20 +319,10 @@ __global__ __launch_bounds__(NT) void eig_update_kernel(const SmallGroup g) {
           jacobi_rotation(zaa, zbb, zab, abs_tol2, c, s, large);
           if (large) s_rotated[(sweeps + (r == m - 2 ? 1 : 0)) & 1] = 1;
         }
-#ifdef NGSGD_EIG_TIMING
-        asm volatile("" :: "v"(c), "v"(s) : "memory");
-        const long long tS = clock64();
-        tm_ch += tS - tA;
-#endif
         s_rc[cur ^ 1][rot_k] = c;
         s_rs[cur ^ 1][rot_k] = s;
         rotlog[(size_t)(rounds + 1) * half + rot_k] = make_double2(c, s);
       }
-#ifdef NGSGD_EIG_TIMING
-      const long long tB = clock64();
-#endif
-      // the other waves hold back for a moment so that the rotation wave's few reads are not queued behind theirs
-      if (tid < nt - 64) __builtin_amdgcn_s_sleep(kEigBlockDelay);
 #pragma unroll
       for (int it = 0; it < ITEMS; ++it) {
         const int t = tid + it * nt;
@@ -372,25 +343,13 @@ __global__ __launch_bounds__(NT) void eig_update_kernel(const SmallGroup g) {
         dyn[no + dst[it][2]] = y10 * cj - y11 * sj;
         dyn[no + dst[it][3]] = y10 * sj + y11 * cj;
       }
-#ifdef NGSGD_EIG_TIMING
-      const long long tC = clock64();
-#endif
       __syncthreads();
-#ifdef NGSGD_EIG_TIMING
-      const long long tD = clock64();
-      tm_rot += tB - tA; tm_blk += tC - tB; tm_bar += tD - tC;
-#endif
     }
     if (s_rotated[sweeps & 1] == 0) converged = true;   // same value for every thread: read after the barrier
     __syncthreads();                                    // everyone has read the flag before it is cleared again
     if (tid == 0) s_rotated[sweeps & 1] = 0;
   }
 
-#ifdef NGSGD_EIG_TIMING
-  if ((tid & 63) == 0 && R >= 64)
-    printf("eig R=%d wave %d rounds %d total %lld rot %lld blk %lld bar %lld ld %lld ch %lld\n", R, tid >> 6, rounds,
-           (long long)(clock64() - tm_start), tm_rot, tm_blk, tm_bar, tm_ld, tm_ch);
-#endif
   // eigenvalues (by player), floor (after eq. zt:eig:repeat), decreasing order
   const int fo = cur ? zcopy : 0;
   const double floor_c = (1.0 - eta) * (1.0 - eta) * rho * rho;
