@@ -86,6 +86,13 @@ struct AccType<true> {
 };
 
 // ---- global -> register -> LDS staging ---------------------------------------------------------
+// The staging objects keep one global pointer and one LDS offset per 16-byte piece, set up once per tile: the
+// K loop only advances the pointers by a constant.  (With the address arithmetic, bounds selects and clamps in
+// the loop, a wave that is alone on its SIMD spent about 600 of its 2100 cycles per K-block issuing them.)
+// Rows beyond the operand are read from a clamped, valid address and left as they are: row m of A and row n of B
+// only ever reach C(m, n), which is not stored for rows outside the problem.  Only the K tail has to be zeroed,
+// and only in a tile's last K-block.  Relies on ld being a multiple of 4 that covers the contiguous extent.
+//
 // K-contiguous operand: element (row, k) at base[row*ld + k]; LDS layout [ROWS][BK+4].
 template <int ROWS, int BK, int NT>
 struct StageKC {
@@ -93,54 +100,56 @@ struct StageKC {
   static constexpr int TOTAL = ROWS * F4_PER_ROW;
   static constexpr int ITER = (TOTAL + NT - 1) / NT;
   static constexpr int LDS_FLOATS = ROWS * (BK + 4);
-  floatx4 reg[ITER];
-  int keep[ITER];   // bit c set: component c of the piece lies inside the operand
+  using Regs = floatx4[ITER];   // one K-block's share of this thread; the caller keeps several in flight
+  const float* ptr[ITER];   // where this thread's piece of the next K-block starts
+  int kq[ITER];             // k offset of the piece inside a K-block
+  int lds_off[ITER];        // -1: surplus lane (TOTAL is not a multiple of NT), nothing to store
+  float row_ok[ITER];       // 1 for rows inside the operand (only the sum of squares needs it)
 
-  // Branch-free: rows and k beyond the operand are read from a clamped (valid) address and zeroed by selects, so
-  // the loads are straight-line code and the compiler can keep several K-blocks in flight with exact wait counts.
-  // Relies on ld being a multiple of 4 that covers the K extent (every float4 of a row lies inside the row).
-  __device__ __forceinline__ void load(const float* __restrict__ base, int ld, int row0, int rows_total,
-                                       int k0, int k_end, int tid) {
+  __device__ __forceinline__ void init(const float* __restrict__ base, int ld, int row0, int rows_total, int k_begin,
+                                       int tid) {
 #pragma unroll
     for (int i = 0; i < ITER; ++i) {
-      const int f = min(tid + i * NT, TOTAL - 1);   // surplus lanes repeat the last piece (never stored)
+      const int f = min(tid + i * NT, TOTAL - 1);
       const int r = f / F4_PER_ROW;
-      const int gk = k0 + (f % F4_PER_ROW) * 4;
+      kq[i] = (f % F4_PER_ROW) * 4;
       const int gr = row0 + r;
-      const bool row_ok = gr < rows_total;
-      const int gk_c = min(gk, (k_end - 1) & ~3);
-      reg[i] = *reinterpret_cast<const floatx4*>(base + (size_t)min(gr, rows_total - 1) * ld + gk_c);
-      const int left = (row_ok && (TOTAL % NT == 0 || tid + i * NT < TOTAL)) ? k_end - gk : 0;   // valid components
-      keep[i] = left >= 4 ? 15 : (left <= 0 ? 0 : (1 << left) - 1);
+      ptr[i] = base + (size_t)min(gr, rows_total - 1) * ld + k_begin + kq[i];
+      lds_off[i] = (TOTAL % NT == 0 || tid + i * NT < TOTAL) ? r * (BK + 4) + kq[i] : -1;
+      row_ok[i] = (gr < rows_total && lds_off[i] >= 0) ? 1.f : 0.f;
     }
   }
-  // Zeroes the components that lie outside the operand; called when the data is consumed (not at the load: a use
-  // of the loaded value would make the wave wait for it there and then).
-  __device__ __forceinline__ void mask() {
+  // loads the K-block that starts at k0 and steps the pointers to the next one; `last`: the block may reach past k_end
+  __device__ __forceinline__ void load(Regs& reg, int k0, int k_end, bool last) {
 #pragma unroll
     for (int i = 0; i < ITER; ++i) {
-      reg[i].x = (keep[i] & 1) ? reg[i].x : 0.f;
-      reg[i].y = (keep[i] & 2) ? reg[i].y : 0.f;
-      reg[i].z = (keep[i] & 4) ? reg[i].z : 0.f;
-      reg[i].w = (keep[i] & 8) ? reg[i].w : 0.f;
+      const float* p = ptr[i];
+      if (last) p -= max(0, k0 + kq[i] - ((k_end - 1) & ~3));   // stay inside the row: the piece is masked anyway
+      reg[i] = *reinterpret_cast<const floatx4*>(p);
+      ptr[i] += BK;
     }
   }
-  __device__ __forceinline__ void store(float* lds, int tid) const {
+  // zeroes what lies past k_end (called for a tile's last K-block only, when the registers are consumed)
+  __device__ __forceinline__ void mask_tail(Regs& reg, int k0, int k_end) const {
 #pragma unroll
     for (int i = 0; i < ITER; ++i) {
-      const int f = tid + i * NT;
-      if (TOTAL % NT == 0 || f < TOTAL) {
-        const int r = f / F4_PER_ROW;
-        const int kq = (f % F4_PER_ROW) * 4;
-        *reinterpret_cast<floatx4*>(&lds[r * (BK + 4) + kq]) = reg[i];
-      }
+      const int left = k_end - (k0 + kq[i]);
+      reg[i].x = left > 0 ? reg[i].x : 0.f;
+      reg[i].y = left > 1 ? reg[i].y : 0.f;
+      reg[i].z = left > 2 ? reg[i].z : 0.f;
+      reg[i].w = left > 3 ? reg[i].w : 0.f;
     }
   }
-  __device__ __forceinline__ float sumsq() const {
+  __device__ __forceinline__ void store(const Regs& reg, float* lds) const {
+#pragma unroll
+    for (int i = 0; i < ITER; ++i)
+      if (TOTAL % NT == 0 || lds_off[i] >= 0) *reinterpret_cast<floatx4*>(&lds[lds_off[i]]) = reg[i];
+  }
+  __device__ __forceinline__ float sumsq(const Regs& reg) const {
     float s = 0.f;
 #pragma unroll
     for (int i = 0; i < ITER; ++i)
-      s += reg[i].x * reg[i].x + reg[i].y * reg[i].y + reg[i].z * reg[i].z + reg[i].w * reg[i].w;
+      s += row_ok[i] * (reg[i].x * reg[i].x + reg[i].y * reg[i].y + reg[i].z * reg[i].z + reg[i].w * reg[i].w);
     return s;
   }
   // fragment for MFMA tile at tile row offset `row` and k-group kk (16 k values each)
@@ -156,50 +165,60 @@ struct StageRC {
   static constexpr int TOTAL = BK * F4_PER_K;
   static constexpr int ITER = (TOTAL + NT - 1) / NT;
   static constexpr int LDS_FLOATS = BK * (ROWS + 4);
-  floatx4 reg[ITER];
-  int keep[ITER];
+  using Regs = floatx4[ITER];
+  const float* ptr[ITER];
+  int kq[ITER];             // k index of the piece inside a K-block
+  int lds_off[ITER];
+  float row_ok[ITER][4];    // per component (rows are the contiguous direction here)
+  size_t block_stride;      // BK * ld
 
-  // Branch-free like the K-contiguous loader; relies on ld being a multiple of 4 that covers the row extent.
-  __device__ __forceinline__ void load(const float* __restrict__ base, int ld, int row0, int rows_total,
-                                       int k0, int k_end, int tid) {
+  __device__ __forceinline__ void init(const float* __restrict__ base, int ld, int row0, int rows_total, int k_begin,
+                                       int tid) {
+    block_stride = (size_t)BK * ld;
 #pragma unroll
     for (int i = 0; i < ITER; ++i) {
       const int f = min(tid + i * NT, TOTAL - 1);
-      const int k = f / F4_PER_K;
-      const int gr = row0 + (f % F4_PER_K) * 4;
-      const int gk = k0 + k;
-      const bool k_ok = gk < k_end;
-      const int gr_c = min(gr, (rows_total - 1) & ~3);
-      reg[i] = *reinterpret_cast<const floatx4*>(base + (size_t)min(gk, k_end - 1) * ld + gr_c);
-      const int left = (k_ok && (TOTAL % NT == 0 || tid + i * NT < TOTAL)) ? rows_total - gr : 0;   // valid components
-      keep[i] = left >= 4 ? 15 : (left <= 0 ? 0 : (1 << left) - 1);
+      kq[i] = f / F4_PER_K;
+      const int r4 = (f % F4_PER_K) * 4;
+      const int gr = row0 + r4;
+      ptr[i] = base + (size_t)(k_begin + kq[i]) * ld + min(gr, (rows_total - 1) & ~3);
+      lds_off[i] = (TOTAL % NT == 0 || tid + i * NT < TOTAL) ? kq[i] * (ROWS + 4) + r4 : -1;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) row_ok[i][c] = (gr + c < rows_total && lds_off[i] >= 0) ? 1.f : 0.f;
     }
+    ld_ = ld;
   }
-  __device__ __forceinline__ void mask() {
+  int ld_;
+  __device__ __forceinline__ void load(Regs& reg, int k0, int k_end, bool last) {
 #pragma unroll
     for (int i = 0; i < ITER; ++i) {
-      reg[i].x = (keep[i] & 1) ? reg[i].x : 0.f;
-      reg[i].y = (keep[i] & 2) ? reg[i].y : 0.f;
-      reg[i].z = (keep[i] & 4) ? reg[i].z : 0.f;
-      reg[i].w = (keep[i] & 8) ? reg[i].w : 0.f;
+      const float* p = ptr[i];
+      if (last) p -= (size_t)max(0, k0 + kq[i] - (k_end - 1)) * ld_;   // stay inside the operand: masked anyway
+      reg[i] = *reinterpret_cast<const floatx4*>(p);
+      ptr[i] += block_stride;
     }
   }
-  __device__ __forceinline__ void store(float* lds, int tid) const {
+  __device__ __forceinline__ void mask_tail(Regs& reg, int k0, int k_end) const {
 #pragma unroll
     for (int i = 0; i < ITER; ++i) {
-      const int f = tid + i * NT;
-      if (TOTAL % NT == 0 || f < TOTAL) {
-        const int k = f / F4_PER_K;
-        const int r4 = (f % F4_PER_K) * 4;
-        *reinterpret_cast<floatx4*>(&lds[k * (ROWS + 4) + r4]) = reg[i];
-      }
+      const bool ok = k0 + kq[i] < k_end;
+      reg[i].x = ok ? reg[i].x : 0.f;
+      reg[i].y = ok ? reg[i].y : 0.f;
+      reg[i].z = ok ? reg[i].z : 0.f;
+      reg[i].w = ok ? reg[i].w : 0.f;
     }
   }
-  __device__ __forceinline__ float sumsq() const {
+  __device__ __forceinline__ void store(const Regs& reg, float* lds) const {
+#pragma unroll
+    for (int i = 0; i < ITER; ++i)
+      if (TOTAL % NT == 0 || lds_off[i] >= 0) *reinterpret_cast<floatx4*>(&lds[lds_off[i]]) = reg[i];
+  }
+  __device__ __forceinline__ float sumsq(const Regs& reg) const {
     float s = 0.f;
 #pragma unroll
     for (int i = 0; i < ITER; ++i)
-      s += reg[i].x * reg[i].x + reg[i].y * reg[i].y + reg[i].z * reg[i].z + reg[i].w * reg[i].w;
+      s += row_ok[i][0] * reg[i].x * reg[i].x + row_ok[i][1] * reg[i].y * reg[i].y + row_ok[i][2] * reg[i].z * reg[i].z +
+           row_ok[i][3] * reg[i].w * reg[i].w;
     return s;
   }
   __device__ __forceinline__ static float4 frag(const float* lds, int row, int kk, int g) {
@@ -314,26 +333,35 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmGroup g) 
     }
   };
   // Software pipeline: K-block i is multiplied out of LDS buffer i & 1 while block i+1 waits in registers to be
-  // written to the other buffer and blocks i+2 .. i+PF are still on their way from memory.  A workgroup that is
-  // alone on its compute unit (the layer GEMMs of one minibatch give only one or two per unit) has nobody to hide
-  // its memory latency behind; PF blocks in flight cover it.  Register set u holds block i+1 for i = u (mod PF).
-  StageA sa[PF];
-  StageB sb[PF];
-  if (nk > 0) {
-    sa[0].load(P.A, P.lda, m0, M, k_begin, k_end, tid);
-    sb[0].load(P.B, P.ldb, n0, N, k_begin, k_end, tid);
-    sa[0].mask();
-    sb[0].mask();
-    if (SUMSQ_A) ssq += sa[0].sumsq();
-    sa[0].store(As, tid);
-    sb[0].store(Bs, tid);
-#pragma unroll
-    for (int u = 0; u < PF; ++u) {
-      if (1 + u < nk) {
-        sa[u].load(P.A, P.lda, m0, M, k_begin + (1 + u) * BK, k_end, tid);
-        sb[u].load(P.B, P.ldb, n0, N, k_begin + (1 + u) * BK, k_end, tid);
-      }
+  // written to the other buffer and blocks i+2 .. i+PF are still on their way from memory.  Register set u holds
+  // block i+1 for i = u (mod PF).  Blocks are requested in increasing order, so one set of pointers serves all.
+  StageA sa;
+  StageB sb;
+  typename StageA::Regs ra[PF];
+  typename StageB::Regs rb[PF];
+  sa.init(P.A, P.lda, m0, M, k_begin, tid);
+  sb.init(P.B, P.ldb, n0, N, k_begin, tid);
+  auto fetch = [&](const int blk, const int set) {   // block `blk` of this tile into register set `set`
+    const int k0 = k_begin + blk * BK;
+    const bool last = blk == nk - 1;
+    sa.load(ra[set], k0, k_end, last);
+    sb.load(rb[set], k0, k_end, last);
+  };
+  auto commit = [&](const int blk, const int set, const int buf) {   // register set -> LDS buffer
+    if (blk == nk - 1) {
+      sa.mask_tail(ra[set], k_begin + blk * BK, k_end);
+      sb.mask_tail(rb[set], k_begin + blk * BK, k_end);
     }
+    if (SUMSQ_A) ssq += sa.sumsq(ra[set]);
+    sa.store(ra[set], As + buf * StageA::LDS_FLOATS);
+    sb.store(rb[set], Bs + buf * StageB::LDS_FLOATS);
+  };
+  if (nk > 0) {
+    fetch(0, 0);
+    commit(0, 0, 0);
+#pragma unroll
+    for (int u = 0; u < PF; ++u)
+      if (1 + u < nk) fetch(1 + u, u);
   }
   __syncthreads();
   // one K-block: multiply block i out of LDS, then pass block i+1 from register set u to LDS and refill the set
@@ -362,16 +390,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmGroup g) 
     // nothing below may move above the products: touching the prefetched registers makes the wave wait for them
     __builtin_amdgcn_sched_barrier(0);
     if (more) {
-      sa[u].mask();
-      sb[u].mask();
-      if (SUMSQ_A) ssq += sa[u].sumsq();   // here, not at the load: the data has had PF blocks' time to arrive
-      sa[u].store(As + (cur ^ 1) * StageA::LDS_FLOATS, tid);
-      sb[u].store(Bs + (cur ^ 1) * StageB::LDS_FLOATS, tid);
-      if (steady || i + 1 + PF < nk) {
-        const int k0 = k_begin + (i + 1 + PF) * BK;
-        sa[u].load(P.A, P.lda, m0, M, k0, k_end, tid);
-        sb[u].load(P.B, P.ldb, n0, N, k0, k_end, tid);
-      }
+      commit(i + 1, u, cur ^ 1);   // (in the steady state block i+1 is never the last one: no tail to mask)
+      if (steady || i + 1 + PF < nk) fetch(i + 1 + PF, u);
     }
     __syncthreads();
   };
