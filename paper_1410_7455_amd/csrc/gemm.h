@@ -236,11 +236,13 @@ struct StageSelect<false, ROWS, BK, NT> {
   using type = StageRC<ROWS, BK, NT>;
 };
 
+// Sum over the 16 lanes of a DPP row, through the vector ALU's cross-lane path (no LDS traffic): xor 1 and xor 2
+// inside a quad, then the two mirrors pair quads and half rows.  Every lane ends up with the total.
 __device__ __forceinline__ float group16_sum(float v) {
-  v += __shfl_xor(v, 1);
-  v += __shfl_xor(v, 2);
-  v += __shfl_xor(v, 4);
-  v += __shfl_xor(v, 8);
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xf, 0xf, true));   // quad_perm [1,0,3,2]
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xf, 0xf, true));   // quad_perm [2,3,0,1]
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xf, 0xf, true));  // row_half_mirror
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xf, 0xf, true));  // row_mirror
   return v;
 }
 

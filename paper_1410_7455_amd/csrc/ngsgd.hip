@@ -301,10 +301,11 @@ int launch_layer_gemms(LayerGemm kind, const GemmDesc* d, int n, hipStream_t s) 
 
 // H = X W^T (split over D, float atomics) with the sum of squares of X as a by-product; two-level accumulation
 // (MFMA chains of 64 products) keeps the rounding error of a long split at the level of a short one
-constexpr int kHAccChunk = 4;
+constexpr int HBK = 32;          // K-block of the H product
+constexpr int kHAccChunk = 2;
 template <int RC>
 hipError_t launch_h(const GemmDesc* d, int n, hipStream_t s) {
-  return launch_gemm_group<64, RC, BK, 4, 1, true, true, EPI_ATOMIC_F32, true, kHAccChunk>(d, n, s);
+  return launch_gemm_group<64, RC, HBK, 4, 1, true, true, EPI_ATOMIC_F32, true, kHAccChunk>(d, n, s);
 }
 // J = H^T X, accumulated in fp64 and rounded once to fp32; narrow column tiles instead of a split over the rows
 template <int RC>
@@ -403,9 +404,9 @@ int join_side(SideSync* sync, hipStream_t s) {
 // Split-K factor of the H = X W^T product of an N x D input (bounded by the room for its sum-of-squares partials).
 // `group` is the number of instances that share the launch: the split only has to fill the chip once for all of
 // them, and a split shorter than kMinSplitSteps K-blocks would spend its time in the atomic epilogue.
-constexpr int kMinSplitSteps = 12;
+constexpr int kMinSplitSteps = 6;
 int h_splits(int N, int D, int group) {
-  const int tiles_m = (N + 63) / 64, ksteps = (D + BK - 1) / BK;
+  const int tiles_m = (N + 63) / 64, ksteps = (D + HBK - 1) / HBK;
   int splits = choose_splits(tiles_m * (group > 0 ? group : 1), ksteps);
   splits = std::min(splits, std::max(1, ksteps / kMinSplitSteps));
   while (splits > 1 && splits * tiles_m > kSumsqMax) --splits;
@@ -495,7 +496,7 @@ int precond_apply(std::vector<PrecondCall>& calls, bool scale_output, hipStream_
       p.last_N = c.N;
       {
         GemmDesc hd = g;
-        p.n_sumsq = planned_sumsq_partials<64, 32, BK>(hd);   // independent of the tile width
+        p.n_sumsq = planned_sumsq_partials<64, 32, HBK>(hd);   // independent of the tile width
       }
       d.push_back(g);
     }
