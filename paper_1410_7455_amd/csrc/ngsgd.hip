@@ -672,7 +672,8 @@ int precond_factor_update(std::vector<PrecondCall>& to_update, hipStream_t s, Si
           const int m_max = (r_max + 1) & ~1;
           const int n_blocks = (m_max / 2) * (m_max / 2 + 1) / 2;   // 2x2 blocks of the upper triangle
           const size_t eig_dyn = (size_t)2 * 4 * n_blocks * sizeof(double);   // two copies of four planes
-          const int items = (n_blocks + kEigThreads - 1) / kEigThreads;
+          const int n_off = (m_max / 2) * (m_max / 2 - 1) / 2;   // off-diagonal blocks, owned by the waves after the first
+          const int items = std::max(1, (n_off + (kEigThreads - 64) - 1) / (kEigThreads - 64));
           if (items <= 1) {
             hipLaunchKernelGGL((eig_update_kernel<1, kEigThreads>), dim3(n), dim3(kEigThreads), eig_dyn, s, g);
           } else if (items == 2) {

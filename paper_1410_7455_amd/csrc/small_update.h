@@ -17,7 +17,7 @@ namespace ngsgd {
 constexpr int kSmallThreads = 1024;          // orthogonality fix kernel
 constexpr int kEigThreads = 1024;            // R x R eigen-update kernel
 // most 2x2 blocks of the upper triangle one thread may own
-constexpr int kEigMaxItems = ((kMaxRank / 2) * (kMaxRank / 2 + 1) / 2 + kEigThreads - 1) / kEigThreads;
+constexpr int kEigMaxItems = ((kMaxRank / 2) * (kMaxRank / 2 - 1) / 2 + (kEigThreads - 64) - 1) / (kEigThreads - 64);
 
 constexpr int kEigvecThreads = 256;          // eigenvector kernel: 4 wavefronts, one row of U each
 constexpr int kEigvecChunk = 32;             // rounds of the rotation log staged in LDS at a time
@@ -235,32 +235,44 @@ __global__ __launch_bounds__(NT) void eig_update_kernel(const SmallGroup g) {
   const double abs_tol = kJacobiAbsTol * zmax;
   const double abs_tol2 = abs_tol * abs_tol;
 
-  // the blocks this thread owns and the (fixed) destinations of their four entries
-  int blk_i[ITEMS], blk_j[ITEMS];
+  // The off-diagonal blocks (bi < bj) this thread owns (the threads after the first wavefront, row by row), where
+  // they are stored, and the (fixed) destinations of their four entries.  The diagonal blocks belong to the
+  // rotation lanes of the first wavefront, so the block waves run one branch-free code path.
+  const int n_off = half * (half - 1) / 2;
+  int blk_i[ITEMS], blk_j[ITEMS], blk_t[ITEMS];
   int dst[ITEMS][4];
 #pragma unroll
   for (int it = 0; it < ITEMS; ++it) {
-    const int item = tid + it * nt;
-    int bi = 0, rem = item < n_blocks ? item : 0;
-    while (rem >= half - bi) {   // row bi holds the blocks (bi, bi), (bi, bi+1), ..., (bi, half-1)
-      rem -= half - bi;
+    const int item = (tid - 64) + it * (nt - 64);
+    int bi = 0, rem = (item >= 0 && item < n_off) ? item : 0;
+    while (half - 1 - bi > 0 && rem >= half - 1 - bi) {   // row bi holds the blocks (bi, bi+1), ..., (bi, half-1)
+      rem -= half - 1 - bi;
       ++bi;
     }
-    const int bj = bi + rem;
+    const int bj = bi + 1 + rem;
     blk_i[it] = bi;
     blk_j[it] = bj;
+    blk_t[it] = (item >= 0 && item < n_off) ? tri(bi) + bj - bi : -1;
 #pragma unroll
     for (int e = 0; e < 4; ++e)
-      dst[it][e] = place(next_position(2 * bi + (e >> 1), half), next_position(2 * bj + (e & 1), half));
+      dst[it][e] = place(next_position(2 * bi + (e >> 1), half), next_position(2 * min(bj, half - 1) + (e & 1), half));
+  }
+  // destinations of the diagonal block (rot_k, rot_k): entries (t,t), (t,b), (b,b)
+  int diag_t = 0, diag_dst[3] = {0, 0, 0};
+  if (tid < half) {
+    diag_t = tri(tid);
+    diag_dst[0] = place(next_position(2 * tid, half), next_position(2 * tid, half));
+    diag_dst[1] = place(next_position(2 * tid, half), next_position(2 * tid + 1, half));
+    diag_dst[2] = place(next_position(2 * tid + 1, half), next_position(2 * tid + 1, half));
   }
   const bool odd_pad = (R & 1) != 0;   // pair 0 then holds the padding player
 
-  // Rotation lanes (the last wavefront): while the 2x2 blocks of round r are being rotated, lane k of this wave
+  // Rotation lanes (the first wavefront): while the 2x2 blocks of round r are being rotated, lane k of this wave
   // prepares pair k's rotation for round r+1.  The pair that will stand at (2k, 2k+1) is made of member A (the
   // later column) and member B (the earlier row) of the present layout; the lane recomputes their two diagonal
   // entries and their common entry after this round's rotations from the old copy, so a round needs one barrier.
-  const int rot_k = tid - (nt - 64);
-  const bool rot_lane = rot_k >= 0 && rot_k < half;
+  const int rot_k = tid;   // the first wavefront: the oldest wave of a SIMD is served first
+  const bool rot_lane = rot_k < half;
   int rz_blk = 0, rz_da = 0, rz_db = 0, rz_pa = 0, rz_pb = 0;
   bool rz_sa0 = true, rz_sb0 = true;
   if (rot_lane && half >= 2) {
@@ -276,7 +288,7 @@ __global__ __launch_bounds__(NT) void eig_update_kernel(const SmallGroup g) {
     rz_db = tri(pb);
   }
   double2* __restrict__ rotlog = a.rotlog;
-  if (tid >= nt - 64) __builtin_amdgcn_s_setprio(3);   // the rotation wave's dependent chain bounds the round
+  if (tid < 64) __builtin_amdgcn_s_setprio(3);   // the rotation wave's dependent chain bounds the round
   if (tid < 2) s_rotated[tid] = 0;
   __syncthreads();
   if (rot_lane) {   // rotations of the very first round
@@ -322,20 +334,20 @@ __global__ __launch_bounds__(NT) void eig_update_kernel(const SmallGroup g) {
         s_rc[cur ^ 1][rot_k] = c;
         s_rs[cur ^ 1][rot_k] = s;
         rotlog[(size_t)(rounds + 1) * half + rot_k] = make_double2(c, s);
+        // this round's rotation of the lane's own pair, applied to its diagonal block
+        const double ck = rc[rot_k], sk = rs[rot_k];
+        const double att = dyn[co + diag_t], atb = dyn[co + np + diag_t], abb = dyn[co + 3 * np + diag_t];
+        dyn[no + diag_dst[0]] = ck * ck * att - 2.0 * ck * sk * atb + sk * sk * abb;
+        dyn[no + diag_dst[2]] = sk * sk * att + 2.0 * ck * sk * atb + ck * ck * abb;
+        dyn[no + diag_dst[1]] = sk == 0.0 ? atb : 0.0;
       }
 #pragma unroll
       for (int it = 0; it < ITEMS; ++it) {
-        const int t = tid + it * nt;
-        if (t >= n_blocks) continue;
+        const int t = blk_t[it];
+        if (t < 0) continue;
         const int bi = blk_i[it], bj = blk_j[it];
         const double ci = rc[bi], si = rs[bi], cj = rc[bj], sj = rs[bj];
         const double x00 = dyn[co + t], x01 = dyn[co + np + t], x10 = dyn[co + 2 * np + t], x11 = dyn[co + 3 * np + t];
-        if (bi == bj) {   // the rotated pair itself: entries (t,t), (t,b), (b,b)
-          dyn[no + dst[it][0]] = ci * ci * x00 - 2.0 * ci * si * x01 + si * si * x11;
-          dyn[no + dst[it][3]] = si * si * x00 + 2.0 * ci * si * x01 + ci * ci * x11;
-          dyn[no + dst[it][1]] = si == 0.0 ? x01 : 0.0;
-          continue;
-        }
         const double y00 = ci * x00 - si * x10, y01 = ci * x01 - si * x11;
         const double y10 = si * x00 + ci * x10, y11 = si * x01 + ci * x11;
         dyn[no + dst[it][0]] = y00 * cj - y01 * sj;
