@@ -12,6 +12,8 @@ Modules
   online_ng_efficient  the same update in the efficient form of App. B.3 / B.5
                        (W_t, H, J, K, L, Z, A_t, B_t) - used by the tests to pin
                        the formulas against the definitional form.
+  simple_ng            the simple method (App. A): hold-one-out Fisher factors
+                       from the current minibatch, definitional and efficient forms.
   network              forward / objective / backward / precondition / update
                        (Sec. 2, Sec. 4.5-4.6).
   averaging            parameter averaging across replicas (Sec. 3.1).

@@ -12,7 +12,9 @@ a 1 appended (Sec. 4.4).  The update of layer i is
 
 where O_i (N x Dout) is the derivative of the objective w.r.t. the affine
 output, X_i (N x (Din+1)) the layer input, and the bar marks the output of that
-matrix's own online preconditioner (2I instances, App. B.5).  Back-propagation
+matrix's own online preconditioner (2I instances, App. B.5) or, with
+method="simple", the output of the simple method of App. A applied to that
+matrix (no state; Fisher factors from the other rows of the same minibatch).  Back-propagation
 itself runs on the unmodified derivatives: the natural gradient only modifies
 the two matrices that enter the update (App. C.3, last paragraph).
 
@@ -34,6 +36,7 @@ from __future__ import annotations
 import numpy as np
 
 from .online_ng import OnlineNaturalGradient
+from .simple_ng import simple_ng
 
 TANH = 0
 PNORM = 1
@@ -89,7 +92,12 @@ class NGSGDNetwork:
     def __init__(self, dims, nonlin, weights, pnorm_group: int = 10, rank_in: int = 20,
                  rank_out: int = 80, alpha: float = 4.0, num_samples_history: float = 2000.0,
                  epsilon: float = 1.0e-10, update_period: int = 4, natural_gradient: bool = True,
-                 renorm: bool = False, max_change_per_sample: float = 0.0):
+                 renorm: bool = False, max_change_per_sample: float = 0.0, method: str = "online",
+                 simple_epsilon: float = 1.0e-20):
+        assert method in ("online", "simple")
+        self.method = method                 # which estimate of the Fisher factors (Sec. 4.5)
+        self.simple_alpha = alpha
+        self.simple_epsilon = simple_epsilon
         self.dims = list(dims)
         self.n_layers = len(dims) - 1
         self.nonlin = list(nonlin)
@@ -175,7 +183,10 @@ class NGSGDNetwork:
         O = self.backward(Xin, A, logp, labels)
         deltas, Obar_all, Xbar_all, scales = [], [], [], []
         for l in range(self.n_layers):
-            if self.natural_gradient:
+            if self.natural_gradient and self.method == "simple":
+                Obar, _, rn_o = simple_ng(O[l], self.simple_alpha, self.simple_epsilon)
+                Xbar, _, rn_x = simple_ng(Xin[l], self.simple_alpha, self.simple_epsilon)
+            elif self.natural_gradient:
                 Obar, _, rn_o = self.precond_out[l].precondition(O[l])
                 Xbar, _, rn_x = self.precond_in[l].precondition(Xin[l])
             else:

@@ -110,6 +110,31 @@ def test_step_update_is_product_of_preconditioned_factors():
     assert all(p.t == 4 for p in net.precond_in + net.precond_out)
 
 
+def test_simple_method_step():
+    """method="simple" (App. A): the update is built from the definitional hold-one-out factors of the same
+    minibatch, keeps no state, and tends to the plain SGD step under heavy smoothing."""
+    from oracle.simple_ng import simple_ng_definitional
+    rng = np.random.default_rng(31)
+    dims, group = [5, 12, 9, 7], 3
+    weights = [rng.standard_normal((12, 6)) / 2, rng.standard_normal((9, 5)) / 2, rng.standard_normal((7, 10)) / 3]
+    mk = lambda **kw: NGSGDNetwork(dims, [PNORM, TANH], [w.copy() for w in weights], pnorm_group=group, **kw)
+    net = mk(method="simple")
+    x = rng.standard_normal((14, 5))
+    y = rng.integers(0, 7, 14)
+    W0 = [w.copy() for w in net.W]
+    net.step(x, y, 0.02)
+    for l in range(3):
+        Ob = simple_ng_definitional(net.last["O"][l])[0]
+        Xb = simple_ng_definitional(net.last["Xin"][l])[0]
+        np.testing.assert_allclose(net.W[l], W0[l] + 0.02 * Ob.T @ Xb, atol=1e-12)
+    assert all(p.t == 0 for p in net.precond_in + net.precond_out)       # the online state is not touched
+    heavy, plain = mk(method="simple", alpha=1e10), mk(natural_gradient=False)
+    heavy.step(x, y, 0.02)
+    plain.step(x, y, 0.02)
+    for l in range(3):
+        np.testing.assert_allclose(heavy.W[l], plain.W[l], atol=1e-7)
+
+
 def test_small_learning_rate_step_increases_objective():
     rng = np.random.default_rng(25)
     net = tiny_net(rng, [TANH, TANH])
