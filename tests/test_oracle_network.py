@@ -117,7 +117,7 @@ def test_simple_method_step():
     rng = np.random.default_rng(31)
     dims, group = [5, 12, 9, 7], 3
     weights = [rng.standard_normal((12, 6)) / 2, rng.standard_normal((9, 5)) / 2, rng.standard_normal((7, 10)) / 3]
-    mk = lambda **kw: NGSGDNetwork(dims, [PNORM, TANH], [w.copy() for w in weights], pnorm_group=group, **kw)
+    mk = lambda **kw: NGSGDNetwork(dims, [PNORM, TANH], [w.copy() for w in weights], pnorm_group=group, rank_in=2, rank_out=3, **kw)
     net = mk(method="simple")
     x = rng.standard_normal((14, 5))
     y = rng.integers(0, 7, 14)
