@@ -48,6 +48,9 @@ extern "C" {
 #define NGSGD_MAX_LAYERS 16
 #define NGSGD_MAX_RANK 96    /* the R x R update runs in one workgroup's LDS */
 
+#define NGSGD_METHOD_ONLINE 0 /* Fisher factors from previous minibatches, App. B (the default)   */
+#define NGSGD_METHOD_SIMPLE 1 /* Fisher factors from the other rows of the minibatch, App. A    */
+
 #define NGSGD_SIDE_INPUT 0   /* preconditioner of the layer-input matrix [X_l, 1]   */
 #define NGSGD_SIDE_OUTPUT 1  /* preconditioner of the output-derivative matrix O_l  */
 
@@ -76,6 +79,8 @@ typedef struct {
   int32_t always_update_first;    /*    or J divides t, App. B.4                       */
   int32_t renorm;                 /* 1: rows leave each p-norm layer with unit rms     */
   float max_change_per_sample;    /* App. C.3; 0 disables the limit (paper: 0.075)     */
+  int32_t method;                 /* NGSGD_METHOD_ONLINE (App. B) or _SIMPLE (App. A)  */
+  float simple_epsilon;           /* floor on tr(X^T X) in beta, App. A.2 (1e-20)      */
 } ngsgd_config;
 
 /* ---- one preconditioner instance (App. B) ------------------------------------------------- */
@@ -121,6 +126,25 @@ int ngsgd_precond_diagnostics(const ngsgd_precond* p, int32_t* flags_host, int32
  * W_t = E_t^{1/2} R_t is formed on the device (eq. beta2, etii, wt:def). */
 int ngsgd_precond_set_state(ngsgd_precond* p, const double* dev_R, const double* dev_d, double rho,
                             int64_t t, void* hip_stream);
+
+/* ---- the simple method (App. A), stateless ---------------------------------------------------- */
+
+/* Device workspace for matrices of up to max_rows rows and dim columns. */
+int ngsgd_simple_workspace_bytes(int32_t max_rows, int32_t dim, size_t* out_bytes);
+
+/* Overwrites the N x D matrix dev_M (leading dimension ld, a multiple of 4, 16-byte aligned rows)
+ * with gamma * Xhat, where row i of Xhat is (beta I + F_i)^{-1} x_i, F_i = sum_{j != i} x_j x_j^T / (N-1)
+ * is estimated from the other rows, beta = alpha max(tr(X^T X), epsilon) / (N D), and gamma restores
+ * the Frobenius norm of the input (App. A.2).  Computed as in App. A.3: one inverse of size
+ * min(N, D) (column space if N > D, row space otherwise) and a scalar correction per row.
+ *   dev_workspace  caller-owned scratch of at least ngsgd_simple_workspace_bytes(N, D) bytes,
+ *                  256-byte aligned; holds nothing between calls
+ *   dev_gamma      (optional, 1 float)  receives gamma
+ *   dev_rownorm2   (optional, N floats) receives the squared 2-norm of each output row
+ * Requires N >= 2.  Returns NGSGD_EINVAL / NGSGD_ENOMEM before anything is enqueued. */
+int ngsgd_precondition_simple(float* dev_M, int32_t N, int32_t D, int32_t ld, float alpha, float epsilon,
+                              void* dev_workspace, size_t workspace_bytes, float* dev_gamma,
+                              float* dev_rownorm2, void* hip_stream);
 
 /* ---- one replica of the network -------------------------------------------------------------- */
 
@@ -181,7 +205,10 @@ int ngsgd_last_max_change_scale(ngsgd_net* net, int32_t layer, double* dev_out, 
 #define NGSGD_PROF_ELEMENTWISE 9     /* nonlinearities, log-softmax, max-change                  */
 #define NGSGD_PROF_PRECOND_MISC 10   /* clears, gamma, B_t, orthogonality check, rescale         */
 #define NGSGD_PROF_INIT 11           /* state initialisation from the first minibatch            */
-#define NGSGD_PROF_CATEGORIES 12
+#define NGSGD_PROF_SIMPLE_GRAM 12    /* simple method: X^T X or X X^T                            */
+#define NGSGD_PROF_SIMPLE_INVERSE 13 /* simple method: (beta I + Gram / (N-1))^{-1}              */
+#define NGSGD_PROF_SIMPLE_APPLY 14   /* simple method: Q, per-row factors, gamma                 */
+#define NGSGD_PROF_CATEGORIES 15
 int ngsgd_profile_enable(int32_t on);
 int ngsgd_profile_read(double* ms_out, int64_t* launches_out, int32_t n_categories);
 

@@ -25,6 +25,8 @@ NGSGD_PNORM = 1
 NGSGD_SIDE_INPUT = 0
 NGSGD_SIDE_OUTPUT = 1
 NGSGD_MAX_RANK = 96
+NGSGD_METHOD_ONLINE = 0
+NGSGD_METHOD_SIMPLE = 1
 
 
 class NgsgdError(RuntimeError):
@@ -41,7 +43,7 @@ class ngsgd_config(ctypes.Structure):
         ("pnorm_group", c_int32), ("max_batch", c_int32), ("rank_in", c_int32), ("rank_out", c_int32),
         ("alpha", c_float), ("num_samples_history", c_float), ("epsilon", c_float),
         ("update_period", c_int32), ("always_update_first", c_int32), ("renorm", c_int32),
-        ("max_change_per_sample", c_float),
+        ("max_change_per_sample", c_float), ("method", c_int32), ("simple_epsilon", c_float),
     ]
 
 
@@ -56,6 +58,9 @@ _SIGNATURES = {
     "ngsgd_precond_get_state": (c_int, [c_void_p, c_void_p, c_void_p, c_void_p, POINTER(c_int64), c_void_p]),
     "ngsgd_precond_diagnostics": (c_int, [c_void_p, POINTER(c_int32), POINTER(c_int32), c_void_p]),
     "ngsgd_precond_set_state": (c_int, [c_void_p, c_void_p, c_void_p, c_double, c_int64, c_void_p]),
+    "ngsgd_simple_workspace_bytes": (c_int, [c_int32, c_int32, POINTER(c_size_t)]),
+    "ngsgd_precondition_simple": (c_int, [c_void_p, c_int32, c_int32, c_int32, c_float, c_float, c_void_p, c_size_t,
+                                          c_void_p, c_void_p, c_void_p]),
     "ngsgd_workspace_bytes": (c_int, [POINTER(ngsgd_config), POINTER(c_size_t)]),
     "ngsgd_create": (c_int, [POINTER(ngsgd_config), c_void_p, c_size_t, POINTER(c_void_p)]),
     "ngsgd_destroy": (c_int, [c_void_p]),
@@ -179,14 +184,36 @@ class Preconditioner:
                                                 _stream_ptr()), "ngsgd_precond_set_state")
 
 
+class SimplePreconditioner:
+    """The simple method of App. A (ngsgd_precondition_simple): stateless, the workspace is kept for reuse."""
+
+    def __init__(self, max_rows, dim, alpha=4.0, epsilon=1e-20):
+        import torch
+        self.lib = load_library()
+        self.max_rows, self.dim, self.alpha, self.epsilon = max_rows, dim, alpha, epsilon
+        nbytes = c_size_t(0)
+        _check(self.lib.ngsgd_simple_workspace_bytes(max_rows, dim, byref(nbytes)), "ngsgd_simple_workspace_bytes")
+        self.workspace_bytes = nbytes.value
+        self.workspace = torch.empty(nbytes.value, dtype=torch.uint8, device="cuda")
+
+    def precondition(self, M, gamma=None, rownorm2=None, stream=None):
+        """In place on the float32 CUDA tensor M (N x dim, row stride M.stride(0)), N <= max_rows."""
+        assert M.is_cuda and M.element_size() == 4 and M.stride(1) == 1 and M.shape[1] == self.dim
+        _check(self.lib.ngsgd_precondition_simple(_ptr(M), M.shape[0], M.shape[1], M.stride(0), self.alpha,
+                                                  self.epsilon, _ptr(self.workspace), self.workspace_bytes,
+                                                  _ptr(gamma), _ptr(rownorm2), _stream_ptr(stream)),
+               "ngsgd_precondition_simple")
+
+
 class Network:
     """One replica (ngsgd_create / ngsgd_step / ...)."""
 
     def __init__(self, dims, nonlin, max_batch, pnorm_group=10, rank_in=20, rank_out=80, alpha=4.0,
                  num_samples_history=2000.0, epsilon=1e-10, update_period=4, always_update_first=10,
-                 renorm=False, max_change_per_sample=0.0):
+                 renorm=False, max_change_per_sample=0.0, method="online", simple_epsilon=1e-20):
         import torch
         self.lib = load_library()
+        self.method = {"online": NGSGD_METHOD_ONLINE, "simple": NGSGD_METHOD_SIMPLE}[method]
         self.dims = list(dims)
         self.nonlin = list(nonlin)
         self.n_layers = len(dims) - 1
@@ -203,7 +230,7 @@ class Network:
         self._nonlin_arr = (c_int32 * max(1, len(nonlin)))(*nonlin)
         cfg = ngsgd_config(self.n_layers, self._dims_arr, self._nonlin_arr, pnorm_group, max_batch, rank_in,
                            rank_out, alpha, num_samples_history, epsilon, update_period, always_update_first,
-                           1 if renorm else 0, max_change_per_sample)
+                           1 if renorm else 0, max_change_per_sample, self.method, simple_epsilon)
         nbytes = c_size_t(0)
         _check(self.lib.ngsgd_workspace_bytes(byref(cfg), byref(nbytes)), "ngsgd_workspace_bytes")
         self.workspace_bytes = nbytes.value
@@ -276,7 +303,8 @@ class Network:
 
 
 PROFILE_CATEGORIES = ["gemm_fwd", "gemm_bwd", "gemm_upd", "precond_h", "precond_j", "precond_xhat", "precond_kl",
-                      "precond_small", "precond_wnew", "elementwise", "precond_misc", "init"]
+                      "precond_small", "precond_wnew", "elementwise", "precond_misc", "init", "simple_gram",
+                      "simple_inverse", "simple_apply"]
 
 
 def profile_enable(on: bool) -> None:

@@ -14,6 +14,7 @@
 #include "gemm.h"
 #include "init.h"
 #include "kernels.h"
+#include "simple_ng.h"
 #include "small_update.h"
 #include "state.h"
 
@@ -763,6 +764,199 @@ int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStr
 
 // ---------------------------------------------------------------------------------------------------
 // preconditioner C ABI
+// ---- simple method (App. A) --------------------------------------------------------------------------
+namespace {
+
+struct SimpleWork {   // device scratch of one matrix, carved for up to max_rows x dim
+  double* scal = nullptr;
+  double* prow = nullptr;
+  double* buf[2] = {nullptr, nullptr};
+  float* ginv = nullptr;
+  float* Q = nullptr;
+  int ldq = 0;
+};
+
+void simple_layout(SimpleWork& w, int max_rows, int dim, bool own_prow, Carver& c) {
+  const size_t np = (size_t)pad32(std::min(max_rows, dim));
+  w.scal = c.take<double>(4);
+  w.prow = own_prow ? c.take<double>(max_rows) : nullptr;
+  w.buf[0] = c.take<double>(np * np);
+  w.buf[1] = c.take<double>(np * np);
+  w.ginv = c.take<float>(np * np);
+  w.ldq = pad32(dim);
+  w.Q = c.take<float>((size_t)max_rows * w.ldq);
+}
+
+struct SimpleCall {
+  float* M;
+  int ld, N, D;
+  double alpha, epsilon;
+  SimpleWork w;
+  double* prow;          // N doubles: ||xhat_i||^2
+  double* gamma;         // 1 double
+  float* gamma_out;      // optional
+  float* rownorm2_out;   // optional
+};
+
+// Enqueues the simple method for a list of independent matrices; every stage is one grouped launch.  With
+// scale_output the matrices are left as gamma * Xhat, without it as Xhat with gamma in *gamma.
+int simple_many(const std::vector<SimpleCall>& calls, bool scale_output, hipStream_t s) {
+  for (auto& c : calls)
+    if (c.M == nullptr || c.N < 2 || c.D < 1 || c.ld < c.D || (c.ld & 3) || !aligned16(c.M) || !(c.alpha > 0.0) ||
+        !(c.epsilon > 0.0))
+      return NGSGD_EINVAL;
+  for (size_t done = 0; done < calls.size();) {
+    const int cnt = (int)std::min<size_t>(kSimpleMaxGroup, calls.size() - done);
+    SimpleGroup g;
+    g.count = cnt;
+    int nblk_max = 0, n_max = 0;
+    for (int i = 0; i < cnt; ++i) {
+      const SimpleCall& c = calls[done + i];
+      SimpleArgs& a = g.a[i];
+      a.M = c.M; a.ld = c.ld; a.Q = c.w.Q; a.ldq = c.w.ldq;
+      a.N = c.N; a.D = c.D;
+      a.n = c.N > c.D ? c.D : c.N;     // column space if N > D, row space otherwise (App. A.3)
+      a.np = pad32(a.n);
+      a.nblk = a.np / kSimpleBlock;
+      a.alpha = c.alpha; a.epsilon = c.epsilon;
+      a.buf[0] = c.w.buf[0]; a.buf[1] = c.w.buf[1];
+      a.ginv = c.w.ginv;
+      a.prow = c.prow; a.scal = c.w.scal; a.gamma = c.gamma;
+      a.gamma_out = c.gamma_out; a.rownorm2_out = c.rownorm2_out;
+      nblk_max = std::max(nblk_max, a.nblk);
+      n_max = std::max(n_max, a.N);
+    }
+    {
+      // Gram matrix in fp64 (split over the long dimension, double atomics)
+      ProfScope prof(NGSGD_PROF_SIMPLE_GRAM, s);
+      FillGroup fg;
+      fg.count = cnt;
+      size_t fill_max = 0;
+      for (int i = 0; i < cnt; ++i) {
+        fg.ptr[i] = reinterpret_cast<uint32_t*>(g.a[i].buf[1]);
+        fg.n[i] = (size_t)g.a[i].np * g.a[i].np * 2;
+        fill_max = std::max(fill_max, fg.n[i]);
+      }
+      const unsigned blocks = (unsigned)std::min<size_t>((fill_max + 2047) / 2048, 256);
+      hipLaunchKernelGGL(fill_zero_group_kernel, dim3(blocks > 0 ? blocks : 1, cnt), dim3(256), 0, s, fg);
+      LAUNCH_CHECK();
+      std::vector<GemmDesc> rows, cols;
+      int tiles_rows = 0, tiles_cols = 0;
+      for (int i = 0; i < cnt; ++i) {
+        const SimpleArgs& a = g.a[i];
+        const int t = ((a.n + 63) / 64) * ((a.n + 63) / 64);
+        (a.N > a.D ? tiles_cols : tiles_rows) += t;
+      }
+      for (int i = 0; i < cnt; ++i) {
+        const SimpleArgs& a = g.a[i];
+        GemmDesc d;
+        d.A = a.M; d.lda = a.ld;
+        d.B = a.M; d.ldb = a.ld;
+        d.C = a.buf[1]; d.ldc = a.np;
+        d.M = d.N = a.n;
+        if (a.N > a.D) {   // X^T X: the sum runs over the rows
+          d.K = a.N;
+          d.splits = choose_splits(tiles_cols, (a.N + BK - 1) / BK);
+          cols.push_back(d);
+        } else {           // X X^T: the sum runs over the columns
+          d.K = a.D;
+          d.splits = choose_splits(tiles_rows, (a.D + BK - 1) / BK);
+          rows.push_back(d);
+        }
+      }
+      if (!rows.empty())
+        HIP_TRY((launch_gemm_group<64, 64, BK, 2, 2, true, true, EPI_ATOMIC_F64, false, 0, true>(rows.data(),
+                                                                                               (int)rows.size(), s)));
+      if (!cols.empty())
+        HIP_TRY((launch_gemm_group<64, 64, BK, 2, 2, false, false, EPI_ATOMIC_F64, false, 0, true>(cols.data(),
+                                                                                                 (int)cols.size(), s)));
+    }
+    {
+      // G = beta I + Gram / (N-1), then its inverse, one launch per pivot block
+      ProfScope prof(NGSGD_PROF_SIMPLE_INVERSE, s);
+      hipLaunchKernelGGL(simple_prepare_kernel, dim3(nblk_max, nblk_max, cnt), dim3(256), 0, s, g);
+      LAUNCH_CHECK();
+      const int wg = (nblk_max + 1) / 2;
+      for (int k = 0; k < nblk_max; ++k) {
+        hipLaunchKernelGGL(simple_sweep_kernel, dim3(wg, wg, cnt), dim3(256), 0, s, g, k);
+        LAUNCH_CHECK();
+      }
+    }
+    {
+      // Q = G^{-1} X (row space) or X G^{-1} (column space), per-row factors, gamma
+      ProfScope prof(NGSGD_PROF_SIMPLE_APPLY, s);
+      std::vector<GemmDesc> rows, cols;
+      for (int i = 0; i < cnt; ++i) {
+        const SimpleArgs& a = g.a[i];
+        GemmDesc d;
+        d.C = a.Q; d.ldc = a.ldq;
+        d.M = a.N; d.N = a.D; d.K = a.n;
+        if (a.N > a.D) {
+          d.A = a.M; d.lda = a.ld;         // X, N x D
+          d.B = a.ginv; d.ldb = a.np;      // G^{-1} is symmetric: row d of it is column d
+          cols.push_back(d);
+        } else {
+          d.A = a.ginv; d.lda = a.np;      // G^{-1}, N x N
+          d.B = a.M; d.ldb = a.ld;         // X stored K x N
+          rows.push_back(d);
+        }
+      }
+      if (!rows.empty())
+        HIP_TRY((launch_layer_tile<true, false, kBwdAccChunk>(pick_layer_tile(rows.data(), (int)rows.size()),
+                                                             rows.data(), (int)rows.size(), s)));
+      if (!cols.empty())
+        HIP_TRY((launch_layer_tile<true, true, 0>(pick_layer_tile(cols.data(), (int)cols.size()), cols.data(),
+                                                  (int)cols.size(), s)));
+      hipLaunchKernelGGL(simple_rows_kernel, dim3(n_max, cnt), dim3(256), 0, s, g);
+      LAUNCH_CHECK();
+      hipLaunchKernelGGL(simple_gamma_kernel, dim3(cnt), dim3(256), 0, s, g);
+      LAUNCH_CHECK();
+      if (scale_output)
+        for (int i = 0; i < cnt; ++i) {
+          const SimpleArgs& a = g.a[i];
+          hipLaunchKernelGGL(scale_rows_kernel, dim3((a.D + 1023) / 1024, a.N), dim3(256), 0, s, a.M, a.ld, a.N, a.D,
+                             a.gamma);
+          LAUNCH_CHECK();
+        }
+    }
+    done += cnt;
+  }
+  return NGSGD_OK;
+}
+
+}  // namespace
+
+extern "C" int ngsgd_simple_workspace_bytes(int32_t max_rows, int32_t dim, size_t* out_bytes) {
+  if (out_bytes == nullptr || max_rows < 2 || dim < 1) return NGSGD_EINVAL;
+  SimpleWork w;
+  Carver c(nullptr);
+  simple_layout(w, max_rows, dim, true, c);
+  (void)c.take<double>(1);   // gamma
+  *out_bytes = align_up(c.off, 256);
+  return NGSGD_OK;
+}
+
+extern "C" int ngsgd_precondition_simple(float* dev_M, int32_t N, int32_t D, int32_t ld, float alpha, float epsilon,
+                                         void* dev_workspace, size_t workspace_bytes, float* dev_gamma,
+                                         float* dev_rownorm2, void* hip_stream) {
+  if (dev_M == nullptr || dev_workspace == nullptr || (reinterpret_cast<uintptr_t>(dev_workspace) & 255u))
+    return NGSGD_EINVAL;
+  size_t need = 0;
+  NG_TRY(ngsgd_simple_workspace_bytes(N, D, &need));
+  if (workspace_bytes < need) return NGSGD_ENOMEM;
+  SimpleCall c;
+  Carver carve(dev_workspace);
+  simple_layout(c.w, N, D, true, carve);
+  c.gamma = carve.take<double>(1);
+  c.M = dev_M; c.ld = ld; c.N = N; c.D = D;
+  c.alpha = alpha; c.epsilon = epsilon;
+  c.prow = c.w.prow;
+  c.gamma_out = dev_gamma;
+  c.rownorm2_out = dev_rownorm2;
+  std::vector<SimpleCall> calls(1, c);
+  return simple_many(calls, true, static_cast<hipStream_t>(hip_stream));
+}
+
 extern "C" int ngsgd_precond_workspace_bytes(int32_t dim, int32_t rank, int32_t max_batch, size_t* out_bytes) {
   if (out_bytes == nullptr) return NGSGD_EINVAL;
   NG_TRY(precond_check_config(dim, rank, max_batch, 4.f, 2000.f, 1e-10f, 4, 10));
@@ -893,6 +1087,7 @@ struct ngsgd_layer {
   float* sigma = nullptr;           // max_batch renorm divisors
   double* mc_scale = nullptr;       // max-change scale of the latest step
   ngsgd_precond pin, pout;
+  SimpleWork sin, sout;             // scratch of the simple method (only laid out when it is selected)
 };
 
 struct ngsgd_net {
@@ -901,6 +1096,8 @@ struct ngsgd_net {
   int pnorm_group = 10;
   int renorm = 0;
   double max_change_per_sample = 0.0;
+  int method = NGSGD_METHOD_ONLINE;
+  double alpha = 4.0, simple_epsilon = 1e-20;
   std::vector<ngsgd_layer> layers;
   float* params = nullptr;
   size_t n_params_padded = 0;
@@ -922,14 +1119,18 @@ int net_check_config(const ngsgd_config* cfg) {
   if (cfg->max_batch < 1 || cfg->pnorm_group < 1) return NGSGD_EINVAL;
   if (cfg->dims[0] < 1 || (cfg->dims[0] & 3)) return NGSGD_EINVAL;
   if (!(cfg->max_change_per_sample >= 0.f)) return NGSGD_EINVAL;
+  if (cfg->method != NGSGD_METHOD_ONLINE && cfg->method != NGSGD_METHOD_SIMPLE) return NGSGD_EINVAL;
+  const bool simple = cfg->method == NGSGD_METHOD_SIMPLE;
+  if (simple && (cfg->max_batch < 2 || !(cfg->alpha > 0.f) || !(cfg->simple_epsilon > 0.f))) return NGSGD_EINVAL;
   int din = cfg->dims[0];
   for (int l = 0; l < cfg->n_layers; ++l) {
     const int dout = cfg->dims[l + 1];
     if (dout < 1) return NGSGD_EINVAL;
-    NG_TRY(precond_check_config(din + 1, cfg->rank_in, cfg->max_batch, cfg->alpha, cfg->num_samples_history,
-                                cfg->epsilon, cfg->update_period, cfg->always_update_first));
-    NG_TRY(precond_check_config(dout, cfg->rank_out, cfg->max_batch, cfg->alpha, cfg->num_samples_history,
-                                cfg->epsilon, cfg->update_period, cfg->always_update_first));
+    // the simple method keeps no factors: the ranks are not used
+    NG_TRY(precond_check_config(din + 1, simple ? 0 : cfg->rank_in, cfg->max_batch, cfg->alpha,
+                                cfg->num_samples_history, cfg->epsilon, cfg->update_period, cfg->always_update_first));
+    NG_TRY(precond_check_config(dout, simple ? 0 : cfg->rank_out, cfg->max_batch, cfg->alpha,
+                                cfg->num_samples_history, cfg->epsilon, cfg->update_period, cfg->always_update_first));
     if (l < cfg->n_layers - 1) {
       if (cfg->nonlin[l] == NGSGD_PNORM) {
         if (dout % cfg->pnorm_group || dout / cfg->pnorm_group > kPnormMaxGroupsLds) return NGSGD_EINVAL;
@@ -950,6 +1151,10 @@ void net_layout(ngsgd_net& net, const ngsgd_config* cfg, Carver& c) {
   net.pnorm_group = cfg->pnorm_group;
   net.renorm = cfg->renorm ? 1 : 0;
   net.max_change_per_sample = cfg->max_change_per_sample;
+  net.method = cfg->method;
+  net.alpha = cfg->alpha;
+  net.simple_epsilon = cfg->simple_epsilon;
+  const bool simple = cfg->method == NGSGD_METHOD_SIMPLE;
   net.layers.assign(cfg->n_layers, ngsgd_layer());
   int din = cfg->dims[0];
   size_t n_params = 0;
@@ -984,14 +1189,18 @@ void net_layout(ngsgd_net& net, const ngsgd_config* cfg, Carver& c) {
     L.A = c.take<float>((size_t)net.max_batch * L.lda);
     L.sigma = c.take<float>(net.max_batch);
     L.mc_scale = c.take<double>(1);
-    precond_configure(L.pin, L.in1, cfg->rank_in, cfg->max_batch, cfg->alpha, cfg->num_samples_history, cfg->epsilon,
-                      cfg->update_period, cfg->always_update_first);
-    precond_configure(L.pout, L.dout, cfg->rank_out, cfg->max_batch, cfg->alpha, cfg->num_samples_history,
+    precond_configure(L.pin, L.in1, simple ? 0 : cfg->rank_in, cfg->max_batch, cfg->alpha, cfg->num_samples_history,
                       cfg->epsilon, cfg->update_period, cfg->always_update_first);
+    precond_configure(L.pout, L.dout, simple ? 0 : cfg->rank_out, cfg->max_batch, cfg->alpha,
+                      cfg->num_samples_history, cfg->epsilon, cfg->update_period, cfg->always_update_first);
     L.pin.owned_by_net = L.pout.owned_by_net = true;
     L.pin.sync = L.pout.sync = &net.side;
     precond_layout(L.pin, c);
     precond_layout(L.pout, c);
+    if (simple) {   // gamma and the row norms go where the online method leaves them (st->gamma, prow)
+      simple_layout(L.sin, cfg->max_batch, L.in1, false, c);
+      simple_layout(L.sout, cfg->max_batch, L.dout, false, c);
+    }
   }
 }
 
@@ -1080,6 +1289,7 @@ extern "C" int ngsgd_step(ngsgd_net* net, const float* dev_x, const int32_t* dev
                           double* dev_logprob_sum, void* hip_stream) {
   if (net == nullptr || dev_x == nullptr || dev_labels == nullptr) return NGSGD_EINVAL;
   if (N < 1 || N > net->max_batch || !aligned16(dev_x)) return NGSGD_EINVAL;
+  if (net->method == NGSGD_METHOD_SIMPLE && N < 2) return NGSGD_EINVAL;   // nothing to hold out
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const int nl = net->n_layers;
   auto& Ls = net->layers;
@@ -1156,12 +1366,24 @@ extern "C" int ngsgd_step(ngsgd_net* net, const float* dev_x, const int32_t* dev
 
   // natural gradient: both matrices of every layer (Sec. 4.6; 2I instances), one grouped call; the factor updates
   // overlap the rest of this step and the next step's forward and backward passes on the side stream
-  std::vector<PrecondCall> calls;
-  for (auto& L : Ls) {
-    calls.push_back(PrecondCall{&L.pout, L.A, L.lda, N, nullptr, nullptr});
-    calls.push_back(PrecondCall{&L.pin, L.Xin, L.ldx, N, nullptr, nullptr});
+  if (net->method == NGSGD_METHOD_SIMPLE) {
+    // App. A instead: the factors come from the other rows of this minibatch, no state
+    std::vector<SimpleCall> calls;
+    for (auto& L : Ls) {
+      calls.push_back(SimpleCall{L.A, L.lda, N, L.dout, net->alpha, net->simple_epsilon, L.sout, L.pout.prow,
+                                 &L.pout.st->gamma, nullptr, nullptr});
+      calls.push_back(SimpleCall{L.Xin, L.ldx, N, L.in1, net->alpha, net->simple_epsilon, L.sin, L.pin.prow,
+                                 &L.pin.st->gamma, nullptr, nullptr});
+    }
+    NG_TRY(simple_many(calls, false, s));
+  } else {
+    std::vector<PrecondCall> calls;
+    for (auto& L : Ls) {
+      calls.push_back(PrecondCall{&L.pout, L.A, L.lda, N, nullptr, nullptr});
+      calls.push_back(PrecondCall{&L.pin, L.Xin, L.ldx, N, nullptr, nullptr});
+    }
+    NG_TRY(precondition_many(calls, false, s, &net->side));
   }
-  NG_TRY(precondition_many(calls, false, s, &net->side));
 
   // maximum parameter change (App. C.3), then W_l += lr a_l gamma_o gamma_x Ohat_l^T Xhat_l  (Sec. 4.6)
   {

@@ -61,16 +61,31 @@ def test_precond_workspace_sizing_and_argument_errors(lib):
     assert lib.ngsgd_precondition(None, None, 1, 4, None, None, None) == ng.NGSGD_EINVAL
 
 
+def test_simple_method_sizing_and_argument_errors(lib):
+    n = c_size_t(0)
+    assert lib.ngsgd_simple_workspace_bytes(512, 5000, byref(n)) == 0
+    # two fp64 512 x 512 buffers, the fp32 inverse, Q
+    assert n.value >= 2 * 512 * 512 * 8 + 512 * 512 * 4 + 512 * 5000 * 4
+    small = c_size_t(0)
+    assert lib.ngsgd_simple_workspace_bytes(100, 5000, byref(small)) == 0 and small.value < n.value
+    for rows, dim in [(1, 10), (0, 10), (10, 0)]:
+        assert lib.ngsgd_simple_workspace_bytes(rows, dim, byref(n)) == ng.NGSGD_EINVAL
+    assert lib.ngsgd_simple_workspace_bytes(10, 10, None) == ng.NGSGD_EINVAL
+    # NULL matrix / workspace are rejected before any device work
+    assert lib.ngsgd_precondition_simple(None, 8, 8, 8, 4.0, 1e-20, None, 0, None, None, None) == ng.NGSGD_EINVAL
+
+
 def make_cfg(dims, nonlin, **kw):
     d = (c_int32 * len(dims))(*dims)
     nl = (c_int32 * max(1, len(nonlin)))(*nonlin)
     vals = dict(pnorm_group=10, max_batch=512, rank_in=20, rank_out=80, alpha=4.0, num_samples_history=2000.0,
-                epsilon=1e-10, update_period=4, always_update_first=10, renorm=0, max_change_per_sample=0.0)
+                epsilon=1e-10, update_period=4, always_update_first=10, renorm=0, max_change_per_sample=0.0,
+                method=ng.NGSGD_METHOD_ONLINE, simple_epsilon=1e-20)
     vals.update(kw)
     cfg = ng.ngsgd_config(len(dims) - 1, d, nl, vals["pnorm_group"], vals["max_batch"], vals["rank_in"],
                           vals["rank_out"], vals["alpha"], vals["num_samples_history"], vals["epsilon"],
                           vals["update_period"], vals["always_update_first"], vals["renorm"],
-                          vals["max_change_per_sample"])
+                          vals["max_change_per_sample"], vals["method"], vals["simple_epsilon"])
     cfg._keep = (d, nl)
     return cfg
 
@@ -91,7 +106,16 @@ def test_network_workspace_sizing_and_config_validation(lib):
         make_cfg([360, 3000, 5000], [1], max_batch=0),
         make_cfg([360, 3000, 5000], [1], update_period=0),
         make_cfg([360, 3000, 5000], [1], max_change_per_sample=-1.0),
+        make_cfg([360, 3000, 5000], [1], method=7),
+        make_cfg([360, 3000, 5000], [1], method=ng.NGSGD_METHOD_SIMPLE, max_batch=1),       # nothing to hold out
+        make_cfg([360, 3000, 5000], [1], method=ng.NGSGD_METHOD_SIMPLE, simple_epsilon=0.0),
+        make_cfg([360, 3000, 5000], [1], method=ng.NGSGD_METHOD_SIMPLE, alpha=0.0),
     ]
+    # the simple method keeps no factors: ranks are ignored, and it needs room for the inverse and Q
+    online = n.value
+    cfg = make_cfg([360, 3000, 3000, 3000, 3000, 5000], [1, 1, 1, 1], method=ng.NGSGD_METHOD_SIMPLE, rank_out=5000)
+    assert lib.ngsgd_workspace_bytes(byref(cfg), byref(n)) == 0
+    assert n.value > 5_297_000 * 4 + 2 * 512 * (4 * 3000 + 5000) * 4 and n.value != online
     for cfg in bad:
         assert lib.ngsgd_workspace_bytes(byref(cfg), byref(n)) == ng.NGSGD_EINVAL
     assert lib.ngsgd_workspace_bytes(None, byref(n)) == ng.NGSGD_EINVAL
