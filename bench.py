@@ -206,6 +206,89 @@ def run_precond_bench(calls=200):
     return out
 
 
+def run_simple_bench(steps=60, warmup=5, calls=40):
+    """The simple method of App. A on the same workloads: the configs[1] step with every one of the 2I matrices
+    preconditioned from the other rows of its own minibatch (no factor state), and the two configs[2] matrix
+    shapes through ngsgd_precondition_simple alone.  The paper's own comparison (Sec. 6): 208 s per outer
+    iteration with the simple method against 93 s with the online method and 88 s for plain SGD, on a K20."""
+    import torch
+
+    import paper_1410_7455_amd as ng
+    import workloads
+
+    spec = workloads.c1_pnorm()
+    n = spec.minibatch
+    net = ng.Network(spec.dims, spec.nonlin, n, spec.pnorm_group, spec.rank_in, spec.rank_out, spec.alpha,
+                     spec.num_samples_history, spec.epsilon, spec.update_period, renorm=True,
+                     max_change_per_sample=0.075, method="simple")
+    for l, w in enumerate(workloads.initial_weights(spec)):
+        net.set_params(l, torch.from_numpy(w).cuda())
+    pool = []
+    for t in range(POOL):
+        x, y = workloads.minibatch(spec, t)
+        pool.append((torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda()))
+    logp = torch.zeros(1, dtype=torch.float64, device="cuda")
+    for t in range(warmup):
+        net.step(*pool[t % POOL], spec.lr, logp)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(steps):
+        net.step(*pool[(warmup + t) % POOL], spec.lr, logp)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    final_logp = float(logp.item()) / n
+    ng.profile_enable(True)
+    for t in range(steps):
+        net.step(*pool[t % POOL], spec.lr, logp)
+    torch.cuda.synchronize()
+    prof = ng.profile_read()
+    ng.profile_enable(False)
+    breakdown = {k: dict(ms_per_step=ms / steps, launches_per_step=c / steps) for k, (ms, c) in prof.items() if c}
+    log(f"[bench] simple method (App. A): {elapsed * 1e3 / steps:.3f} ms/step, {n * steps / elapsed:,.0f} frames/s, "
+        f"mean log-prob of last minibatch {final_logp:.4f}; "
+        + ", ".join(f"{k} {v['ms_per_step'] * 1e3:.0f} us" for k, v in breakdown.items() if k.startswith("simple")))
+    del net
+    shapes = []
+    for ps in (workloads.c2_input_side(), workloads.c2_output_side()):
+        ld = (ps.dim + 3) // 4 * 4
+        pre = ng.SimplePreconditioner(ps.rows, ps.dim)
+        mats = []
+        for t in range(4):
+            buf = torch.zeros((ps.rows, ld), dtype=torch.float32, device="cuda")
+            buf[:, :ps.dim] = torch.from_numpy(workloads.spectrum_matrix(ps, t)).cuda()
+            mats.append(buf)
+        work = torch.empty_like(mats[0])
+        for t in range(3):
+            work.copy_(mats[t % 4])
+            pre.precondition(work[:, :ps.dim])
+        torch.cuda.synchronize()
+        starts = [torch.cuda.Event(enable_timing=True) for _ in range(calls)]
+        stops = [torch.cuda.Event(enable_timing=True) for _ in range(calls)]
+        for t in range(calls):
+            work.copy_(mats[t % 4])
+            starts[t].record()
+            pre.precondition(work[:, :ps.dim])
+            stops[t].record()
+        torch.cuda.synchronize()
+        us = sum(a.elapsed_time(b) for a, b in zip(starts, stops)) * 1e3 / calls
+        m = min(ps.rows, ps.dim)
+        big = max(ps.rows, ps.dim)
+        mp = (m + 31) // 32 * 32
+        fl = 2.0 * m * m * big + 2.0 * mp ** 3 + 2.0 * ps.rows * ps.dim * m     # Gram, inverse, Q
+        nbytes = 8.0 * ps.rows * ps.dim                                            # X read once, Xbar written once
+        entry = dict(workload=ps.name.replace("_r20", "").replace("_r80", ""), us_per_call=us, flops=fl,
+                     achieved_tflops=fl / (us * 1e-6) / 1e12, algorithmic_bytes=nbytes,
+                     achieved_gbs=nbytes / (us * 1e-6) / 1e9, inverse_size=m)
+        log(f"[bench] simple method {entry['workload']}: {us:.1f} us/call, {entry['achieved_tflops']:.2f} TFLOP/s, "
+            f"{entry['achieved_gbs']:.0f} GB/s algorithmic")
+        shapes.append(entry)
+        del pre
+    return dict(workload="configs[1] step and configs[2] matrix shapes with the simple method (App. A)",
+                value=n * steps / elapsed, unit="frames/s", ms_per_step=elapsed * 1e3 / steps, steps=steps,
+                final_mean_logprob=final_logp, breakdown=breakdown, precondition=shapes,
+                paper_context="K20, seconds per outer iteration: plain SGD 88, online NG-SGD 93, simple NG-SGD 208")
+
+
 def run_replica_bench(replicas=8, rounds=2, steps_per_round=200):
     """BASELINE configs[4] in small: `replicas` copies of the configs[1] network resident on the one GPU, each
     stepping on its own HIP stream over its own data shard, parameters averaged on the device between rounds
@@ -312,8 +395,11 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-precond", action="store_true")
     ap.add_argument("--no-replicas", action="store_true")
+    ap.add_argument("--no-simple", action="store_true", help="skip the simple-method leg (App. A)")
     ap.add_argument("--precond-only", action="store_true",
                     help="run only the preconditioner microbenchmark (BASELINE configs[2]); used for its profile")
+    ap.add_argument("--simple-only", action="store_true",
+                    help="run only the simple-method leg (App. A); used for its profile")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device-to-device copy (the known-size reference for scaling "
                          "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -330,6 +416,9 @@ def main():
     if args.precond_only:
         print(json.dumps({"precondition_roofline": run_precond_bench()}), flush=True)
         return
+    if args.simple_only:
+        print(json.dumps({"simple_method": run_simple_bench()}), flush=True)
+        return
     spec, ms_per_step, frames_per_s, roofline, breakdown, final_logp = run_step_bench(args)
     if args.calibrate_copy:
         src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
@@ -339,6 +428,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     precond = None if args.no_precond else run_precond_bench()
+    simple = None if args.no_simple else run_simple_bench()
     replica = None if args.no_replicas else run_replica_bench()
     cpu = None if args.no_cpu_baseline else run_cpu_baseline()
     result = {
@@ -365,6 +455,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "precondition_roofline": precond,
+        "simple_method": simple,
         "replica_interleaving": replica,
         "breakdown": breakdown,
     }

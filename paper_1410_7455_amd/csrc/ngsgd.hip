@@ -840,36 +840,47 @@ int simple_many(const std::vector<SimpleCall>& calls, bool scale_output, hipStre
       const unsigned blocks = (unsigned)std::min<size_t>((fill_max + 2047) / 2048, 256);
       hipLaunchKernelGGL(fill_zero_group_kernel, dim3(blocks > 0 ? blocks : 1, cnt), dim3(256), 0, s, fg);
       LAUNCH_CHECK();
+      // the Gram matrix is symmetric: only the 128 x 128 tiles on and above the diagonal are computed, one
+      // problem per tile row; the kernel that forms G mirrors them
       std::vector<GemmDesc> rows, cols;
       int tiles_rows = 0, tiles_cols = 0;
+      constexpr int T = kSimpleGramTile;
       for (int i = 0; i < cnt; ++i) {
         const SimpleArgs& a = g.a[i];
-        const int t = ((a.n + 63) / 64) * ((a.n + 63) / 64);
-        (a.N > a.D ? tiles_cols : tiles_rows) += t;
+        const int tr = (a.n + T - 1) / T;
+        (a.N > a.D ? tiles_cols : tiles_rows) += tr * (tr + 1) / 2;
       }
+      auto splits_for = [](int tiles, int k) {
+        const int ksteps = (k + BK - 1) / BK;
+        return std::max(1, std::min(768 / std::max(1, tiles), ksteps / 4));
+      };
       for (int i = 0; i < cnt; ++i) {
         const SimpleArgs& a = g.a[i];
-        GemmDesc d;
-        d.A = a.M; d.lda = a.ld;
-        d.B = a.M; d.ldb = a.ld;
-        d.C = a.buf[1]; d.ldc = a.np;
-        d.M = d.N = a.n;
-        if (a.N > a.D) {   // X^T X: the sum runs over the rows
-          d.K = a.N;
-          d.splits = choose_splits(tiles_cols, (a.N + BK - 1) / BK);
-          cols.push_back(d);
-        } else {           // X X^T: the sum runs over the columns
-          d.K = a.D;
-          d.splits = choose_splits(tiles_rows, (a.D + BK - 1) / BK);
-          rows.push_back(d);
+        for (int r0 = 0; r0 < a.n; r0 += T) {
+          GemmDesc d;
+          d.lda = d.ldb = a.ld;
+          d.C = a.buf[1] + (size_t)r0 * a.np + r0; d.ldc = a.np;
+          d.M = std::min(T, a.n - r0);
+          d.N = a.n - r0;
+          if (a.N > a.D) {   // X^T X: the sum runs over the rows; operands start at column r0
+            d.A = d.B = a.M + r0;
+            d.K = a.N;
+            d.splits = splits_for(tiles_cols, d.K);
+            cols.push_back(d);
+          } else {           // X X^T: the sum runs over the columns; operands start at row r0
+            d.A = d.B = a.M + (size_t)r0 * a.ld;
+            d.K = a.D;
+            d.splits = splits_for(tiles_rows, d.K);
+            rows.push_back(d);
+          }
         }
       }
       if (!rows.empty())
-        HIP_TRY((launch_gemm_group<64, 64, BK, 2, 2, true, true, EPI_ATOMIC_F64, false, 0, true>(rows.data(),
-                                                                                               (int)rows.size(), s)));
+        HIP_TRY((launch_gemm_group<T, T, BK, 2, 2, true, true, EPI_ATOMIC_F64, false, 0, true>(rows.data(),
+                                                                                             (int)rows.size(), s)));
       if (!cols.empty())
-        HIP_TRY((launch_gemm_group<64, 64, BK, 2, 2, false, false, EPI_ATOMIC_F64, false, 0, true>(cols.data(),
-                                                                                                 (int)cols.size(), s)));
+        HIP_TRY((launch_gemm_group<T, T, BK, 2, 2, false, false, EPI_ATOMIC_F64, false, 0, true>(cols.data(),
+                                                                                               (int)cols.size(), s)));
     }
     {
       // G = beta I + Gram / (N-1), then its inverse, one launch per pivot block

@@ -23,6 +23,7 @@
 namespace ngsgd {
 
 constexpr int kSimpleBlock = 32;      // pivot block of the inversion
+constexpr int kSimpleGramTile = 128;  // the Gram matrix is computed in tiles of this size, upper triangle only
 constexpr int kSimpleMaxGroup = 16;   // matrices per grouped launch (the argument block stays within 4 KB)
 
 struct SimpleArgs {
@@ -45,7 +46,7 @@ struct SimpleGroup {
   SimpleArgs a[kSimpleMaxGroup];
 };
 
-// G = beta I + S / (N-1) with beta = alpha max(tr S, epsilon) / (N D) (App. A.2); rows and columns beyond n carry
+// G = beta I + S / (N-1), S given by its tiles on and above the diagonal, with beta = alpha max(tr S, epsilon) / (N D) (App. A.2); rows and columns beyond n carry
 // the identity so that the padded matrix stays positive definite.  Grid (np/32, np/32, count), 256 threads.
 __global__ __launch_bounds__(256) void simple_prepare_kernel(const SimpleGroup g) {
   const SimpleArgs& a = g.a[blockIdx.z];
@@ -66,7 +67,10 @@ __global__ __launch_bounds__(256) void simple_prepare_kernel(const SimpleGroup g
   for (int e = tid; e < kSimpleBlock * kSimpleBlock; e += 256) {
     const int i = blockIdx.y * kSimpleBlock + (e >> 5), j = blockIdx.x * kSimpleBlock + (e & 31);
     double v;
-    if (i < n && j < n) v = S[(size_t)i * np + j] * inv_nm1 + (i == j ? beta : 0.0);
+    if (i < n && j < n) {
+      const bool upper = i / kSimpleGramTile <= j / kSimpleGramTile;   // tiles below the diagonal were not computed
+      v = (upper ? S[(size_t)i * np + j] : S[(size_t)j * np + i]) * inv_nm1 + (i == j ? beta : 0.0);
+    }
     else v = i == j ? 1.0 : 0.0;
     G[(size_t)i * np + j] = v;
   }
@@ -81,7 +85,8 @@ __global__ __launch_bounds__(256) void simple_sweep_kernel(const SimpleGroup g, 
   const int nblk = a.nblk;
   if (k >= nblk || 2 * (int)blockIdx.x >= nblk || 2 * (int)blockIdx.y >= nblk) return;   // uniform per workgroup
   constexpr int B = kSimpleBlock;
-  __shared__ double sP[B][B + 1];
+  __shared__ double sP[B][B + 1];      // the inverse of the pivot block
+  __shared__ double sRow[2][B], sCol[2][B];
   __shared__ double sT[4][B][B + 1];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int np = a.np;
@@ -89,70 +94,133 @@ __global__ __launch_bounds__(256) void simple_sweep_kernel(const SimpleGroup g, 
   double* __restrict__ dst = a.buf[(k & 1) ^ 1];
   const size_t k0 = (size_t)k * B;
 
-  for (int e = tid; e < B * B; e += 256) sP[e >> 5][e & 31] = src[(k0 + (e >> 5)) * np + k0 + (e & 31)];
-  __syncthreads();
-  // in-place Gauss-Jordan on the pivot block: thread owns column c of rows r0, r0+8, r0+16, r0+24
-  {
-    const int c = tid & 31, r0 = tid >> 5;
-    for (int p = 0; p < B; ++p) {
-      const double inv = 1.0 / sP[p][p];
-      const double rowv = sP[p][c] * inv;
-      double colv[4], cur[4];
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        colv[q] = sP[r0 + 8 * q][p];
-        cur[q] = sP[r0 + 8 * q][c];
-      }
-      __syncthreads();
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int r = r0 + 8 * q;
-        double v;
-        if (r == p) v = c == p ? inv : rowv;
-        else if (c == p) v = -colv[q] * inv;
-        else v = cur[q] - colv[q] * rowv;
-        sP[r][c] = v;
-      }
-      __syncthreads();
-    }
-  }
-
   const int bi = 2 * blockIdx.y + (wave >> 1), bj = 2 * blockIdx.x + (wave & 1);
   const bool active = bi < nblk && bj < nblk;
   const int l16 = lane & 15, g4 = lane >> 4;
   const size_t i0 = (size_t)bi * B, j0 = (size_t)bj * B;
   typedef double doublex4 __attribute__((ext_vector_type(4)));
-  doublex4 acc[2][2];
 
-  // T = A_ik P  (bi != k)  or  -P  (bi == k), kept in LDS in row-major form for the second product
+  // Everything this wavefront needs from the old matrix is requested before the pivot block is inverted, so the
+  // loads complete under the elimination: A_ik by rows into LDS, A_kj as B-operand fragments, A_ij as accumulators.
+  double pv[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int e = tid + 256 * q;
+    pv[q] = src[(k0 + (e >> 5)) * np + k0 + (e & 31)];
+  }
+  double aik[16];
+  double bf[B / 4][2];
+  doublex4 acc[2][2];
   if (active) {
     if (bi != k) {
 #pragma unroll
-      for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-        for (int nj = 0; nj < 2; ++nj) acc[mi][nj] = doublex4{0, 0, 0, 0};
-#pragma unroll
-      for (int ks = 0; ks < B / 4; ++ks) {
-        double af[2], bf[2];
-#pragma unroll
-        for (int mi = 0; mi < 2; ++mi) af[mi] = src[(i0 + mi * 16 + l16) * np + k0 + ks * 4 + g4];
-#pragma unroll
-        for (int nj = 0; nj < 2; ++nj) bf[nj] = sP[ks * 4 + g4][nj * 16 + l16];
-#pragma unroll
-        for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-          for (int nj = 0; nj < 2; ++nj)
-            acc[mi][nj] = __builtin_amdgcn_mfma_f64_16x16x4f64(af[mi], bf[nj], acc[mi][nj], 0, 0, 0);
+      for (int q = 0; q < 16; ++q) {
+        const int e = lane + 64 * q;
+        aik[q] = src[(i0 + (e >> 5)) * np + k0 + (e & 31)];
       }
+    }
+    if (bj != k) {
+#pragma unroll
+      for (int ks = 0; ks < B / 4; ++ks)
+#pragma unroll
+        for (int nj = 0; nj < 2; ++nj) bf[ks][nj] = src[(k0 + ks * 4 + g4) * np + j0 + nj * 16 + l16];
 #pragma unroll
       for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
         for (int nj = 0; nj < 2; ++nj)
 #pragma unroll
-          for (int r = 0; r < 4; ++r) sT[wave][mi * 16 + 4 * r + g4][nj * 16 + l16] = acc[mi][nj][r];
-    } else {
-      for (int e = lane; e < B * B; e += 64) sT[wave][e >> 5][e & 31] = -sP[e >> 5][e & 31];
+          for (int r = 0; r < 4; ++r)
+            acc[mi][nj][r] = bi != k ? src[(i0 + mi * 16 + 4 * r + g4) * np + j0 + nj * 16 + l16] : 0.0;
     }
+  }
+  // Gauss-Jordan on the pivot block.  Thread (c, r0) keeps column c of rows r0, r0+8, r0+16, r0+24 in registers;
+  // a step only needs the pivot row and the pivot column, which their owners publish (for the next step, into
+  // the other pair of arrays) as soon as they have them: one barrier and a few LDS words per step.
+  {
+    const int c = tid & 31, r0 = tid >> 5;
+    double cur[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) cur[q] = pv[q];   // element e = tid + 256 q is (r0 + 8 q, c)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      if (r0 + 8 * q == 0) sRow[0][c] = cur[q];
+      if (c == 0) sCol[0][r0 + 8 * q] = cur[q];
+    }
+    __syncthreads();
+    for (int p = 0; p < B; ++p) {
+      const int par = p & 1;
+      // all LDS reads of the step are issued together, the arithmetic is branch-free (selects)
+      const double piv = sRow[par][p];
+      const double rv = sRow[par][c];
+      double colv[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) colv[q] = sCol[par][r0 + 8 * q];
+      double inv = __builtin_amdgcn_rcp(piv);        // hardware estimate, two Newton steps
+      inv = fma(fma(-piv, inv, 1.0), inv, inv);
+      inv = fma(fma(-piv, inv, 1.0), inv, inv);
+      const double rowv = rv * inv;
+      const double on_row = c == p ? inv : rowv;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int r = r0 + 8 * q;
+        const double off_row = c == p ? -colv[q] * inv : fma(-colv[q], rowv, cur[q]);
+        cur[q] = r == p ? on_row : off_row;
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int r = r0 + 8 * q;
+        if (r == p + 1) sRow[par ^ 1][c] = cur[q];
+        if (c == p + 1) sCol[par ^ 1][r] = cur[q];
+      }
+      __syncthreads();
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) sP[r0 + 8 * q][c] = cur[q];
+  }
+  __syncthreads();
+  const double (*P)[B + 1] = sP;
+
+  // T = A_ik P  (bi != k)  or  -P  (bi == k), kept in LDS in row-major form for the second product.  The
+  // barriers are outside every wave-dependent branch; they also order the wavefront's own LDS writes and reads.
+  const bool mult = active && bi != k;
+  if (mult) {
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+      const int e = lane + 64 * q;
+      sT[wave][e >> 5][e & 31] = aik[q];
+    }
+  }
+  __syncthreads();
+  doublex4 t[2][2];
+  if (mult) {
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+      for (int nj = 0; nj < 2; ++nj) t[mi][nj] = doublex4{0, 0, 0, 0};
+#pragma unroll
+    for (int ks = 0; ks < B / 4; ++ks) {
+      double af[2], pf[2];
+#pragma unroll
+      for (int mi = 0; mi < 2; ++mi) af[mi] = sT[wave][mi * 16 + l16][ks * 4 + g4];
+#pragma unroll
+      for (int nj = 0; nj < 2; ++nj) pf[nj] = P[ks * 4 + g4][nj * 16 + l16];
+#pragma unroll
+      for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int nj = 0; nj < 2; ++nj)
+          t[mi][nj] = __builtin_amdgcn_mfma_f64_16x16x4f64(af[mi], pf[nj], t[mi][nj], 0, 0, 0);
+    }
+  }
+  __syncthreads();
+  if (mult) {
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+      for (int nj = 0; nj < 2; ++nj)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) sT[wave][mi * 16 + 4 * r + g4][nj * 16 + l16] = t[mi][nj][r];
+  } else if (active) {
+    for (int e = lane; e < B * B; e += 64) sT[wave][e >> 5][e & 31] = -P[e >> 5][e & 31];
   }
   __syncthreads();
   if (!active) return;
@@ -160,24 +228,15 @@ __global__ __launch_bounds__(256) void simple_sweep_kernel(const SimpleGroup g, 
   // new block: (bj != k)  C0 - T A_kj with C0 = A_ij (bi != k) or 0;   (bj == k)  -T
   if (bj != k) {
 #pragma unroll
-    for (int mi = 0; mi < 2; ++mi)
-#pragma unroll
-      for (int nj = 0; nj < 2; ++nj)
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-          acc[mi][nj][r] = bi != k ? src[(i0 + mi * 16 + 4 * r + g4) * np + j0 + nj * 16 + l16] : 0.0;
-#pragma unroll
     for (int ks = 0; ks < B / 4; ++ks) {
-      double af[2], bf[2];
+      double af[2];
 #pragma unroll
       for (int mi = 0; mi < 2; ++mi) af[mi] = -sT[wave][mi * 16 + l16][ks * 4 + g4];
-#pragma unroll
-      for (int nj = 0; nj < 2; ++nj) bf[nj] = src[(k0 + ks * 4 + g4) * np + j0 + nj * 16 + l16];
 #pragma unroll
       for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
         for (int nj = 0; nj < 2; ++nj)
-          acc[mi][nj] = __builtin_amdgcn_mfma_f64_16x16x4f64(af[mi], bf[nj], acc[mi][nj], 0, 0, 0);
+          acc[mi][nj] = __builtin_amdgcn_mfma_f64_16x16x4f64(af[mi], bf[ks][nj], acc[mi][nj], 0, 0, 0);
     }
   } else {
 #pragma unroll
