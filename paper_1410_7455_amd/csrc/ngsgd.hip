@@ -771,6 +771,7 @@ struct SimpleWork {   // device scratch of one matrix, carved for up to max_rows
   double* scal = nullptr;
   double* prow = nullptr;
   double* buf[2] = {nullptr, nullptr};
+  double* pinv[2] = {nullptr, nullptr};
   float* ginv = nullptr;
   float* Q = nullptr;
   int ldq = 0;
@@ -782,6 +783,8 @@ void simple_layout(SimpleWork& w, int max_rows, int dim, bool own_prow, Carver& 
   w.prow = own_prow ? c.take<double>(max_rows) : nullptr;
   w.buf[0] = c.take<double>(np * np);
   w.buf[1] = c.take<double>(np * np);
+  w.pinv[0] = c.take<double>(kSimpleBlock * kSimpleBlock);
+  w.pinv[1] = c.take<double>(kSimpleBlock * kSimpleBlock);
   w.ginv = c.take<float>(np * np);
   w.ldq = pad32(dim);
   w.Q = c.take<float>((size_t)max_rows * w.ldq);
@@ -820,6 +823,7 @@ int simple_many(const std::vector<SimpleCall>& calls, bool scale_output, hipStre
       a.nblk = a.np / kSimpleBlock;
       a.alpha = c.alpha; a.epsilon = c.epsilon;
       a.buf[0] = c.w.buf[0]; a.buf[1] = c.w.buf[1];
+      a.pinv[0] = c.w.pinv[0]; a.pinv[1] = c.w.pinv[1];
       a.ginv = c.w.ginv;
       a.prow = c.prow; a.scal = c.w.scal; a.gamma = c.gamma;
       a.gamma_out = c.gamma_out; a.rownorm2_out = c.rownorm2_out;
@@ -889,7 +893,7 @@ int simple_many(const std::vector<SimpleCall>& calls, bool scale_output, hipStre
       LAUNCH_CHECK();
       const int wg = (nblk_max + 1) / 2;
       for (int k = 0; k < nblk_max; ++k) {
-        hipLaunchKernelGGL(simple_sweep_kernel, dim3(wg, wg, cnt), dim3(256), 0, s, g, k);
+        hipLaunchKernelGGL(simple_sweep_kernel, dim3(wg + 1, wg, cnt), dim3(256), 0, s, g, k);   // + look-ahead column
         LAUNCH_CHECK();
       }
     }

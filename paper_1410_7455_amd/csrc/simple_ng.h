@@ -35,6 +35,7 @@ struct SimpleArgs {
   double alpha, epsilon;
   double* buf[2];   // np x np each; the Gram matrix is accumulated in buf[1]
   float* ginv;      // np x np, G^{-1} rounded to fp32 for the Q product
+  double* pinv[2];  // 32 x 32 each: inverse of the pivot block of the current / the next elimination step
   double* prow;     // N: ||xhat_i||^2
   double* scal;     // [0] tr(X^T X), [1] beta
   double* gamma;    // gamma (App. A.2)
@@ -46,12 +47,58 @@ struct SimpleGroup {
   SimpleArgs a[kSimpleMaxGroup];
 };
 
-// G = beta I + S / (N-1), S given by its tiles on and above the diagonal, with beta = alpha max(tr S, epsilon) / (N D) (App. A.2); rows and columns beyond n carry
-// the identity so that the padded matrix stays positive definite.  Grid (np/32, np/32, count), 256 threads.
+// Gauss-Jordan inversion of a 32 x 32 positive-definite block by a workgroup of 256 threads, without pivoting.
+// Thread (c = tid % 32, r0 = tid / 32) holds column c of rows r0, r0+8, r0+16, r0+24 in cur[] on entry (the
+// block) and on exit (its inverse).  A step only needs the pivot row and the pivot column, which their owners
+// publish (for the next step, into the other pair of arrays) as soon as they have them: one barrier and a few
+// LDS words per step, and the arithmetic is branch-free.  sRow, sCol: LDS, [2][32] each.
+__device__ __forceinline__ void invert_block_32(double (&cur)[4], double (*sRow)[kSimpleBlock],
+                                                double (*sCol)[kSimpleBlock]) {
+  constexpr int B = kSimpleBlock;
+  const int tid = threadIdx.x, c = tid & 31, r0 = tid >> 5;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    if (r0 + 8 * q == 0) sRow[0][c] = cur[q];
+    if (c == 0) sCol[0][r0 + 8 * q] = cur[q];
+  }
+  __syncthreads();
+  for (int p = 0; p < B; ++p) {
+    const int par = p & 1;
+    const double piv = sRow[par][p];
+    const double rv = sRow[par][c];
+    double colv[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) colv[q] = sCol[par][r0 + 8 * q];
+    double inv = __builtin_amdgcn_rcp(piv);        // hardware estimate, two Newton steps
+    inv = fma(fma(-piv, inv, 1.0), inv, inv);
+    inv = fma(fma(-piv, inv, 1.0), inv, inv);
+    const double rowv = rv * inv;
+    const double on_row = c == p ? inv : rowv;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int r = r0 + 8 * q;
+      const double off_row = c == p ? -colv[q] * inv : fma(-colv[q], rowv, cur[q]);
+      cur[q] = r == p ? on_row : off_row;
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int r = r0 + 8 * q;
+      if (r == p + 1) sRow[par ^ 1][c] = cur[q];
+      if (c == p + 1) sCol[par ^ 1][r] = cur[q];
+    }
+    __syncthreads();
+  }
+}
+
+// G = beta I + S / (N-1), S given by its tiles on and above the diagonal, with beta = alpha max(tr S, epsilon) / (N D)
+// (App. A.2); rows and columns beyond n carry the identity so that the padded matrix stays positive definite.
+// The workgroup of block (0, 0) also inverts it: the pivot block of the first elimination step.
+// Grid (np/32, np/32, count), 256 threads.
 __global__ __launch_bounds__(256) void simple_prepare_kernel(const SimpleGroup g) {
   const SimpleArgs& a = g.a[blockIdx.z];
   if ((int)blockIdx.x >= a.nblk || (int)blockIdx.y >= a.nblk) return;
   __shared__ double scratch[16];
+  __shared__ double sRow[2][kSimpleBlock], sCol[2][kSimpleBlock];
   const int tid = threadIdx.x, np = a.np, n = a.n;
   const double* __restrict__ S = a.buf[1];
   double t = 0.0;
@@ -64,28 +111,44 @@ __global__ __launch_bounds__(256) void simple_prepare_kernel(const SimpleGroup g
   }
   const double inv_nm1 = 1.0 / (double)(a.N - 1);
   double* __restrict__ G = a.buf[0];
-  for (int e = tid; e < kSimpleBlock * kSimpleBlock; e += 256) {
+  double blk[4];   // element tid + 256 q of the block: row (tid / 32) + 8 q, column tid % 32
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int e = tid + 256 * q;
     const int i = blockIdx.y * kSimpleBlock + (e >> 5), j = blockIdx.x * kSimpleBlock + (e & 31);
     double v;
     if (i < n && j < n) {
       const bool upper = i / kSimpleGramTile <= j / kSimpleGramTile;   // tiles below the diagonal were not computed
       v = (upper ? S[(size_t)i * np + j] : S[(size_t)j * np + i]) * inv_nm1 + (i == j ? beta : 0.0);
+    } else {
+      v = i == j ? 1.0 : 0.0;
     }
-    else v = i == j ? 1.0 : 0.0;
     G[(size_t)i * np + j] = v;
+    blk[q] = v;
+  }
+  if (blockIdx.x == 0 && blockIdx.y == 0) {
+    invert_block_32(blk, sRow, sCol);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) a.pinv[0][tid + 256 * q] = blk[q];
   }
 }
 
-// One pivot block of the blocked Gauss-Jordan inversion.  Grid (ceil(nblk_max/2), ceil(nblk_max/2), count),
-// 256 threads: wavefront w of workgroup (x, y) owns block (2y + w/2, 2x + w%2).
+// One pivot block k of the blocked Gauss-Jordan inversion.  Grid (ceil(nblk_max/2) + 1, ceil(nblk_max/2), count),
+// 256 threads: wavefront w of workgroup (x, y) owns block (2y + w/2, 2x + w%2) and replaces it, using the inverse
+// P_k of the pivot block that the previous launch left in pinv[k % 2].  The one workgroup of the extra grid column
+// looks ahead: it forms the next pivot block (k+1, k+1) as this step leaves it and inverts it into pinv[(k+1) % 2],
+// so the 32-step elimination is done once per matrix and step, beside the block updates and not before them.
 // v_mfma_f64_16x16x4_f64: lane l supplies A[l%16][l/16] and B[l/16][l%16]; register r of lane l holds
 // row 4r + l/16, column l%16 of the 16 x 16 result.
 __global__ __launch_bounds__(256) void simple_sweep_kernel(const SimpleGroup g, const int k) {
   const SimpleArgs& a = g.a[blockIdx.z];
   const int nblk = a.nblk;
-  if (k >= nblk || 2 * (int)blockIdx.x >= nblk || 2 * (int)blockIdx.y >= nblk) return;   // uniform per workgroup
+  const bool ahead = blockIdx.x == gridDim.x - 1;
+  if (k >= nblk) return;                                                                  // uniform per workgroup
+  if (ahead && (blockIdx.y != 0 || k + 1 >= nblk)) return;
+  if (!ahead && (2 * (int)blockIdx.x >= nblk || 2 * (int)blockIdx.y >= nblk)) return;
   constexpr int B = kSimpleBlock;
-  __shared__ double sP[B][B + 1];      // the inverse of the pivot block
+  __shared__ double sP[B][B + 1];      // P_k
   __shared__ double sRow[2][B], sCol[2][B];
   __shared__ double sT[4][B][B + 1];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -94,20 +157,17 @@ __global__ __launch_bounds__(256) void simple_sweep_kernel(const SimpleGroup g, 
   double* __restrict__ dst = a.buf[(k & 1) ^ 1];
   const size_t k0 = (size_t)k * B;
 
-  const int bi = 2 * blockIdx.y + (wave >> 1), bj = 2 * blockIdx.x + (wave & 1);
-  const bool active = bi < nblk && bj < nblk;
+  const int bi = ahead ? k + 1 : 2 * blockIdx.y + (wave >> 1), bj = ahead ? k + 1 : 2 * blockIdx.x + (wave & 1);
+  const bool active = ahead ? wave == 0 : (bi < nblk && bj < nblk);
   const int l16 = lane & 15, g4 = lane >> 4;
   const size_t i0 = (size_t)bi * B, j0 = (size_t)bj * B;
   typedef double doublex4 __attribute__((ext_vector_type(4)));
 
-  // Everything this wavefront needs from the old matrix is requested before the pivot block is inverted, so the
-  // loads complete under the elimination: A_ik by rows into LDS, A_kj as B-operand fragments, A_ij as accumulators.
+  // everything this wavefront needs is requested up front: P_k, A_ik by rows (it goes to LDS), A_kj as B-operand
+  // fragments, A_ij as accumulators
   double pv[4];
 #pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    const int e = tid + 256 * q;
-    pv[q] = src[(k0 + (e >> 5)) * np + k0 + (e & 31)];
-  }
+  for (int q = 0; q < 4; ++q) pv[q] = a.pinv[k & 1][tid + 256 * q];
   double aik[16];
   double bf[B / 4][2];
   doublex4 acc[2][2];
@@ -133,49 +193,10 @@ __global__ __launch_bounds__(256) void simple_sweep_kernel(const SimpleGroup g, 
             acc[mi][nj][r] = bi != k ? src[(i0 + mi * 16 + 4 * r + g4) * np + j0 + nj * 16 + l16] : 0.0;
     }
   }
-  // Gauss-Jordan on the pivot block.  Thread (c, r0) keeps column c of rows r0, r0+8, r0+16, r0+24 in registers;
-  // a step only needs the pivot row and the pivot column, which their owners publish (for the next step, into
-  // the other pair of arrays) as soon as they have them: one barrier and a few LDS words per step.
-  {
-    const int c = tid & 31, r0 = tid >> 5;
-    double cur[4];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) cur[q] = pv[q];   // element e = tid + 256 q is (r0 + 8 q, c)
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      if (r0 + 8 * q == 0) sRow[0][c] = cur[q];
-      if (c == 0) sCol[0][r0 + 8 * q] = cur[q];
-    }
-    __syncthreads();
-    for (int p = 0; p < B; ++p) {
-      const int par = p & 1;
-      // all LDS reads of the step are issued together, the arithmetic is branch-free (selects)
-      const double piv = sRow[par][p];
-      const double rv = sRow[par][c];
-      double colv[4];
-#pragma unroll
-      for (int q = 0; q < 4; ++q) colv[q] = sCol[par][r0 + 8 * q];
-      double inv = __builtin_amdgcn_rcp(piv);        // hardware estimate, two Newton steps
-      inv = fma(fma(-piv, inv, 1.0), inv, inv);
-      inv = fma(fma(-piv, inv, 1.0), inv, inv);
-      const double rowv = rv * inv;
-      const double on_row = c == p ? inv : rowv;
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int r = r0 + 8 * q;
-        const double off_row = c == p ? -colv[q] * inv : fma(-colv[q], rowv, cur[q]);
-        cur[q] = r == p ? on_row : off_row;
-      }
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int r = r0 + 8 * q;
-        if (r == p + 1) sRow[par ^ 1][c] = cur[q];
-        if (c == p + 1) sCol[par ^ 1][r] = cur[q];
-      }
-      __syncthreads();
-    }
-#pragma unroll
-    for (int q = 0; q < 4; ++q) sP[r0 + 8 * q][c] = cur[q];
+  for (int q = 0; q < 4; ++q) {
+    const int e = tid + 256 * q;
+    sP[e >> 5][e & 31] = pv[q];
   }
   __syncthreads();
   const double (*P)[B + 1] = sP;
@@ -223,10 +244,12 @@ __global__ __launch_bounds__(256) void simple_sweep_kernel(const SimpleGroup g, 
     for (int e = lane; e < B * B; e += 64) sT[wave][e >> 5][e & 31] = -P[e >> 5][e & 31];
   }
   __syncthreads();
-  if (!active) return;
+  if (!active && !ahead) return;
 
   // new block: (bj != k)  C0 - T A_kj with C0 = A_ij (bi != k) or 0;   (bj == k)  -T
-  if (bj != k) {
+  if (!active) {
+    // look-ahead workgroup, wavefronts 1..3: nothing to multiply
+  } else if (bj != k) {
 #pragma unroll
     for (int ks = 0; ks < B / 4; ++ks) {
       double af[2];
@@ -245,6 +268,28 @@ __global__ __launch_bounds__(256) void simple_sweep_kernel(const SimpleGroup g, 
       for (int nj = 0; nj < 2; ++nj)
 #pragma unroll
         for (int r = 0; r < 4; ++r) acc[mi][nj][r] = -sT[wave][mi * 16 + 4 * r + g4][nj * 16 + l16];
+  }
+  if (ahead) {
+    // the next pivot block is in wavefront 0's accumulators: through LDS to the elimination's layout, invert, publish
+    if (active) {
+#pragma unroll
+      for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int nj = 0; nj < 2; ++nj)
+#pragma unroll
+          for (int r = 0; r < 4; ++r) sT[1][mi * 16 + 4 * r + g4][nj * 16 + l16] = acc[mi][nj][r];
+    }
+    __syncthreads();
+    double blk[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int e = tid + 256 * q;
+      blk[q] = sT[1][e >> 5][e & 31];
+    }
+    invert_block_32(blk, sRow, sCol);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) a.pinv[(k + 1) & 1][tid + 256 * q] = blk[q];
+    return;
   }
   const bool last = k == nblk - 1;
 #pragma unroll
