@@ -80,11 +80,13 @@ __device__ __forceinline__ void invert_block_32(double (&cur)[4], double (*sRow)
       const double off_row = c == p ? -colv[q] * inv : fma(-colv[q], rowv, cur[q]);
       cur[q] = r == p ? on_row : off_row;
     }
+    // row p+1 is register (p+1)/8 of the threads with r0 = (p+1) % 8; column p+1 is all four registers of two lanes
+    const int qn = (p + 1) >> 3;
+    const double next_row = qn == 0 ? cur[0] : (qn == 1 ? cur[1] : (qn == 2 ? cur[2] : cur[3]));
+    if (r0 == ((p + 1) & 7)) sRow[par ^ 1][c] = next_row;
+    if (c == p + 1) {
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int r = r0 + 8 * q;
-      if (r == p + 1) sRow[par ^ 1][c] = cur[q];
-      if (c == p + 1) sCol[par ^ 1][r] = cur[q];
+      for (int q = 0; q < 4; ++q) sCol[par ^ 1][r0 + 8 * q] = cur[q];
     }
     __syncthreads();
   }
@@ -310,11 +312,18 @@ __global__ __launch_bounds__(256) void simple_rows_kernel(const SimpleGroup g) {
   const int i = blockIdx.x;
   if (i >= a.N) return;
   __shared__ double scratch[16];
-  const int tid = threadIdx.x;
-  float* __restrict__ x = a.M + (size_t)i * a.ld;
+  const int tid = threadIdx.x, D = a.D, D4 = D >> 2;
+  float* __restrict__ x = a.M + (size_t)i * a.ld;           // rows start on 16-byte boundaries
   const float* __restrict__ q = a.Q + (size_t)i * a.ldq;
+  float4* __restrict__ x4 = reinterpret_cast<float4*>(x);
+  const float4* __restrict__ q4 = reinterpret_cast<const float4*>(q);
   double dot = 0.0, qq = 0.0;
-  for (int c = tid; c < a.D; c += 256) {
+  for (int c = tid; c < D4; c += 256) {
+    const float4 xv = x4[c], qv = q4[c];
+    dot += (double)xv.x * qv.x + (double)xv.y * qv.y + (double)xv.z * qv.z + (double)xv.w * qv.w;
+    qq += (double)qv.x * qv.x + (double)qv.y * qv.y + (double)qv.z * qv.z + (double)qv.w * qv.w;
+  }
+  for (int c = 4 * D4 + tid; c < D; c += 256) {
     const double xv = x[c], qv = q[c];
     dot += xv * qv;
     qq += qv * qv;
@@ -322,7 +331,11 @@ __global__ __launch_bounds__(256) void simple_rows_kernel(const SimpleGroup g) {
   dot = block_sum(dot, scratch);
   qq = block_sum(qq, scratch);
   const double b = 1.0 + dot / ((double)(a.N - 1) - dot);
-  for (int c = tid; c < a.D; c += 256) x[c] = (float)(b * (double)q[c]);
+  for (int c = tid; c < D4; c += 256) {
+    const float4 qv = q4[c];
+    x4[c] = make_float4((float)(b * qv.x), (float)(b * qv.y), (float)(b * qv.z), (float)(b * qv.w));
+  }
+  for (int c = 4 * D4 + tid; c < D; c += 256) x[c] = (float)(b * (double)q[c]);
   if (tid == 0) a.prow[i] = b * b * qq;
 }
 
