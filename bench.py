@@ -206,6 +206,54 @@ def run_precond_bench(calls=200):
     return out
 
 
+def run_wide_bench(steps=40, warmup=12):
+    """BASELINE configs[3]: the wider tanh DNN (440 -> 6 x tanh 2048 -> 8000, minibatch 1024, ranks 20 / 80),
+    whose layer products (1024 x 2049 x 2048) are large enough to fill the chip several times over."""
+    import torch
+
+    import paper_1410_7455_amd as ng
+    import workloads
+
+    spec = workloads.c3_wide_tanh()
+    n = spec.minibatch
+    net = ng.Network(spec.dims, spec.nonlin, n, spec.pnorm_group, spec.rank_in, spec.rank_out, spec.alpha,
+                     spec.num_samples_history, spec.epsilon, spec.update_period, max_change_per_sample=0.075)
+    for l, w in enumerate(workloads.initial_weights(spec)):
+        net.set_params(l, torch.from_numpy(w).cuda())
+    pool = []
+    for t in range(4):
+        x, y = workloads.minibatch(spec, t)
+        pool.append((torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda()))
+    logp = torch.zeros(1, dtype=torch.float64, device="cuda")
+    for t in range(warmup):
+        net.step(*pool[t % 4], spec.lr, logp)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(steps):
+        net.step(*pool[(warmup + t) % 4], spec.lr, logp)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    final_logp = float(logp.item()) / n
+    ng.profile_enable(True)
+    for t in range(steps):
+        net.step(*pool[t % 4], spec.lr, logp)
+    torch.cuda.synchronize()
+    prof = ng.profile_read()
+    ng.profile_enable(False)
+    flops = gemm_flops_per_step(spec, n)
+    gemm = {k: dict(ms_per_step=prof[k][0] / steps, tflops=flops[k] * steps / (prof[k][0] * 1e-3) / 1e12) for k in flops}
+    all_tf = sum(flops.values()) * steps / (sum(prof[k][0] for k in flops) * 1e-3) / 1e12
+    log(f"[bench] configs[3] wide tanh net: {elapsed * 1e3 / steps:.3f} ms/step, {n * steps / elapsed:,.0f} frames/s, "
+        f"layer GEMMs {all_tf:.1f} TFLOP/s ({all_tf / PEAK_MFMA_F32_TFLOPS * 100:.0f} % of fp32 matrix peak): "
+        + ", ".join(f"{k} {v['tflops']:.1f}" for k, v in gemm.items()) + f"; mean log-prob {final_logp:.4f}")
+    del net
+    return dict(workload="configs[3] wider tanh DNN: 440 -> 6x tanh 2048 -> 8000, minibatch 1024, ranks 20/80, "
+                         "update period 4, max-change 0.075, lr 0.01",
+                value=n * steps / elapsed, unit="frames/s", ms_per_step=elapsed * 1e3 / steps, steps=steps,
+                final_mean_logprob=final_logp, gemm=gemm, all_gemms_tflops=all_tf,
+                all_gemms_mfma_frac=all_tf / PEAK_MFMA_F32_TFLOPS)
+
+
 def run_simple_bench(steps=60, warmup=5, calls=40):
     """The simple method of App. A on the same workloads: the configs[1] step with every one of the 2I matrices
     preconditioned from the other rows of its own minibatch (no factor state), and the two configs[2] matrix
@@ -395,6 +443,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-precond", action="store_true")
     ap.add_argument("--no-replicas", action="store_true")
+    ap.add_argument("--no-wide", action="store_true", help="skip the configs[3] leg (wider tanh DNN)")
     ap.add_argument("--no-simple", action="store_true", help="skip the simple-method leg (App. A)")
     ap.add_argument("--precond-only", action="store_true",
                     help="run only the preconditioner microbenchmark (BASELINE configs[2]); used for its profile")
@@ -428,6 +477,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     precond = None if args.no_precond else run_precond_bench()
+    wide = None if args.no_wide else run_wide_bench()
     simple = None if args.no_simple else run_simple_bench()
     replica = None if args.no_replicas else run_replica_bench()
     cpu = None if args.no_cpu_baseline else run_cpu_baseline()
@@ -455,6 +505,7 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
         "precondition_roofline": precond,
+        "wide_tanh_net": wide,
         "simple_method": simple,
         "replica_interleaving": replica,
         "breakdown": breakdown,

@@ -152,19 +152,33 @@ struct StageKC {
       s += row_ok[i] * (reg[i].x * reg[i].x + reg[i].y * reg[i].y + reg[i].z * reg[i].z + reg[i].w * reg[i].w);
     return s;
   }
-  // fragment for MFMA tile at tile row offset `row` and k-group kk (16 k values each)
-  __device__ __forceinline__ static float4 frag(const float* lds, int row, int kk, int g) {
-    return *reinterpret_cast<const float4*>(&lds[row * (BK + 4) + kk * 16 + 4 * g]);
+  // Operand fragments of a wavefront's T MFMA tiles for k-group kk (16 k values): out[t] holds the four k values
+  // 16 kk + 4 g + {0..3} of the tile row that lane r16 supplies.  Tile t covers rows row0 + 16 t + (0..15).
+  template <int T>
+  __device__ __forceinline__ static void frags(const float* lds, int row0, int r16, int kk, int g, float4 (&out)[T]) {
+#pragma unroll
+    for (int t = 0; t < T; ++t)
+      out[t] = *reinterpret_cast<const float4*>(&lds[(row0 + t * 16 + r16) * (BK + 4) + kk * 16 + 4 * g]);
   }
+  // row (inside the wavefront's T tiles) of MFMA tile t, tile row j
+  template <int T>
+  __device__ __forceinline__ static int tile_row(int t, int j) { return t * 16 + j; }
 };
 
-// Row-contiguous operand: element (row, k) at base[k*ld + row]; LDS layout [BK][ROWS+4].
-template <int ROWS, int BK, int NT>
+// Row-contiguous operand: element (row, k) at base[k*ld + row]; LDS layout [BK][ROWS+PAD].  T is the number of
+// MFMA tiles a wavefront has along this operand's rows.  The tiles are interleaved: tile t covers rows
+// row0 + T j + t (j = 0..15), so the T values a lane needs for one k are adjacent in LDS and come with one read of
+// the widest width that divides T (one 16-byte read for T = 4 instead of four 4-byte reads).  PAD keeps the
+// k rows that the four 16-lane groups of a read touch on different banks.
+template <int ROWS, int BK, int NT, int T>
 struct StageRC {
+  static constexpr int VW = (T % 4 == 0) ? 4 : ((T % 2 == 0) ? 2 : 1);   // floats per LDS read
+  static constexpr int PAD = VW == 2 ? 8 : 4;
+  static constexpr int LD = ROWS + PAD;
   static constexpr int F4_PER_K = ROWS / 4;
   static constexpr int TOTAL = BK * F4_PER_K;
   static constexpr int ITER = (TOTAL + NT - 1) / NT;
-  static constexpr int LDS_FLOATS = BK * (ROWS + 4);
+  static constexpr int LDS_FLOATS = BK * LD;
   using Regs = floatx4[ITER];
   const float* ptr[ITER];
   int kq[ITER];             // k index of the piece inside a K-block
@@ -182,7 +196,7 @@ struct StageRC {
       const int r4 = (f % F4_PER_K) * 4;
       const int gr = row0 + r4;
       ptr[i] = base + (size_t)(k_begin + kq[i]) * ld + min(gr, (rows_total - 1) & ~3);
-      lds_off[i] = (TOTAL % NT == 0 || tid + i * NT < TOTAL) ? kq[i] * (ROWS + 4) + r4 : -1;
+      lds_off[i] = (TOTAL % NT == 0 || tid + i * NT < TOTAL) ? kq[i] * LD + r4 : -1;
 #pragma unroll
       for (int c = 0; c < 4; ++c) row_ok[i][c] = (gr + c < rows_total && lds_off[i] >= 0) ? 1.f : 0.f;
     }
@@ -221,19 +235,40 @@ struct StageRC {
            row_ok[i][3] * reg[i].w * reg[i].w;
     return s;
   }
-  __device__ __forceinline__ static float4 frag(const float* lds, int row, int kk, int g) {
-    const float* p = &lds[(kk * 16 + 4 * g) * (ROWS + 4) + row];
-    return make_float4(p[0], p[ROWS + 4], p[2 * (ROWS + 4)], p[3 * (ROWS + 4)]);
+  template <int T_>
+  __device__ __forceinline__ static void frags(const float* lds, int row0, int r16, int kk, int g, float4 (&out)[T_]) {
+    static_assert(T_ == T, "tiles per wavefront");
+    const float* p = &lds[(kk * 16 + 4 * g) * LD + row0 + r16 * T];
+    float v[4][T];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+#pragma unroll
+      for (int t = 0; t < T; t += VW) {
+        if (VW == 4) {
+          const float4 x = *reinterpret_cast<const float4*>(p + q * LD + t);
+          v[q][t] = x.x; v[q][t + 1] = x.y; v[q][t + 2] = x.z; v[q][t + 3] = x.w;
+        } else if (VW == 2) {
+          const float2 x = *reinterpret_cast<const float2*>(p + q * LD + t);
+          v[q][t] = x.x; v[q][t + 1] = x.y;
+        } else {
+          v[q][t] = p[q * LD + t];
+        }
+      }
+    }
+#pragma unroll
+    for (int t = 0; t < T; ++t) out[t] = make_float4(v[0][t], v[1][t], v[2][t], v[3][t]);
   }
+  template <int T_>
+  __device__ __forceinline__ static int tile_row(int t, int j) { return j * T + t; }
 };
 
-template <bool KC, int ROWS, int BK, int NT>
+template <bool KC, int ROWS, int BK, int NT, int T>
 struct StageSelect {
   using type = StageKC<ROWS, BK, NT>;
 };
-template <int ROWS, int BK, int NT>
-struct StageSelect<false, ROWS, BK, NT> {
-  using type = StageRC<ROWS, BK, NT>;
+template <int ROWS, int BK, int NT, int T>
+struct StageSelect<false, ROWS, BK, NT, T> {
+  using type = StageRC<ROWS, BK, NT, T>;
 };
 
 // Sum over the 16 lanes of a DPP row, through the vector ALU's cross-lane path (no LDS traffic): xor 1 and xor 2
@@ -266,8 +301,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmGroup g) 
   constexpr int TM = WM / 16, TN = WN / 16;
   static_assert(WM % 16 == 0 && WN % 16 == 0, "wave tile must be a multiple of 16x16");
   static_assert(BK % 16 == 0, "BK must be a multiple of 16");
-  using StageA = typename StageSelect<A_KC, BM, BK, NT>::type;
-  using StageB = typename StageSelect<B_KC, BN, BK, NT>::type;
+  using StageA = typename StageSelect<A_KC, BM, BK, NT, TM>::type;
+  using StageB = typename StageSelect<B_KC, BN, BK, NT, TN>::type;
   constexpr int EPI_LDS = (EPI == EPI_SUB_ROWNORM) ? WGN * BM : 0;
   constexpr int LDS_TOTAL = 2 * (StageA::LDS_FLOATS + StageB::LDS_FLOATS);
   __shared__ __attribute__((aligned(16))) float lds[(LDS_TOTAL > EPI_LDS ? LDS_TOTAL : EPI_LDS)];
@@ -375,10 +410,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmGroup g) 
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
       float4 af[TM], bf[TN];
-#pragma unroll
-      for (int ti = 0; ti < TM; ++ti) af[ti] = StageA::frag(a_lds, wm * WM + ti * 16 + r16, kk, g4);
-#pragma unroll
-      for (int tj = 0; tj < TN; ++tj) bf[tj] = StageB::frag(b_lds, wn * WN + tj * 16 + r16, kk, g4);
+      StageA::template frags<TM>(a_lds, wm * WM, r16, kk, g4, af);
+      StageB::template frags<TN>(b_lds, wn * WN, r16, kk, g4, bf);
       // one k value at a time over all TM x TN accumulators: consecutive MFMAs are independent, so a wave
       // that is alone on its SIMD still issues them back to back
 #pragma unroll
@@ -434,8 +467,13 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmGroup g) 
   for (int i = 0; i < 3; ++i)
     if (P.alpha_dev[i] != nullptr) alpha *= (float)(*P.alpha_dev[i]);
 
-  // accumulator layout: register r of lane l holds column l%16 and row 4*(l/16)+r for v_mfma_f32_16x16x4_f32,
-  // row 4*r+(l/16) for v_mfma_f64_16x16x4_f64
+  // accumulator layout: register r of lane l holds tile column l%16 and tile row 4*(l/16)+r for
+  // v_mfma_f32_16x16x4_f32, tile row 4*r+(l/16) for v_mfma_f64_16x16x4_f64; where a tile's rows and columns lie
+  // in the wavefront's part of C is the operand staging's business (interleaved for row-contiguous operands)
+  auto local_row = [&](const int i, const int r) {
+    return wm * WM + StageA::template tile_row<TM>(i, ACC64 ? 4 * r + g4 : 4 * g4 + r);
+  };
+  auto local_col = [&](const int j) { return wn * WN + StageB::template tile_row<TN>(j, r16); };
   if (EPI == EPI_SUB_ROWNORM) {
     float* C = static_cast<float*>(P.C);
     float* rowsum = lds;  // [WGN][BM], operand tiles are no longer needed
@@ -443,12 +481,12 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmGroup g) 
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        const int lrow = wm * WM + i * 16 + (ACC64 ? 4 * r + g4 : 4 * g4 + r);
+        const int lrow = local_row(i, r);
         const int row = m0 + lrow;
         float sq = 0.f;
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-          const int col = n0 + wn * WN + j * 16 + r16;
+          const int col = n0 + local_col(j);
           if (row < M && col < N) {
             float* c = C + (size_t)row * P.ldc + col;
             const float v = *c - (float)acc[i][j][r];
@@ -477,10 +515,10 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmGroup g) 
   for (int i = 0; i < TM; ++i) {
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
-      const int col = n0 + wn * WN + j * 16 + r16;
+      const int col = n0 + local_col(j);
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        const int row = m0 + wm * WM + i * 16 + (ACC64 ? 4 * r + g4 : 4 * g4 + r);
+        const int row = m0 + local_row(i, r);
         if (row < M && col < N) {
           const float v = ACC64 ? (float)((double)alpha * (double)acc[i][j][r]) : alpha * (float)acc[i][j][r];
           if (EPI == EPI_STORE) {
