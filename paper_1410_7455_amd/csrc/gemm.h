@@ -15,6 +15,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <stdint.h>
 
 namespace ngsgd {
 
@@ -170,9 +171,11 @@ struct StageKC {
 // row0 + T j + t (j = 0..15), so the T values a lane needs for one k are adjacent in LDS and come with one read of
 // the widest width that divides T (one 16-byte read for T = 4 instead of four 4-byte reads).  PAD keeps the
 // k rows that the four 16-lane groups of a read touch on different banks.
-template <int ROWS, int BK, int NT, int T>
+// With IL false the tiles are not interleaved (tile t covers rows row0 + 16 t + j, four 4-byte reads each): the
+// atomic epilogues want a wavefront's 16 lanes on adjacent columns of C.
+template <int ROWS, int BK, int NT, int T, bool IL>
 struct StageRC {
-  static constexpr int VW = (T % 4 == 0) ? 4 : ((T % 2 == 0) ? 2 : 1);   // floats per LDS read
+  static constexpr int VW = !IL ? 1 : ((T % 4 == 0) ? 4 : ((T % 2 == 0) ? 2 : 1));   // floats per LDS read
   static constexpr int PAD = VW == 2 ? 8 : 4;
   static constexpr int LD = ROWS + PAD;
   static constexpr int F4_PER_K = ROWS / 4;
@@ -238,6 +241,14 @@ struct StageRC {
   template <int T_>
   __device__ __forceinline__ static void frags(const float* lds, int row0, int r16, int kk, int g, float4 (&out)[T_]) {
     static_assert(T_ == T, "tiles per wavefront");
+    if (!IL) {
+#pragma unroll
+      for (int t = 0; t < T; ++t) {
+        const float* p = &lds[(kk * 16 + 4 * g) * LD + row0 + t * 16 + r16];
+        out[t] = make_float4(p[0], p[LD], p[2 * LD], p[3 * LD]);
+      }
+      return;
+    }
     const float* p = &lds[(kk * 16 + 4 * g) * LD + row0 + r16 * T];
     float v[4][T];
 #pragma unroll
@@ -259,16 +270,16 @@ struct StageRC {
     for (int t = 0; t < T; ++t) out[t] = make_float4(v[0][t], v[1][t], v[2][t], v[3][t]);
   }
   template <int T_>
-  __device__ __forceinline__ static int tile_row(int t, int j) { return j * T + t; }
+  __device__ __forceinline__ static int tile_row(int t, int j) { return IL ? j * T + t : t * 16 + j; }
 };
 
-template <bool KC, int ROWS, int BK, int NT, int T>
+template <bool KC, int ROWS, int BK, int NT, int T, bool IL>
 struct StageSelect {
   using type = StageKC<ROWS, BK, NT>;
 };
-template <int ROWS, int BK, int NT, int T>
-struct StageSelect<false, ROWS, BK, NT, T> {
-  using type = StageRC<ROWS, BK, NT, T>;
+template <int ROWS, int BK, int NT, int T, bool IL>
+struct StageSelect<false, ROWS, BK, NT, T, IL> {
+  using type = StageRC<ROWS, BK, NT, T, IL>;
 };
 
 // Sum over the 16 lanes of a DPP row, through the vector ALU's cross-lane path (no LDS traffic): xor 1 and xor 2
@@ -301,8 +312,11 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmGroup g) 
   constexpr int TM = WM / 16, TN = WN / 16;
   static_assert(WM % 16 == 0 && WN % 16 == 0, "wave tile must be a multiple of 16x16");
   static_assert(BK % 16 == 0, "BK must be a multiple of 16");
-  using StageA = typename StageSelect<A_KC, BM, BK, NT, TM>::type;
-  using StageB = typename StageSelect<B_KC, BN, BK, NT, TN>::type;
+  // B's tiles set the columns a lane owns: interleaved, they are TN adjacent columns (vector stores); the atomic
+  // epilogues keep the 16 lanes of a tile row on adjacent columns instead
+  constexpr bool B_IL = EPI == EPI_STORE || EPI == EPI_SUB_ROWNORM;
+  using StageA = typename StageSelect<A_KC, BM, BK, NT, TM, true>::type;
+  using StageB = typename StageSelect<B_KC, BN, BK, NT, TN, B_IL>::type;
   constexpr int EPI_LDS = (EPI == EPI_SUB_ROWNORM) ? WGN * BM : 0;
   constexpr int LDS_TOTAL = 2 * (StageA::LDS_FLOATS + StageB::LDS_FLOATS);
   __shared__ __attribute__((aligned(16))) float lds[(LDS_TOTAL > EPI_LDS ? LDS_TOTAL : EPI_LDS)];
@@ -506,6 +520,47 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmGroup g) 
 #pragma unroll
         for (int w = 0; w < WGN; ++w) s += rowsum[w * BM + lrow];
         P.aux[(size_t)tn * M + row] = s;
+      }
+    }
+    return;
+  }
+
+  if (EPI == EPI_STORE && !B_KC && (TN == 2 || TN == 4)) {
+    // a lane owns TN adjacent columns of each of its rows: one vector store where the row allows it
+    float* const C = static_cast<float*>(P.C) + (size_t)split * P.c_split_stride;
+    const int col0 = n0 + local_col(0);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int row = m0 + local_row(i, r);
+        if (row >= M || col0 >= N) continue;
+        float v[TN];
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          v[j] = ACC64 ? (float)((double)alpha * (double)acc[i][j][r]) : alpha * (float)acc[i][j][r];
+        float* c = C + (size_t)row * P.ldc + col0;
+        if (col0 + TN <= N && (reinterpret_cast<uintptr_t>(c) & (4 * TN - 1)) == 0) {
+          if (TN == 4) {
+            float4 o = make_float4(v[0], v[1], v[2], v[TN - 1]);
+            if (P.beta != 0.f) {
+              const float4 old = *reinterpret_cast<const float4*>(c);
+              o.x += P.beta * old.x; o.y += P.beta * old.y; o.z += P.beta * old.z; o.w += P.beta * old.w;
+            }
+            *reinterpret_cast<float4*>(c) = o;
+          } else {
+            float2 o = make_float2(v[0], v[1]);
+            if (P.beta != 0.f) {
+              const float2 old = *reinterpret_cast<const float2*>(c);
+              o.x += P.beta * old.x; o.y += P.beta * old.y;
+            }
+            *reinterpret_cast<float2*>(c) = o;
+          }
+        } else {
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            if (col0 + j < N) c[j] = (P.beta != 0.f) ? v[j] + P.beta * c[j] : v[j];
+        }
       }
     }
     return;

@@ -70,9 +70,11 @@ __global__ void fill_zero_group_kernel(const FillGroup g) {
 }
 
 // out[n][0..D) = x[n][0..D), out[n][D] = 1, out[n][D+1..ldo) = 0   (input with the bias 1 appended, Sec. 4.4)
+// Also clears *clear (the step's objective accumulator), if given.
 __global__ void copy_append_ones_kernel(const float* __restrict__ x, int ldx, float* __restrict__ out, int ldo,
-                                        int N, int D) {
+                                        int N, int D, double* __restrict__ clear) {
   const int row = blockIdx.y;
+  if (clear != nullptr && row == 0 && blockIdx.x == 0 && threadIdx.x == 0) *clear = 0.0;
   for (int c = blockIdx.x * blockDim.x + threadIdx.x; c < ldo; c += gridDim.x * blockDim.x)
     out[(size_t)row * ldo + c] = c < D ? x[(size_t)row * ldx + c] : (c == D ? 1.f : 0.f);
 }
@@ -200,6 +202,7 @@ __global__ __launch_bounds__(256) void pnorm_forward_kernel(const float* __restr
 // with dy = dYn, y = Yn without renorm; with renorm  y = Yn*sigma, dy = (dYn - Yn * mean_j(dYn_j Yn_j)) / sigma.
 // dYn arrives as n_slabs partial products (see slab_sum).  The per-group factor dy_j / y_j goes through LDS.
 constexpr int kPnormMaxGroupsLds = 4096;
+constexpr int kPnormPrefetch = 8;   // float2 per thread held across the reductions (rows of up to 4096 outputs)
 
 __global__ __launch_bounds__(256) void pnorm_backward_kernel(const float* __restrict__ dYn, int ldd, int n_slabs,
                                                              size_t slab_stride,
@@ -213,6 +216,18 @@ __global__ __launch_bounds__(256) void pnorm_backward_kernel(const float* __rest
   const float* dy = dYn + (size_t)row * ldd;
   const float* yn = Yn + (size_t)row * ldy;
   float* ao = AO + (size_t)row * lda;
+  const int D = groups * G;
+  // the affine outputs this thread will rescale are requested first: they arrive while the row's factors are made
+  const bool vec2 = (G & 1) == 0 && (lda & 1) == 0;
+  float2* ao2 = reinterpret_cast<float2*>(ao);
+  float2 pre[kPnormPrefetch];
+  if (vec2) {
+#pragma unroll
+    for (int u = 0; u < kPnormPrefetch; ++u) {
+      const int c2 = threadIdx.x + u * 256;
+      if (c2 < D / 2) pre[u] = ao2[c2];
+    }
+  }
   float dot = 0.f;
   for (int j = threadIdx.x; j < groups; j += 256) {
     const float d = slab_sum(dy + j, n_slabs, slab_stride);
@@ -233,11 +248,17 @@ __global__ __launch_bounds__(256) void pnorm_backward_kernel(const float* __rest
     s_f[j] = yj > 0.f ? d / yj : 0.f;
   }
   __syncthreads();
-  const int D = groups * G;
-  if ((G & 1) == 0 && (lda & 1) == 0) {
-    float2* ao2 = reinterpret_cast<float2*>(ao);
+  if (vec2) {
     const int half_g = G / 2;
-    for (int c2 = threadIdx.x; c2 < D / 2; c2 += 256) {
+#pragma unroll
+    for (int u = 0; u < kPnormPrefetch; ++u) {
+      const int c2 = threadIdx.x + u * 256;
+      if (c2 < D / 2) {
+        const float f = s_f[c2 / half_g];
+        ao2[c2] = make_float2(pre[u].x * f, pre[u].y * f);
+      }
+    }
+    for (int c2 = threadIdx.x + kPnormPrefetch * 256; c2 < D / 2; c2 += 256) {
       const float f = s_f[c2 / half_g];
       float2 v = ao2[c2];
       v.x *= f;
@@ -251,12 +272,12 @@ __global__ __launch_bounds__(256) void pnorm_backward_kernel(const float* __rest
 
 // ---- log-softmax, objective and its derivative (Sec. 2) ------------------------------------------
 // One 256-thread workgroup per row, in place: AO[n][c] <- [c == y_n] - softmax(a_n)_c;
-// rowobj[n] = log p(y_n | x_n).  Rows of up to 256*4*kSoftmaxVec classes are read once and kept in registers.
+// rowobj[n] = log p(y_n | x_n), also added to *total.  Rows of up to 256*4*kSoftmaxVec classes are read once and kept in registers.
 constexpr int kSoftmaxVec = 8;   // float4 per thread
 
 __global__ __launch_bounds__(256) void softmax_xent_kernel(float* __restrict__ AO, int ld,
                                                            const int32_t* __restrict__ labels, int N, int C,
-                                                           double* __restrict__ rowobj) {
+                                                           double* __restrict__ rowobj, double* __restrict__ total) {
   __shared__ float red[4];
   const int row = blockIdx.x;
   float* a = AO + (size_t)row * ld;
@@ -290,7 +311,11 @@ __global__ __launch_bounds__(256) void softmax_xent_kernel(float* __restrict__ A
       s += (v[u].x + v[u].y) + (v[u].z + v[u].w);
     }
     s = block256_sum(s, red);
-    if (threadIdx.x == 0) rowobj[row] = valid ? (double)a[y] - ((double)m + log((double)s)) : (double)NAN;
+    if (threadIdx.x == 0) {
+      const double lp = valid ? (double)a[y] - ((double)m + log((double)s)) : (double)NAN;
+      rowobj[row] = lp;
+      unsafeAtomicAdd(total, lp);   // the objective, cleared at the start of the step (fp64: order does not matter)
+    }
     __syncthreads();   // a[y] is read before any thread overwrites the row
     const float inv = 1.f / s;
 #pragma unroll
@@ -319,18 +344,13 @@ __global__ __launch_bounds__(256) void softmax_xent_kernel(float* __restrict__ A
   for (int c = threadIdx.x; c < C; c += 256) s += expf(a[c] - m);
   s = block256_sum(s, red);
   const float lse = m + logf(s);
-  if (threadIdx.x == 0) rowobj[row] = valid ? (double)a[y] - ((double)m + log((double)s)) : (double)NAN;
+  if (threadIdx.x == 0) {
+    const double lp = valid ? (double)a[y] - ((double)m + log((double)s)) : (double)NAN;
+    rowobj[row] = lp;
+    unsafeAtomicAdd(total, lp);
+  }
   __syncthreads();
   for (int c = threadIdx.x; c < C; c += 256) a[c] = (c == y ? 1.f : 0.f) - expf(a[c] - lse);
-}
-
-__global__ __launch_bounds__(256) void sum_double_kernel(const double* __restrict__ v, int n,
-                                                         double* __restrict__ out) {
-  __shared__ double scratch[16];
-  double s = 0.0;
-  for (int i = threadIdx.x; i < n; i += blockDim.x) s += v[i];
-  s = block_sum(s, scratch);
-  if (threadIdx.x == 0) *out = s;
 }
 
 // ---- preconditioner helpers -----------------------------------------------------------------------

@@ -1313,11 +1313,13 @@ extern "C" int ngsgd_step(ngsgd_net* net, const float* dev_x, const int32_t* dev
     if (L.pout.rank > 0 && L.pout.t == 0 && N <= L.pout.rank) return NGSGD_EINVAL;
   }
 
-  // forward (Sec. 2): A_l = [X_l, 1] W_l^T, nonlinearity, log-softmax
+  // forward (Sec. 2): A_l = [X_l, 1] W_l^T, nonlinearity, log-softmax; the objective is cleared by the first
+  // kernel of the step and accumulated by the log-softmax kernel
+  double* const objective = dev_logprob_sum != nullptr ? dev_logprob_sum : net->logprob;
   {
     ProfScope prof(NGSGD_PROF_ELEMENTWISE, s);
     hipLaunchKernelGGL(copy_append_ones_kernel, dim3((Ls[0].ldx + 255) / 256, N), dim3(256), 0, s, dev_x, Ls[0].din,
-                       Ls[0].Xin, Ls[0].ldx, N, Ls[0].din);
+                       Ls[0].Xin, Ls[0].ldx, N, Ls[0].din, objective);
     LAUNCH_CHECK();
   }
   for (int l = 0; l < nl; ++l) {
@@ -1345,10 +1347,7 @@ extern "C" int ngsgd_step(ngsgd_net* net, const float* dev_x, const int32_t* dev
   {
   ProfScope prof(NGSGD_PROF_ELEMENTWISE, s);
   hipLaunchKernelGGL(softmax_xent_kernel, dim3(N), dim3(256), 0, s, last.A, last.lda, dev_labels, N, last.dout,
-                     net->rowobj);
-  LAUNCH_CHECK();
-  hipLaunchKernelGGL(sum_double_kernel, dim3(1), dim3(256), 0, s, net->rowobj, N,
-                     dev_logprob_sum != nullptr ? dev_logprob_sum : net->logprob);
+                     net->rowobj, objective);
   LAUNCH_CHECK();
   }
 
