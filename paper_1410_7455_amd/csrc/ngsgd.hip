@@ -132,8 +132,11 @@ struct ngsgd_precond {
   double* prow = nullptr;
   // initialisation scratch
   int n_init_max = 0;
-  double* Ai[2] = {nullptr, nullptr};
-  double* Vi[2] = {nullptr, nullptr};
+  double* Ai = nullptr;
+  double* Vi = nullptr;
+  double* Qi = nullptr;
+  double* init_stat = nullptr;
+  int* init_cnt = nullptr;
   int* idx = nullptr;
   double* vwork = nullptr;
   double2* rotlog = nullptr;      // Jacobi rotation log of the latest factor update
@@ -168,11 +171,12 @@ void precond_layout(ngsgd_precond& p, Carver& c) {
   p.rownorm_part = c.take<float>((size_t)p.max_col_tiles * NB);
   p.sumsq_part = c.take<double>(kSumsqMax);
   p.n_init_max = NB < D ? NB : D;
-  const size_t nn = (size_t)p.n_init_max * p.n_init_max;
-  p.Ai[0] = c.take<double>(nn);
-  p.Ai[1] = c.take<double>(nn);
-  p.Vi[0] = c.take<double>(nn);
-  p.Vi[1] = c.take<double>(nn);
+  const size_t np_init = (size_t)(p.n_init_max + kInitPair - 1) / kInitPair * kInitPair;
+  p.Ai = c.take<double>(np_init * np_init);
+  p.Vi = c.take<double>(np_init * np_init);
+  p.Qi = c.take<double>(np_init / kInitPair * kInitPair * kInitPair);
+  p.init_stat = c.take<double>(2);
+  p.init_cnt = c.take<int>(4);
   p.idx = c.take<int>(kMaxRank);
   p.vwork = c.take<double>((size_t)kMaxRank + D);
   {
@@ -216,6 +220,8 @@ int ensure_kernel_attributes() {
                               hipFuncAttributeMaxDynamicSharedMemorySize, max_dyn));
   HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(orth_apply_kernel),
                               hipFuncAttributeMaxDynamicSharedMemorySize, max_dyn));
+  HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(init_block_solve_kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, kInitSolveLds));
   g_attr_done = true;
   return NGSGD_OK;
 }
@@ -354,10 +360,12 @@ int run_init(const std::vector<PrecondCall>& calls, hipStream_t s) {
       a.R = p.rank;
       a.use_cov = p.dim <= c.N ? 1 : 0;
       a.n = a.use_cov ? p.dim : c.N;
-      a.A[0] = p.Ai[0];
-      a.A[1] = p.Ai[1];
-      a.V[0] = p.Vi[0];
-      a.V[1] = p.Vi[1];
+      a.np = (a.n + kInitPair - 1) / kInitPair * kInitPair;
+      a.A = p.Ai;
+      a.V = p.Vi;
+      a.Q = p.Qi;
+      a.stat = p.init_stat;
+      a.cnt = p.init_cnt;
       a.idx = p.idx;
       a.W = p.W;
       a.ldw = p.ldw;
@@ -368,23 +376,23 @@ int run_init(const std::vector<PrecondCall>& calls, hipStream_t s) {
       g.alpha = p.alpha;       // one configuration per group (instances of one net share it)
       g.epsilon = p.epsilon;
     }
-    const int tiles = (n_max + 31) / 32;
+    const int np_max = (n_max + kInitPair - 1) / kInitPair * kInitPair;
+    const int tiles = np_max / 32;
     hipLaunchKernelGGL(init_gram_kernel, dim3(tiles, tiles, n), dim3(256), 0, s, g);
     LAUNCH_CHECK();
-    const int m_max = (n_max + 1) & ~1;
-    const int rounds = kInitSweeps * (m_max - 1);
-    const long long work = (long long)(m_max / 2) * (m_max / 2) + (long long)n_max * (m_max / 2);
-    int blocks = (int)std::min<long long>((work + 255) / 256, 4096);
-    if (blocks < 1) blocks = 1;
-    int src = 0;
-    for (int r = 0; r < rounds; ++r) {
-      hipLaunchKernelGGL(init_jacobi_round_kernel, dim3(blocks, 1, n), dim3(256), 0, s, g, r, src);
-      src ^= 1;
+    hipLaunchKernelGGL(init_scale_kernel, dim3(n), dim3(256), 0, s, g);
+    LAUNCH_CHECK();
+    // block Jacobi: every instance runs its own sweeps of (blocks - 1) rounds inside the common launches and
+    // drops out (its workgroups return at once) after a sweep without a significant rotation
+    const int pairs_max = np_max / kInitPair, rounds_per_sweep = 2 * pairs_max;   // inside round + round-robin
+    for (int r = 0; r < kInitMaxSweeps * rounds_per_sweep; ++r) {
+      hipLaunchKernelGGL(init_block_solve_kernel, dim3(pairs_max, n), dim3(1024), kInitSolveLds, s, g, r);
+      hipLaunchKernelGGL(init_block_apply_kernel, dim3(2 * pairs_max, pairs_max, n), dim3(256), 0, s, g, r, pairs_max);
     }
     LAUNCH_CHECK();
-    hipLaunchKernelGGL(init_select_kernel, dim3(n), dim3(1024), 0, s, g, src);
+    hipLaunchKernelGGL(init_select_kernel, dim3(n), dim3(1024), 0, s, g);
     LAUNCH_CHECK();
-    hipLaunchKernelGGL(init_rows_kernel, dim3((ldw_max + 63) / 64, r_max, n), dim3(256), 0, s, g, src);
+    hipLaunchKernelGGL(init_rows_kernel, dim3((ldw_max + 63) / 64, r_max, n), dim3(256), 0, s, g);
     LAUNCH_CHECK();
     hipLaunchKernelGGL(init_complete_kernel, dim3(n), dim3(1024), 0, s, g);
     LAUNCH_CHECK();
