@@ -337,11 +337,13 @@ def run_simple_bench(steps=60, warmup=5, calls=40):
                 paper_context="K20, seconds per outer iteration: plain SGD 88, online NG-SGD 93, simple NG-SGD 208")
 
 
-def run_replica_bench(replicas=8, rounds=2, steps_per_round=200):
-    """BASELINE configs[4] in small: `replicas` copies of the configs[1] network resident on the one GPU, each
+def run_replica_bench(replicas=8, rounds=4, steps_per_round=400):
+    """BASELINE configs[4]: `replicas` copies of the configs[1] network resident on the one GPU, each
     stepping on its own HIP stream over its own data shard, parameters averaged on the device between rounds
     (which also resets the preconditioners, as the paper's re-spawned jobs do).  A single step leaves much of the
-    chip idle (a few hundred tiles for 256 compute units); independent replicas fill it."""
+    chip idle (a few hundred tiles for 256 compute units); independent replicas fill it.  The labels of the
+    synthetic data are independent of the inputs, so a replica can only learn the prior and memorise its own
+    minibatches: the log-probabilities after averaging say nothing about the method."""
     import torch
 
     import paper_1410_7455_amd as ng
@@ -399,8 +401,8 @@ def run_replica_bench(replicas=8, rounds=2, steps_per_round=200):
         f"({rounds} x {steps_per_round} steps each), averaging {t_avg * 1e3 / rounds:.2f} ms, re-initialisation step "
         f"{t_reinit * 1e3 / rounds:.1f} ms, {overall:,.0f} frames/s overall; last mean log-probs "
         f"{min(last):.3f} .. {max(last):.3f}")
-    return dict(workload="configs[4] shape: replicas of configs[1] interleaved on HIP streams, on-device averaging "
-                         "with preconditioner reset between rounds",
+    return dict(workload="configs[4]: replicas of configs[1] interleaved on HIP streams, on-device averaging every "
+                         f"{steps_per_round} minibatches with preconditioner reset, {rounds} rounds",
                 replicas=replicas, rounds=rounds, steps_per_round=steps_per_round, value=steady, unit="frames/s",
                 ms_per_replica_step=t_steady * 1e3 / (replicas * rounds * steps_per_round),
                 averaging_ms=t_avg * 1e3 / rounds, reinitialisation_step_ms=t_reinit * 1e3 / rounds,
