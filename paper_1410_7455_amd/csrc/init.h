@@ -54,9 +54,17 @@ struct InitGroup {
   InitArgs a[kMaxInstances];
 };
 
+// The initialisation is some hundreds of small launches: the instance list is stored in device memory once and the
+// kernels take a pointer to it (a launch that carries the 3.6 KB list by value costs the host three times as much).
+__global__ void init_store_group_kernel(const InitGroup g, InitGroup* __restrict__ dst) {
+  const uint32_t* src = reinterpret_cast<const uint32_t*>(&g);
+  uint32_t* out = reinterpret_cast<uint32_t*>(dst);
+  for (int i = threadIdx.x; i < (int)(sizeof(InitGroup) / sizeof(uint32_t)); i += blockDim.x) out[i] = src[i];
+}
+
 // C = (1/N) X^T X (use_cov) or (1/N) X X^T, fp64 accumulation of fp32 data; V = I.  Grid (tiles, tiles, instance).
-__global__ __launch_bounds__(256) void init_gram_kernel(const InitGroup g) {
-  const InitArgs& a = g.a[blockIdx.z];
+__global__ __launch_bounds__(256) void init_gram_kernel(const InitGroup* __restrict__ gp) {
+  const InitArgs& a = gp->a[blockIdx.z];
   const int n = a.n, np = a.np;
   const int i0 = blockIdx.y * 32, j0 = blockIdx.x * 32;
   if (i0 >= np || j0 >= np) return;
@@ -110,8 +118,8 @@ __global__ __launch_bounds__(256) void init_gram_kernel(const InitGroup g) {
 }
 
 // Trace of the matrix (the scale of the convergence test) and cleared rotation counters.  One workgroup per instance.
-__global__ __launch_bounds__(256) void init_scale_kernel(const InitGroup g) {
-  const InitArgs& a = g.a[blockIdx.x];
+__global__ __launch_bounds__(256) void init_scale_kernel(const InitGroup* __restrict__ gp) {
+  const InitArgs& a = gp->a[blockIdx.x];
   __shared__ double scratch[16];
   double t = 0.0;
   for (int i = threadIdx.x; i < a.n; i += 256) t += a.A[(size_t)i * a.np + i];
@@ -174,8 +182,8 @@ __device__ __forceinline__ void init_inner_pair(bool inside, int ir, int k, int&
 // round's rotations (division-free); then thread t updates the 2 x 2 block (pair t / 32, pair t % 32) of the
 // sub-matrix and two rows of Q's column pair t % 32; both are double-buffered, two barriers per inner round.
 // Grid (pairs, count), 1024 threads, kInitSolveLds bytes of dynamic LDS.
-__global__ __launch_bounds__(1024) void init_block_solve_kernel(const InitGroup g, const int ground) {
-  const InitArgs& a = g.a[blockIdx.y];
+__global__ __launch_bounds__(1024) void init_block_solve_kernel(const InitGroup* __restrict__ gp, const int ground) {
+  const InitArgs& a = gp->a[blockIdx.y];
   const InitRound rd = init_round(a, ground);
   const int pair = blockIdx.x;
   // the counter of the next sweep is cleared whether or not this instance still iterates (nobody reads or adds to
@@ -260,8 +268,8 @@ __global__ __launch_bounds__(1024) void init_block_solve_kernel(const InitGroup 
 // V <- V Q on the tile (64 rows, workgroup y's blocks), in place (a tile depends on itself only).
 // Grid (pairs + row chunks, pairs, count), 256 threads: wavefront w owns the 32 x 32 quadrant (w / 2, w % 2).
 // v_mfma_f64_16x16x4_f64: lane l supplies A[l%16][l/16] and B[l/16][l%16]; register r holds row 4r + l/16, column l%16.
-__global__ __launch_bounds__(256) void init_block_apply_kernel(const InitGroup g, const int ground, const int pairs_max) {
-  const InitArgs& a = g.a[blockIdx.z];
+__global__ __launch_bounds__(256) void init_block_apply_kernel(const InitGroup* __restrict__ gp, const int ground, const int pairs_max) {
+  const InitArgs& a = gp->a[blockIdx.z];
   const InitRound rd = init_round(a, ground);
   const int pb = blockIdx.y;
   const bool is_v = (int)blockIdx.x >= pairs_max;
@@ -353,11 +361,11 @@ __global__ __launch_bounds__(256) void init_block_apply_kernel(const InitGroup g
 }
 
 // Top-R eigenvalues, rho_0, D_0, E_0 (App. B.3.2 with eq. beta2, etii).  One workgroup per instance.
-__global__ __launch_bounds__(1024) void init_select_kernel(const InitGroup g) {
+__global__ __launch_bounds__(1024) void init_select_kernel(const InitGroup* __restrict__ gp) {
   __shared__ double scratch[16];
   __shared__ double s_lam[kMaxRank];
   __shared__ int s_idx[kMaxRank];
-  const InitArgs& a = g.a[blockIdx.x];
+  const InitArgs& a = gp->a[blockIdx.x];
   const int n = a.n, R = a.R, D = a.D;
   const size_t lda = a.np;
   const double* A = a.A;
@@ -389,14 +397,14 @@ __global__ __launch_bounds__(1024) void init_select_kernel(const InitGroup g) {
       }
       sum_l += s_lam[k];
     }
-    const double rho0 = fmax((tr - sum_l) / (double)(D - R), g.epsilon);
+    const double rho0 = fmax((tr - sum_l) / (double)(D - R), gp->epsilon);
     double sum_d = 0.0;
     for (int k = 0; k < R; ++k) {
-      const double d = fmax(g.epsilon, s_lam[k] - rho0);
+      const double d = fmax(gp->epsilon, s_lam[k] - rho0);
       st->d[k] = d;
       sum_d += d;
     }
-    const double beta = rho0 * (1.0 + g.alpha) + g.alpha / (double)D * sum_d;
+    const double beta = rho0 * (1.0 + gp->alpha) + gp->alpha / (double)D * sum_d;
     for (int k = 0; k < R; ++k) st->e[k] = 1.0 / (beta / st->d[k] + 1.0);
     st->rho = rho0;
     st->beta = beta;
@@ -413,8 +421,8 @@ __global__ __launch_bounds__(1024) void init_select_kernel(const InitGroup g) {
 
 // W_0 rows of the kept eigenpairs: sqrt(e_i) v_i with v_i a column of V (covariance route) or
 // X_0^T u_i / sqrt(N lambda_i) (Gram route); zero for null directions.  Grid (col blocks of 64, R, instance).
-__global__ __launch_bounds__(256) void init_rows_kernel(const InitGroup g) {
-  const InitArgs& a = g.a[blockIdx.z];
+__global__ __launch_bounds__(256) void init_rows_kernel(const InitGroup* __restrict__ gp) {
+  const InitArgs& a = gp->a[blockIdx.z];
   const int i = blockIdx.y;
   if (i >= a.R) return;
   const int col = blockIdx.x * 64 + (threadIdx.x & 63);
@@ -453,12 +461,12 @@ __global__ __launch_bounds__(256) void init_rows_kernel(const InitGroup g) {
 // candidate orthogonalised twice against all rows fixed so far, accepted when its residual exceeds 0.1).
 // One workgroup per instance; returns at once when every direction was kept.  A pass takes all its inner
 // products against the same vector (every wavefront a share of the fixed rows) and then subtracts them together.
-__global__ __launch_bounds__(1024) void init_complete_kernel(const InitGroup g) {
+__global__ __launch_bounds__(1024) void init_complete_kernel(const InitGroup* __restrict__ gp) {
   __shared__ double scratch[16];
   __shared__ int s_fixed[kMaxRank];
   __shared__ double s_dot[kMaxRank], s_inv[kMaxRank];
   __shared__ int s_nfixed, s_missing;
-  const InitArgs& a = g.a[blockIdx.x];
+  const InitArgs& a = gp->a[blockIdx.x];
   const int R = a.R, D = a.D, ldw = a.ldw;
   const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63, wave = tid >> 6, nw = nt >> 6;
   if (tid == 0) {

@@ -137,6 +137,7 @@ struct ngsgd_precond {
   double* Qi = nullptr;
   double* init_stat = nullptr;
   int* init_cnt = nullptr;
+  InitGroup* init_group = nullptr;   // device copy of the instance list of an initialisation this instance leads
   int* idx = nullptr;
   double* vwork = nullptr;
   double2* rotlog = nullptr;      // Jacobi rotation log of the latest factor update
@@ -177,6 +178,7 @@ void precond_layout(ngsgd_precond& p, Carver& c) {
   p.Qi = c.take<double>(np_init / kInitPair * kInitPair * kInitPair);
   p.init_stat = c.take<double>(2);
   p.init_cnt = c.take<int>(4);
+  p.init_group = c.take<InitGroup>(1);
   p.idx = c.take<int>(kMaxRank);
   p.vwork = c.take<double>((size_t)kMaxRank + D);
   {
@@ -378,23 +380,27 @@ int run_init(const std::vector<PrecondCall>& calls, hipStream_t s) {
     }
     const int np_max = (n_max + kInitPair - 1) / kInitPair * kInitPair;
     const int tiles = np_max / 32;
-    hipLaunchKernelGGL(init_gram_kernel, dim3(tiles, tiles, n), dim3(256), 0, s, g);
+    InitGroup* gd = calls[done].p->init_group;
+    static_assert(sizeof(InitGroup) % sizeof(uint32_t) == 0, "copied word by word");
+    hipLaunchKernelGGL(init_store_group_kernel, dim3(1), dim3(256), 0, s, g, gd);
     LAUNCH_CHECK();
-    hipLaunchKernelGGL(init_scale_kernel, dim3(n), dim3(256), 0, s, g);
+    hipLaunchKernelGGL(init_gram_kernel, dim3(tiles, tiles, n), dim3(256), 0, s, gd);
     LAUNCH_CHECK();
-    // block Jacobi: every instance runs its own sweeps of (blocks - 1) rounds inside the common launches and
-    // drops out (its workgroups return at once) after a sweep without a significant rotation
+    hipLaunchKernelGGL(init_scale_kernel, dim3(n), dim3(256), 0, s, gd);
+    LAUNCH_CHECK();
+    // block Jacobi: every instance runs its own sweeps of (blocks) rounds inside the common launches and
+    // drops out (its workgroups return at once) after a sweep without a rotation
     const int pairs_max = np_max / kInitPair, rounds_per_sweep = 2 * pairs_max;   // inside round + round-robin
     for (int r = 0; r < kInitMaxSweeps * rounds_per_sweep; ++r) {
-      hipLaunchKernelGGL(init_block_solve_kernel, dim3(pairs_max, n), dim3(1024), kInitSolveLds, s, g, r);
-      hipLaunchKernelGGL(init_block_apply_kernel, dim3(2 * pairs_max, pairs_max, n), dim3(256), 0, s, g, r, pairs_max);
+      hipLaunchKernelGGL(init_block_solve_kernel, dim3(pairs_max, n), dim3(1024), kInitSolveLds, s, gd, r);
+      hipLaunchKernelGGL(init_block_apply_kernel, dim3(2 * pairs_max, pairs_max, n), dim3(256), 0, s, gd, r, pairs_max);
     }
     LAUNCH_CHECK();
-    hipLaunchKernelGGL(init_select_kernel, dim3(n), dim3(1024), 0, s, g);
+    hipLaunchKernelGGL(init_select_kernel, dim3(n), dim3(1024), 0, s, gd);
     LAUNCH_CHECK();
-    hipLaunchKernelGGL(init_rows_kernel, dim3((ldw_max + 63) / 64, r_max, n), dim3(256), 0, s, g);
+    hipLaunchKernelGGL(init_rows_kernel, dim3((ldw_max + 63) / 64, r_max, n), dim3(256), 0, s, gd);
     LAUNCH_CHECK();
-    hipLaunchKernelGGL(init_complete_kernel, dim3(n), dim3(1024), 0, s, g);
+    hipLaunchKernelGGL(init_complete_kernel, dim3(n), dim3(1024), 0, s, gd);
     LAUNCH_CHECK();
     done += n;
   }
