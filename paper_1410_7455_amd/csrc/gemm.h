@@ -357,6 +357,40 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmGroup g) 
   const int k_end = min(P.K, k_begin + P.k_per_split);
   const int M = P.M, N = P.N;
 
+  // accumulator layout: register r of lane l holds tile column l%16 and tile row 4*(l/16)+r for
+  // v_mfma_f32_16x16x4_f32, tile row 4*r+(l/16) for v_mfma_f64_16x16x4_f64; where a tile's rows and columns lie
+  // in the wavefront's part of C is the operand staging's business (interleaved for row-contiguous operands)
+  auto local_row = [&](const int i, const int r) {
+    return wm * WM + StageA::template tile_row<TM>(i, ACC64 ? 4 * r + g4 : 4 * g4 + r);
+  };
+  auto local_col = [&](const int j) { return wn * WN + StageB::template tile_row<TN>(j, r16); };
+  // C - acc: the old values of C do not depend on the product; they are requested before the K loop and arrive
+  // under it.  A lane that owns two adjacent columns (interleaved B, TN = 2) moves them as one 8-byte word.
+  constexpr bool SUB = EPI == EPI_SUB_ROWNORM;
+  constexpr bool SUB_V2 = SUB && !B_KC && TN == 2;
+  float c_old[SUB ? TM : 1][SUB ? 4 : 1][SUB ? TN : 1];
+  if (SUB) {
+    const float* C = static_cast<const float*>(P.C);
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int row = m0 + local_row(i, r);
+        const int col0 = n0 + local_col(0);
+        if (SUB_V2 && row < M && col0 + 1 < N) {
+          const float2 v = *reinterpret_cast<const float2*>(C + (size_t)row * P.ldc + col0);
+          c_old[i][r][0] = v.x;
+          c_old[i][r][TN - 1] = v.y;
+        } else {
+#pragma unroll
+          for (int j = 0; j < TN; ++j) {
+            const int col = n0 + local_col(j);
+            c_old[i][r][j] = (row < M && col < N) ? C[(size_t)row * P.ldc + col] : 0.f;
+          }
+        }
+      }
+  }
+
   float* const As = lds;                             // two buffers of StageA::LDS_FLOATS
   float* const Bs = lds + 2 * StageA::LDS_FLOATS;    // two buffers of StageB::LDS_FLOATS
 
@@ -481,13 +515,6 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmGroup g) 
   for (int i = 0; i < 3; ++i)
     if (P.alpha_dev[i] != nullptr) alpha *= (float)(*P.alpha_dev[i]);
 
-  // accumulator layout: register r of lane l holds tile column l%16 and tile row 4*(l/16)+r for
-  // v_mfma_f32_16x16x4_f32, tile row 4*r+(l/16) for v_mfma_f64_16x16x4_f64; where a tile's rows and columns lie
-  // in the wavefront's part of C is the operand staging's business (interleaved for row-contiguous operands)
-  auto local_row = [&](const int i, const int r) {
-    return wm * WM + StageA::template tile_row<TM>(i, ACC64 ? 4 * r + g4 : 4 * g4 + r);
-  };
-  auto local_col = [&](const int j) { return wn * WN + StageB::template tile_row<TN>(j, r16); };
   if (EPI == EPI_SUB_ROWNORM) {
     float* C = static_cast<float*>(P.C);
     float* rowsum = lds;  // [WGN][BM], operand tiles are no longer needed
@@ -498,14 +525,21 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmGroup g) 
         const int lrow = local_row(i, r);
         const int row = m0 + lrow;
         float sq = 0.f;
+        float v[TN];
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-          const int col = n0 + local_col(j);
-          if (row < M && col < N) {
-            float* c = C + (size_t)row * P.ldc + col;
-            const float v = *c - (float)acc[i][j][r];
-            *c = v;
-            sq += v * v;
+        for (int j = 0; j < TN; ++j) v[j] = c_old[SUB ? i : 0][SUB ? r : 0][SUB ? j : 0] - (float)acc[i][j][r];
+        const int col0 = n0 + local_col(0);
+        if (SUB_V2 && row < M && col0 + 1 < N) {
+          *reinterpret_cast<float2*>(C + (size_t)row * P.ldc + col0) = make_float2(v[0], v[TN - 1]);
+          sq = v[0] * v[0] + v[TN - 1] * v[TN - 1];
+        } else {
+#pragma unroll
+          for (int j = 0; j < TN; ++j) {
+            const int col = n0 + local_col(j);
+            if (row < M && col < N) {
+              C[(size_t)row * P.ldc + col] = v[j];
+              sq += v[j] * v[j];
+            }
           }
         }
         sq = group16_sum(sq);
