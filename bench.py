@@ -457,7 +457,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py measures one GPU: this build has no multi-GPU path (replicas only exchange parameters "
-            "at averaging points; see DESIGN.md).  Run with --gpus 1.")
+            "at averaging points).  Run with --gpus 1.")
         sys.exit(2)
     import torch
     if not torch.cuda.is_available():

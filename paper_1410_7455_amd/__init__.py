@@ -91,6 +91,12 @@ def load_library():
         raise ImportError(
             f"{LIB_PATH} is missing: build it with `python -m paper_1410_7455_amd.build` "
             "(hipcc, gfx950); there is no CPU fallback")
+    try:
+        # PyTorch ships its own HIP runtime: load it first, so that the library binds to the same copy as the
+        # tensors whose pointers it is given (two runtimes in one process do not know each other's memory)
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = ctypes.CDLL(LIB_PATH)
     for name, (restype, argtypes) in _SIGNATURES.items():
         fn = getattr(lib, name)          # AttributeError if the symbol is not exported

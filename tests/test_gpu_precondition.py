@@ -67,7 +67,7 @@ def upload_state(torch, pre, ora):
 
 
 @pytest.mark.parametrize("N,D,R,period", [(200, 301, 20, 1), (96, 1000, 80, 1), (333, 77, 5, 2), (130, 520, 90, 1),
-                                           (64, 41, 4, 1)])
+                                           (64, 41, 4, 1), (150, 400, 96, 1), (120, 333, 95, 1), (40, 9, 1, 1)])
 def test_from_shared_state_matches_oracle(ngsgd, N, D, R, period):
     """Oracle warms up, its state is uploaded, then both process the same matrices (apply and update paths)."""
     import torch
