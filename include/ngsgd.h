@@ -22,6 +22,12 @@
  *     return without waiting for it.  Scalars results are written to device
  *     memory.  Calls on the same handle must be issued in order on one stream.
  *     Handles are not thread-safe.
+ *   - A network also owns one internal stream (default priority): the factor
+ *     updates of its preconditioners run there, so that they overlap the rest
+ *     of the step and the following minibatch.  Every call on the handle
+ *     orders itself after whatever it depends on; a caller that wants the
+ *     stream it passed to cover all of a step's work (to time it, or to read
+ *     the handle's device memory directly) calls ngsgd_join first.
  *   - Every function returns NGSGD_OK (0) or a negative NGSGD_E* code.  After
  *     an error the handle's state is unchanged when the error is an argument
  *     error, and unspecified for NGSGD_EHIP.
@@ -164,6 +170,10 @@ int ngsgd_destroy(ngsgd_net* net);
  *   dev_logprob_sum (optional, 1 double) receives sum_i log p(y_i | x_i) evaluated before the update */
 int ngsgd_step(ngsgd_net* net, const float* dev_x, const int32_t* dev_labels, int32_t N, float lr,
                double* dev_logprob_sum, void* hip_stream);
+
+/* Makes hip_stream wait for what the network still has in flight on its internal stream (the latest
+ * factor updates); enqueues nothing else. */
+int ngsgd_join(ngsgd_net* net, void* hip_stream);
 
 /* Parameter averaging of Sec. 3.1: every replica's weights are replaced by the arithmetic mean over
  * the n replicas (same configuration, same device).  With reset_preconditioners != 0 all their

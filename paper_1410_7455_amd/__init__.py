@@ -65,6 +65,7 @@ _SIGNATURES = {
     "ngsgd_create": (c_int, [POINTER(ngsgd_config), c_void_p, c_size_t, POINTER(c_void_p)]),
     "ngsgd_destroy": (c_int, [c_void_p]),
     "ngsgd_step": (c_int, [c_void_p, c_void_p, c_void_p, c_int32, c_float, c_void_p, c_void_p]),
+    "ngsgd_join": (c_int, [c_void_p, c_void_p]),
     "ngsgd_average": (c_int, [POINTER(c_void_p), c_int32, c_int32, c_void_p]),
     "ngsgd_get_params": (c_int, [c_void_p, c_int32, c_void_p, c_void_p]),
     "ngsgd_set_params": (c_int, [c_void_p, c_int32, c_void_p, c_void_p]),
@@ -276,6 +277,10 @@ class Network:
         _check(self.lib.ngsgd_step(self.handle, _ptr(x), _ptr(labels), x.shape[0], float(lr), _ptr(out),
                                    _stream_ptr(stream)), "ngsgd_step")
         return out
+
+    def join(self, stream=None):
+        """Makes the stream wait for the factor updates the network has in flight on its internal stream."""
+        _check(self.lib.ngsgd_join(self.handle, _stream_ptr(stream)), "ngsgd_join")
 
     def precond(self, layer, side):
         h = c_void_p(0)

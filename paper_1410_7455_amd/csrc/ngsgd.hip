@@ -1442,6 +1442,12 @@ extern "C" int ngsgd_step(ngsgd_net* net, const float* dev_x, const int32_t* dev
   return NGSGD_OK;
 }
 
+extern "C" int ngsgd_join(ngsgd_net* net, void* hip_stream) {
+  if (net == nullptr) return NGSGD_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  return join_side(&net->side, s);
+}
+
 extern "C" int ngsgd_average(ngsgd_net* const* nets, int32_t n, int32_t reset_preconditioners, void* hip_stream) {
   if (nets == nullptr || n < 1 || n > kMaxReplicas) return NGSGD_EINVAL;
   for (int i = 0; i < n; ++i) {

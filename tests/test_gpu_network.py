@@ -213,3 +213,31 @@ def test_average_replicas(ngsgd):
         assert abs(float(out.item()) - obj_o) / len(y) < 1e-3
         for l in range(spec.n_layers):
             assert rel(gpu.last_gradient(l).cpu().numpy(), ora.last["delta"][l]) < TOL
+
+
+def test_back_to_back_steps_equal_synchronised_steps(ngsgd):
+    """The factor updates of a step overlap the following steps on an internal stream: steps enqueued back to back
+    must give what steps separated by a device synchronisation give.
+    (Both are GPU runs; sums over split products use atomics, so they agree to rounding, not bit for bit.)"""
+    import torch
+    spec = workloads.small_pnorm()
+    batches = [workloads.minibatch(spec, t) for t in range(14)]
+    batches = [(torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda()) for x, y in batches]
+    finals = []
+    for synchronise in (False, True):
+        _, gpu = make_pair(ngsgd, spec, renorm=True, max_change=0.075)
+        out = torch.zeros(1, dtype=torch.float64, device="cuda")
+        objs = []
+        for t, (x, y) in enumerate(batches):
+            gpu.step(x, y, spec.lr, out)
+            if synchronise:
+                torch.cuda.synchronize()
+            objs.append(out.clone())
+        gpu.join()                                   # the caller's stream now covers the last factor updates too
+        torch.cuda.current_stream().synchronize()
+        finals.append(([gpu.get_params(l).cpu().numpy() for l in range(spec.n_layers)],
+                       np.array([float(o.item()) for o in objs])))
+    (w_free, o_free), (w_sync, o_sync) = finals
+    np.testing.assert_allclose(o_free, o_sync, rtol=1e-5)
+    for a, b in zip(w_free, w_sync):
+        assert rel(a, b) < 1e-5
