@@ -220,8 +220,6 @@ int ensure_kernel_attributes() {
                               hipFuncAttributeMaxDynamicSharedMemorySize, max_dyn));
   HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(orth_fix_kernel),
                               hipFuncAttributeMaxDynamicSharedMemorySize, max_dyn));
-  HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(orth_apply_kernel),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, max_dyn));
   HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(init_block_solve_kernel),
                               hipFuncAttributeMaxDynamicSharedMemorySize, kInitSolveLds));
   g_attr_done = true;
@@ -675,12 +673,12 @@ int precond_factor_update(std::vector<PrecondCall>& to_update, hipStream_t s, Si
         a.sumsq_part = p.sumsq_part;
         a.n_sumsq = p.n_sumsq;
         OrthArgs& o = og.a[n];
-        o.st = p.st; o.G = p.K; o.W = p.W; o.ld = p.ldw; o.R = p.rank; o.D = p.dim;
+        o.st = p.st; o.G = p.K; o.At = p.At; o.ldat = p.ldh; o.R = p.rank;
         r_max = std::max(r_max, p.rank);
         ++n;
       }
       g.count = og.count = n;
-      const size_t dyn = (size_t)r_max * (r_max | 1) * sizeof(double);
+      const size_t dyn = (size_t)2 * r_max * (r_max | 1) * sizeof(double);   // the factor L and its inverse
       {
         ProfScope prof(NGSGD_PROF_PRECOND_SMALL, s);
         {
@@ -705,24 +703,32 @@ int precond_factor_update(std::vector<PrecondCall>& to_update, hipStream_t s, Si
       }
       // W_{t+1} = A_t B_t   (eq. wt1), once nothing reads W_t any more
       if (on_side) HIP_TRY(hipStreamWaitEvent(side->stream, side->outputs_done, 0));
-      for (int rc : {32, 80, 96}) {
-        std::vector<GemmDesc> d;
-        for (int i = 0; i < n; ++i) {
-          ngsgd_precond& p = *to_update[done + i].p;
-          if (p.ldh != rc) continue;
-          GemmDesc w;
-          w.A = p.At; w.lda = p.ldh;
-          w.B = p.J; w.ldb = p.ldw;
-          w.C = p.W; w.ldc = p.ldw;
-          w.M = p.rank; w.N = p.dim; w.K = p.rank;
-          d.push_back(w);
+      auto launch_new_factor = [&](const bool only_if_reorthogonalised) -> int {
+        for (int rc : {32, 80, 96}) {
+          std::vector<GemmDesc> d;
+          for (int i = 0; i < n; ++i) {
+            ngsgd_precond& p = *to_update[done + i].p;
+            if (p.ldh != rc) continue;
+            GemmDesc w;
+            w.A = p.At; w.lda = p.ldh;
+            w.B = p.J; w.ldb = p.ldw;
+            w.C = p.W; w.ldc = p.ldw;
+            w.M = p.rank; w.N = p.dim; w.K = p.rank;
+            if (only_if_reorthogonalised) {
+              w.gate = &p.st->flags;
+              w.gate_mask = kFlagReorth;
+            }
+            d.push_back(w);
+          }
+          if (d.empty()) continue;
+          ProfScope prof(only_if_reorthogonalised ? NGSGD_PROF_PRECOND_MISC : NGSGD_PROF_PRECOND_WNEW, s);
+          HIP_TRY(by_rank_class(rc, [&] { return launch_wnew<32>(d.data(), (int)d.size(), s); },
+                                [&] { return launch_wnew<80>(d.data(), (int)d.size(), s); },
+                                [&] { return launch_wnew<96>(d.data(), (int)d.size(), s); }));
         }
-        if (d.empty()) continue;
-        ProfScope prof(NGSGD_PROF_PRECOND_WNEW, s);
-        HIP_TRY(by_rank_class(rc, [&] { return launch_wnew<32>(d.data(), (int)d.size(), s); },
-                              [&] { return launch_wnew<80>(d.data(), (int)d.size(), s); },
-                              [&] { return launch_wnew<96>(d.data(), (int)d.size(), s); }));
-      }
+        return NGSGD_OK;
+      };
+      NG_TRY(launch_new_factor(false));
       {
         // App. B.3.1: W W^T of the new factor, accumulated into K (cleared by the R x R kernel) only for the
         // instances whose update asked for the check, then the check itself and, if needed, the Cholesky fix
@@ -745,13 +751,9 @@ int precond_factor_update(std::vector<PrecondCall>& to_update, hipStream_t s, Si
                                                                                                (int)dg.size(), s)));
         hipLaunchKernelGGL(orth_fix_kernel, dim3(n), dim3(kSmallThreads), dyn, s, og);
         LAUNCH_CHECK();
-        int d_max = 0;
-        for (int i = 0; i < n; ++i) d_max = std::max(d_max, to_update[done + i].p->dim);
-        const size_t apply_dyn = ((size_t)r_max * r_max + (size_t)r_max * kOrthApplyThreads) * sizeof(double);
-        hipLaunchKernelGGL(orth_apply_kernel, dim3((d_max + kOrthApplyThreads - 1) / kOrthApplyThreads, n),
-                           dim3(kOrthApplyThreads), apply_dyn, s, og);
-        LAUNCH_CHECK();
       }
+      // where the check failed the kernel has folded the fix into A_t: W_{t+1} = A_t B_t once more for those
+      NG_TRY(launch_new_factor(true));
       done += n;
     }
     if (on_side) {

@@ -530,11 +530,10 @@ __global__ __launch_bounds__(kEigvecThreads) void eigvec_kernel(const SmallGroup
 // 1e-3, W <- E^{1/2} L^{-1} E^{-1/2} W with O = L L^T.  Runs only when the update asked for the check.
 struct OrthArgs {
   PrecondScalars* st;
-  double* G;         // R x R, W W^T of the new factor (accumulated only when the check was requested); on return
-                     // the Cholesky factor L when the fix is needed
-  float* W;
-  int ld;
-  int R, D;
+  const double* G;   // R x R, W W^T of the new factor (accumulated only when the check was requested)
+  float* At;         // R x R (ldat): A_t on entry; when the fix is needed, E^{1/2} L^{-1} E^{-1/2} A_t on return
+  int ldat;
+  int R;
 };
 struct OrthGroup {
   int count;
@@ -550,7 +549,7 @@ __global__ __launch_bounds__(kSmallThreads) void orth_fix_kernel(const OrthGroup
   const int R = a.R;
   const int tid = threadIdx.x, nt = blockDim.x;
   const int Rs = R | 1;
-  double* O = dyn;                    // R x Rs, becomes L
+  double* O = dyn;                    // R x Rs, becomes L, later holds A_t
 
   double dev = 0.0;
   for (int idx = tid; idx < R * R; idx += nt) {
@@ -582,45 +581,38 @@ __global__ __launch_bounds__(kSmallThreads) void orth_fix_kernel(const OrthGroup
     }
     __syncthreads();
   }
-  // hand L to the kernel that applies the fix; G is not needed any more
-  for (int idx = tid; idx < R * R; idx += nt) a.G[idx] = idx % R <= idx / R ? O[(idx / R) * Rs + idx % R] : 0.0;
-  if (tid == 0) st->flags = (st->flags & ~kFlagOrthCheck) | kFlagReorth;
-}
-
-// W <- E^{1/2} L^{-1} E^{-1/2} W for the instances whose check asked for it (kFlagReorth), L as left in G by
-// orth_fix_kernel: every column of W is one forward substitution.  Grid (column blocks, instance), one column
-// per thread, L and the columns staged through LDS.
-constexpr int kOrthApplyThreads = 64;
-__global__ __launch_bounds__(kOrthApplyThreads) void orth_apply_kernel(const OrthGroup g) {
-  extern __shared__ __attribute__((aligned(16))) double dyn[];
-  const OrthArgs& a = g.a[blockIdx.y];
-  if (!(a.st->flags & kFlagReorth)) return;   // uniform over the workgroup
-  const int R = a.R, D = a.D, ld = a.ld;
-  const int c0 = blockIdx.x * kOrthApplyThreads;
-  if (c0 >= D) return;
-  const int tid = threadIdx.x;
-  double* L = dyn;                          // R x R
-  double* Y = dyn + (size_t)R * R;          // R x kOrthApplyThreads: E^{-1/2} W on entry, the solution on exit
-  for (int idx = tid; idx < R * R; idx += kOrthApplyThreads) L[idx] = a.G[idx];
-  const int c = c0 + tid;
-  for (int k = 0; k < R; ++k)
-    Y[k * kOrthApplyThreads + tid] = c < D ? (double)a.W[(size_t)k * ld + c] / sqrt(a.st->e[k]) : 0.0;
+  // The fix W <- E^{1/2} L^{-1} E^{-1/2} W is applied to the factor it came from: W = A_t B_t, so the triangular
+  // mixing matrix goes into A_t and the product with B_t (still in its buffer) is simply launched again, gated on
+  // the flag set below.  L^{-1}: thread j solves column j by forward substitution (entries i >= j).
+  double* X = dyn + (size_t)R * Rs;   // R x Rs
+  for (int idx = tid; idx < R * Rs; idx += nt) X[idx] = 0.0;
   __syncthreads();
-  if (c >= D) return;
-  for (int i = 0; i < R; ++i) {
-    double s0 = Y[i * kOrthApplyThreads + tid], s1 = 0.0, s2 = 0.0, s3 = 0.0;
-    int k = 0;
-    for (; k + 4 <= i; k += 4) {
-      s0 -= L[i * R + k] * Y[k * kOrthApplyThreads + tid];
-      s1 -= L[i * R + k + 1] * Y[(k + 1) * kOrthApplyThreads + tid];
-      s2 -= L[i * R + k + 2] * Y[(k + 2) * kOrthApplyThreads + tid];
-      s3 -= L[i * R + k + 3] * Y[(k + 3) * kOrthApplyThreads + tid];
+  if (tid < R) {
+    const int j = tid;
+    for (int i = j; i < R; ++i) {
+      double s0 = i == j ? 1.0 : 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+      int k = j;
+      for (; k + 4 <= i; k += 4) {
+        s0 -= O[i * Rs + k] * X[k * Rs + j];
+        s1 -= O[i * Rs + k + 1] * X[(k + 1) * Rs + j];
+        s2 -= O[i * Rs + k + 2] * X[(k + 2) * Rs + j];
+        s3 -= O[i * Rs + k + 3] * X[(k + 3) * Rs + j];
+      }
+      for (; k < i; ++k) s0 -= O[i * Rs + k] * X[k * Rs + j];
+      X[i * Rs + j] = ((s0 + s1) + (s2 + s3)) / O[i * Rs + i];   // only this thread reads column j
     }
-    for (; k < i; ++k) s0 -= L[i * R + k] * Y[k * kOrthApplyThreads + tid];
-    const double y = ((s0 + s1) + (s2 + s3)) / L[i * R + i];
-    Y[i * kOrthApplyThreads + tid] = y;   // only this thread reads its column
-    a.W[(size_t)i * ld + c] = (float)(sqrt(a.st->e[i]) * y);
   }
+  __syncthreads();
+  // A_t into the space of L (no longer needed), then A_t <- (E^{1/2} L^{-1} E^{-1/2}) A_t
+  for (int idx = tid; idx < R * R; idx += nt) O[(idx / R) * Rs + idx % R] = (double)a.At[(idx / R) * a.ldat + idx % R];
+  __syncthreads();
+  for (int idx = tid; idx < R * R; idx += nt) {
+    const int i = idx / R, k = idx % R;
+    double acc = 0.0;
+    for (int j = 0; j <= i; ++j) acc += X[i * Rs + j] * rsqrt(st->e[j]) * O[j * Rs + k];
+    a.At[i * a.ldat + k] = (float)(sqrt(st->e[i]) * acc);
+  }
+  if (tid == 0) st->flags = (st->flags & ~kFlagOrthCheck) | kFlagReorth;
 }
 
 }  // namespace ngsgd
