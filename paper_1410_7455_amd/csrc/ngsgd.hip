@@ -99,11 +99,16 @@ inline int rank_class(int rank) { return rank <= 32 ? 32 : (rank <= 80 ? 80 : 96
 
 }  // namespace
 
-// The factor update of a network's instances runs on a second stream so that it overlaps the rest of the step
-// and the next step's forward / backward pass; the new factor is first needed by the next preconditioning.
+// The factor updates of a network's instances run on side streams so that they overlap the rest of the step and
+// the next step's forward / backward pass; the new factor is first needed by the next preconditioning.  The
+// instances are split over kSideStreams streams by the moment their matrix exists (the last layer's derivatives
+// and all layer inputs after the forward pass, the other derivatives as the backward pass produces them), so that
+// each group's products H, J and its R x R work start as early as possible.
+constexpr int kSideStreams = 3;
 struct SideSync {
   hipStream_t stream = nullptr;
-  hipEvent_t inputs_ready = nullptr;   // recorded on the caller's stream: H, J and the partial sums of tr(X X^T) are final
+  hipEvent_t inputs_ready = nullptr;   // recorded on the caller's stream: the group's matrices exist
+  hipEvent_t hj_done = nullptr;        // recorded on the side stream: H, J and the partial sums of tr(X X^T) are final
   hipEvent_t outputs_done = nullptr;   // recorded on the caller's stream: the last reader of W_t (Xhat) has been enqueued
   hipEvent_t done = nullptr;           // recorded on the side stream: W_{t+1}, D_{t+1}, rho_{t+1} are final
   bool pending = false;
@@ -444,45 +449,21 @@ int precond_validate(const std::vector<PrecondCall>& calls) {
   return NGSGD_OK;
 }
 
-// With `side`, two events are recorded on s for a factor update that runs on the side stream: inputs_ready once
-// H, J and the partial sums of tr(X X^T) are final, outputs_done once the last reader of W_t has been enqueued.
-int precond_apply(std::vector<PrecondCall>& calls, bool scale_output, hipStream_t s, SideSync* side,
-                  std::vector<PrecondCall>& to_update_out) {
-  const hipStream_t main_stream = s;
-  std::vector<PrecondCall> full, to_init, to_update;
-  for (auto& c : calls) {
-    ngsgd_precond& p = *c.p;
-    if (p.rank == 0) {
-      hipLaunchKernelGGL(rownorm_kernel, dim3((c.N + 3) / 4), dim3(256), 0, s, c.M, c.ld, c.N, p.dim, p.prow,
-                         c.rownorm2_out);
-      LAUNCH_CHECK();
-      if (c.gamma_out != nullptr) {
-        const uint32_t one_bits = 0x3f800000u;
-        hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(c.gamma_out),
-                           (size_t)1, one_bits);
-        LAUNCH_CHECK();
-      }
-      continue;
-    }
-    full.push_back(c);
-    if (p.t == 0) to_init.push_back(c);
-    if (p.t < p.always_update_first || p.t % p.update_period == 0) to_update.push_back(c);
-  }
-  if (!to_init.empty()) NG_TRY(run_init(to_init, s));
+inline bool factor_due(const ngsgd_precond& p) { return p.t < p.always_update_first || p.t % p.update_period == 0; }
 
-  // clear the accumulation buffers (H always; K, L when the factor is updated)
-  for (size_t done = 0; done < full.size();) {
+// Clears the accumulation buffers of the listed instances (H always; K, L when the factor is updated).
+int clear_accumulators(const std::vector<PrecondCall>& list, hipStream_t s) {
+  for (size_t done = 0; done < list.size();) {
     ProfScope prof(NGSGD_PROF_PRECOND_MISC, s);
     FillGroup fg;
-    const int n = (int)std::min<size_t>(kMaxInstances, full.size() - done);
+    const int n = (int)std::min<size_t>(kMaxInstances, list.size() - done);
     fg.count = n;
     size_t n_max = 0;
     for (int i = 0; i < n; ++i) {
-      const PrecondCall& c = full[done + i];
+      const PrecondCall& c = list[done + i];
       ngsgd_precond& p = *c.p;
-      const bool upd = p.t < p.always_update_first || p.t % p.update_period == 0;
       fg.ptr[i] = reinterpret_cast<uint32_t*>(p.zero_region);
-      fg.n[i] = upd ? p.zero_floats_all : (size_t)c.N * p.ldh;
+      fg.n[i] = factor_due(p) ? p.zero_floats_all : (size_t)c.N * p.ldh;
       n_max = std::max(n_max, fg.n[i]);
     }
     const unsigned blocks = (unsigned)std::min<size_t>((n_max + 2047) / 2048, 64);
@@ -490,13 +471,17 @@ int precond_apply(std::vector<PrecondCall>& calls, bool scale_output, hipStream_
     LAUNCH_CHECK();
     done += n;
   }
-  // H = X W^T   (eq. ht), tr(X X^T) partials
+  return NGSGD_OK;
+}
+
+// H = X W^T   (eq. ht) and the partial sums of tr(X X^T) for the listed instances, one launch per rank class.
+int launch_h_products(std::vector<PrecondCall>& list, hipStream_t s) {
   int class_count[3] = {0, 0, 0};   // instances per rank class (they share a launch)
-  for (auto& c : full) class_count[c.p->ldh == 32 ? 0 : (c.p->ldh == 80 ? 1 : 2)] += 1;
+  for (auto& c : list) class_count[c.p->ldh == 32 ? 0 : (c.p->ldh == 80 ? 1 : 2)] += 1;
   auto group_of = [&](const ngsgd_precond& p) { return class_count[p.ldh == 32 ? 0 : (p.ldh == 80 ? 1 : 2)]; };
   for (int rc : {32, 80, 96}) {
     std::vector<GemmDesc> d;
-    for (auto& c : full) {
+    for (auto& c : list) {
       ngsgd_precond& p = *c.p;
       if (p.ldh != rc) continue;
       GemmDesc g;
@@ -519,10 +504,14 @@ int precond_apply(std::vector<PrecondCall>& calls, bool scale_output, hipStream_
                           [&] { return launch_h<80>(d.data(), (int)d.size(), s); },
                           [&] { return launch_h<96>(d.data(), (int)d.size(), s); }));
   }
-  // J = H^T X   (must read X before it is overwritten by Xhat)
+  return NGSGD_OK;
+}
+
+// J = H^T X for the listed instances (must read X before it is overwritten by Xhat).
+int launch_j_products(std::vector<PrecondCall>& list, hipStream_t s) {
   for (int rc : {32, 80, 96}) {
     std::vector<GemmDesc> d;
-    for (auto& c : to_update) {
+    for (auto& c : list) {
       ngsgd_precond& p = *c.p;
       if (p.ldh != rc) continue;
       GemmDesc g;
@@ -537,6 +526,41 @@ int precond_apply(std::vector<PrecondCall>& calls, bool scale_output, hipStream_
     HIP_TRY(by_rank_class(rc, [&] { return launch_j<32>(d.data(), (int)d.size(), s); },
                           [&] { return launch_j<80>(d.data(), (int)d.size(), s); },
                           [&] { return launch_j<96>(d.data(), (int)d.size(), s); }));
+  }
+  return NGSGD_OK;
+}
+
+// With `side`, two events are recorded on s for a factor update that runs on the side stream: inputs_ready once
+// H, J and the partial sums of tr(X X^T) are final, outputs_done once the last reader of W_t has been enqueued.
+// With hj_ready the caller has already produced H and J of every instance (all due for an update, none at t = 0)
+// and ordered s behind them; only Xhat and gamma remain.
+int precond_apply(std::vector<PrecondCall>& calls, bool scale_output, hipStream_t s, SideSync* side,
+                  std::vector<PrecondCall>& to_update_out, bool hj_ready = false) {
+  const hipStream_t main_stream = s;
+  std::vector<PrecondCall> full, to_init, to_update;
+  for (auto& c : calls) {
+    ngsgd_precond& p = *c.p;
+    if (p.rank == 0) {
+      hipLaunchKernelGGL(rownorm_kernel, dim3((c.N + 3) / 4), dim3(256), 0, s, c.M, c.ld, c.N, p.dim, p.prow,
+                         c.rownorm2_out);
+      LAUNCH_CHECK();
+      if (c.gamma_out != nullptr) {
+        const uint32_t one_bits = 0x3f800000u;
+        hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, s, reinterpret_cast<uint32_t*>(c.gamma_out),
+                           (size_t)1, one_bits);
+        LAUNCH_CHECK();
+      }
+      continue;
+    }
+    full.push_back(c);
+    if (p.t == 0) to_init.push_back(c);
+    if (factor_due(p)) to_update.push_back(c);
+  }
+  if (!hj_ready) {
+    if (!to_init.empty()) NG_TRY(run_init(to_init, s));
+    NG_TRY(clear_accumulators(full, s));
+    NG_TRY(launch_h_products(full, s));
+    NG_TRY(launch_j_products(to_update, s));
   }
   // The factor update needs only H, J and the partial sums of tr(X X^T): with a side stream it starts here and
   // overlaps the rest of this call; it must not replace W_t before Xhat has read it (second event below).
@@ -596,16 +620,25 @@ int precond_apply(std::vector<PrecondCall>& calls, bool scale_output, hipStream_
   return NGSGD_OK;
 }
 
-// With `side` the work is enqueued on the side stream behind the two events of precond_apply; without it, on s.
-int precond_factor_update(std::vector<PrecondCall>& to_update, hipStream_t s, SideSync* side) {
-  if (to_update.empty()) return NGSGD_OK;
-  const bool on_side = side != nullptr;
-  if (on_side) {
-    HIP_TRY(hipStreamWaitEvent(side->stream, side->inputs_ready, 0));
-    s = side->stream;
+// Instances of one small-kernel launch share alpha / epsilon / S (instances of one net do): length of the run
+// of compatible instances that starts at `done`.
+int small_chunk(const std::vector<PrecondCall>& list, size_t done) {
+  const ngsgd_precond& p0 = *list[done].p;
+  int n = 0;
+  while (n < kMaxInstances && done + n < list.size()) {
+    const ngsgd_precond& p = *list[done + n].p;
+    if (p.alpha != p0.alpha || p.epsilon != p0.epsilon || p.num_samples_history != p0.num_samples_history) break;
+    ++n;
   }
+  return n;
+}
+
+// First half of the factor update (App. B.3): K, L, B_t, then Z_t, its eigen-decomposition, rho_{t+1}, D_{t+1}
+// and A_t.  Reads H, J and the partial sums of tr(X X^T); leaves W_t alone.
+int factor_begin(std::vector<PrecondCall>& to_update, hipStream_t s) {
+  if (to_update.empty()) return NGSGD_OK;
   {
-    // K = J J^T, L = H^T H   (App. B.3), fp64 accumulation across the splits
+    // K = J J^T, L = H^T H, fp64 accumulation across the splits
     std::vector<GemmDesc> dk, dl;
     for (auto& c : to_update) {
       ngsgd_precond& p = *c.p;
@@ -625,141 +658,162 @@ int precond_factor_update(std::vector<PrecondCall>& to_update, hipStream_t s, Si
       h.splits = choose_splits(tiles * (int)to_update.size(), (p.last_N + BK - 1) / BK);
       dl.push_back(h);
     }
+    ProfScope prof(NGSGD_PROF_PRECOND_KL, s);
+    HIP_TRY((launch_gemm_group<64, 64, BK, 2, 2, true, true, EPI_ATOMIC_F64, false, 0, true>(dk.data(),
+                                                                                           (int)dk.size(), s)));
+    HIP_TRY((launch_gemm_group<64, 64, BK, 2, 2, false, false, EPI_ATOMIC_F64, false, 0, true>(dl.data(),
+                                                                                             (int)dl.size(), s)));
+  }
+  // B_t over J (needs D_t, rho_t: before the R x R update)
+  for (size_t done = 0; done < to_update.size();) {
+    ProfScope prof(NGSGD_PROF_PRECOND_MISC, s);
+    BtGroup bg;
+    bg.num_samples_history = to_update[done].p->num_samples_history;
+    int n = 0, r_max = 0, d_max = 0;
+    while (n < kMaxInstances && done + n < to_update.size()) {
+      const PrecondCall& c = to_update[done + n];
+      ngsgd_precond& p = *c.p;
+      if (p.num_samples_history != bg.num_samples_history) break;
+      bg.a[n] = BtArgs{p.J, p.W, p.st, p.ldw, p.dim, p.rank, p.last_N};
+      r_max = std::max(r_max, p.rank);
+      d_max = std::max(d_max, p.dim);
+      ++n;
+    }
+    bg.count = n;
+    hipLaunchKernelGGL(make_bt_kernel, dim3((d_max + 1023) / 1024, r_max, n), dim3(256), 0, s, bg);
+    LAUNCH_CHECK();
+    done += n;
+  }
+  // Z_t, eigen-decomposition, rho_{t+1}, D_{t+1}, A_t
+  for (size_t done = 0; done < to_update.size();) {
+    SmallGroup g;
+    const ngsgd_precond& p0 = *to_update[done].p;
+    g.alpha = p0.alpha;
+    g.epsilon = p0.epsilon;
+    g.num_samples_history = p0.num_samples_history;
+    const int n = small_chunk(to_update, done);
+    int r_max = 0;
+    for (int i = 0; i < n; ++i) {
+      const ngsgd_precond& p = *to_update[done + i].p;
+      SmallArgs& a = g.a[i];
+      a.st = p.st; a.K = p.K; a.L = p.L; a.At = p.At; a.ldat = p.ldh;
+      a.R = p.rank; a.D = p.dim; a.N = p.last_N;
+      a.rotlog = p.rotlog; a.work = p.eigwork;
+      a.sumsq_part = p.sumsq_part;
+      a.n_sumsq = p.n_sumsq;
+      r_max = std::max(r_max, p.rank);
+    }
+    g.count = n;
+    ProfScope prof(NGSGD_PROF_PRECOND_SMALL, s);
     {
-      ProfScope prof(NGSGD_PROF_PRECOND_KL, s);
-      HIP_TRY((launch_gemm_group<64, 64, BK, 2, 2, true, true, EPI_ATOMIC_F64, false, 0, true>(dk.data(),
-                                                                                             (int)dk.size(), s)));
-      HIP_TRY((launch_gemm_group<64, 64, BK, 2, 2, false, false, EPI_ATOMIC_F64, false, 0, true>(dl.data(),
-                                                                                               (int)dl.size(), s)));
-    }
-    // B_t over J (needs D_t, rho_t: before the R x R update)
-    for (size_t done = 0; done < to_update.size();) {
-      ProfScope prof(NGSGD_PROF_PRECOND_MISC, s);
-      BtGroup bg;
-      bg.num_samples_history = to_update[done].p->num_samples_history;
-      int n = 0, r_max = 0, d_max = 0;
-      while (n < kMaxInstances && done + n < to_update.size()) {
-        const PrecondCall& c = to_update[done + n];
-        ngsgd_precond& p = *c.p;
-        if (p.num_samples_history != bg.num_samples_history) break;
-        bg.a[n] = BtArgs{p.J, p.W, p.st, p.ldw, p.dim, p.rank, p.last_N};
-        r_max = std::max(r_max, p.rank);
-        d_max = std::max(d_max, p.dim);
-        ++n;
+      const int m_max = (r_max + 1) & ~1;
+      const int n_blocks = (m_max / 2) * (m_max / 2 + 1) / 2;   // 2x2 blocks of the upper triangle
+      const size_t eig_dyn = (size_t)2 * 4 * n_blocks * sizeof(double);   // two copies of four planes
+      const int n_off = (m_max / 2) * (m_max / 2 - 1) / 2;   // off-diagonal blocks, owned by the waves after the first
+      const int items = std::max(1, (n_off + (kEigThreads - 64) - 1) / (kEigThreads - 64));
+      if (items <= 1) {
+        hipLaunchKernelGGL((eig_update_kernel<1, kEigThreads>), dim3(n), dim3(kEigThreads), eig_dyn, s, g);
+      } else if (items == 2) {
+        hipLaunchKernelGGL((eig_update_kernel<2, kEigThreads>), dim3(n), dim3(kEigThreads), eig_dyn, s, g);
+      } else {
+        hipLaunchKernelGGL((eig_update_kernel<kEigMaxItems, kEigThreads>), dim3(n), dim3(kEigThreads), eig_dyn, s, g);
       }
-      bg.count = n;
-      hipLaunchKernelGGL(make_bt_kernel, dim3((d_max + 1023) / 1024, r_max, n), dim3(256), 0, s, bg);
       LAUNCH_CHECK();
-      done += n;
     }
-    // Z_t, eigen-decomposition, rho_{t+1}, D_{t+1}, A_t
-    for (size_t done = 0; done < to_update.size();) {
-      // instances of one launch share alpha / epsilon / S (instances of one net do)
-      SmallGroup g;
-      OrthGroup og;
-      const ngsgd_precond& p0 = *to_update[done].p;
-      g.alpha = p0.alpha;
-      g.epsilon = p0.epsilon;
-      g.num_samples_history = p0.num_samples_history;
-      int n = 0, r_max = 0;
-      while (n < kMaxInstances && done + n < to_update.size()) {
-        const PrecondCall& c = to_update[done + n];
-        const ngsgd_precond& p = *c.p;
-        if (p.alpha != g.alpha || p.epsilon != g.epsilon || p.num_samples_history != g.num_samples_history) break;
-        SmallArgs& a = g.a[n];
-        a.st = p.st; a.K = p.K; a.L = p.L; a.At = p.At; a.ldat = p.ldh;
-        a.R = p.rank; a.D = p.dim; a.N = p.last_N;
-        a.rotlog = p.rotlog; a.work = p.eigwork;
-        a.sumsq_part = p.sumsq_part;
-        a.n_sumsq = p.n_sumsq;
-        OrthArgs& o = og.a[n];
-        o.st = p.st; o.G = p.K; o.At = p.At; o.ldat = p.ldh; o.R = p.rank;
-        r_max = std::max(r_max, p.rank);
-        ++n;
-      }
-      g.count = og.count = n;
-      const size_t dyn = (size_t)2 * r_max * (r_max | 1) * sizeof(double);   // the factor L and its inverse
-      {
-        ProfScope prof(NGSGD_PROF_PRECOND_SMALL, s);
-        {
-          const int m_max = (r_max + 1) & ~1;
-          const int n_blocks = (m_max / 2) * (m_max / 2 + 1) / 2;   // 2x2 blocks of the upper triangle
-          const size_t eig_dyn = (size_t)2 * 4 * n_blocks * sizeof(double);   // two copies of four planes
-          const int n_off = (m_max / 2) * (m_max / 2 - 1) / 2;   // off-diagonal blocks, owned by the waves after the first
-          const int items = std::max(1, (n_off + (kEigThreads - 64) - 1) / (kEigThreads - 64));
-          if (items <= 1) {
-            hipLaunchKernelGGL((eig_update_kernel<1, kEigThreads>), dim3(n), dim3(kEigThreads), eig_dyn, s, g);
-          } else if (items == 2) {
-            hipLaunchKernelGGL((eig_update_kernel<2, kEigThreads>), dim3(n), dim3(kEigThreads), eig_dyn, s, g);
-          } else {
-            hipLaunchKernelGGL((eig_update_kernel<kEigMaxItems, kEigThreads>), dim3(n), dim3(kEigThreads), eig_dyn, s, g);
-          }
-          LAUNCH_CHECK();
-        }
-        const int rows_per_block = kEigvecThreads / 64;
-        hipLaunchKernelGGL(eigvec_kernel, dim3(n, (r_max + rows_per_block - 1) / rows_per_block), dim3(kEigvecThreads),
-                           0, s, g);
-        LAUNCH_CHECK();
-      }
-      // W_{t+1} = A_t B_t   (eq. wt1), once nothing reads W_t any more
-      if (on_side) HIP_TRY(hipStreamWaitEvent(side->stream, side->outputs_done, 0));
-      auto launch_new_factor = [&](const bool only_if_reorthogonalised) -> int {
-        for (int rc : {32, 80, 96}) {
-          std::vector<GemmDesc> d;
-          for (int i = 0; i < n; ++i) {
-            ngsgd_precond& p = *to_update[done + i].p;
-            if (p.ldh != rc) continue;
-            GemmDesc w;
-            w.A = p.At; w.lda = p.ldh;
-            w.B = p.J; w.ldb = p.ldw;
-            w.C = p.W; w.ldc = p.ldw;
-            w.M = p.rank; w.N = p.dim; w.K = p.rank;
-            if (only_if_reorthogonalised) {
-              w.gate = &p.st->flags;
-              w.gate_mask = kFlagReorth;
-            }
-            d.push_back(w);
-          }
-          if (d.empty()) continue;
-          ProfScope prof(only_if_reorthogonalised ? NGSGD_PROF_PRECOND_MISC : NGSGD_PROF_PRECOND_WNEW, s);
-          HIP_TRY(by_rank_class(rc, [&] { return launch_wnew<32>(d.data(), (int)d.size(), s); },
-                                [&] { return launch_wnew<80>(d.data(), (int)d.size(), s); },
-                                [&] { return launch_wnew<96>(d.data(), (int)d.size(), s); }));
-        }
-        return NGSGD_OK;
-      };
-      NG_TRY(launch_new_factor(false));
-      {
-        // App. B.3.1: W W^T of the new factor, accumulated into K (cleared by the R x R kernel) only for the
-        // instances whose update asked for the check, then the check itself and, if needed, the Cholesky fix
-        ProfScope prof(NGSGD_PROF_PRECOND_MISC, s);
-        std::vector<GemmDesc> dg;
+    const int rows_per_block = kEigvecThreads / 64;
+    hipLaunchKernelGGL(eigvec_kernel, dim3(n, (r_max + rows_per_block - 1) / rows_per_block), dim3(kEigvecThreads),
+                       0, s, g);
+    LAUNCH_CHECK();
+    done += n;
+  }
+  return NGSGD_OK;
+}
+
+// Second half: W_{t+1} = A_t B_t (eq. wt1) and the orthogonality check of App. B.3.1.  Overwrites W_t, so the
+// caller orders it behind the last reader of W_t.
+int factor_finish(std::vector<PrecondCall>& to_update, hipStream_t s) {
+  for (size_t done = 0; done < to_update.size();) {
+    OrthGroup og;
+    const int n = small_chunk(to_update, done);
+    int r_max = 0;
+    for (int i = 0; i < n; ++i) {
+      const ngsgd_precond& p = *to_update[done + i].p;
+      OrthArgs& o = og.a[i];
+      o.st = p.st; o.G = p.K; o.At = p.At; o.ldat = p.ldh; o.R = p.rank;
+      r_max = std::max(r_max, p.rank);
+    }
+    og.count = n;
+    const size_t dyn = (size_t)2 * r_max * (r_max | 1) * sizeof(double);   // the factor L and its inverse
+    auto launch_new_factor = [&](const bool only_if_reorthogonalised) -> int {
+      for (int rc : {32, 80, 96}) {
+        std::vector<GemmDesc> d;
         for (int i = 0; i < n; ++i) {
           ngsgd_precond& p = *to_update[done + i].p;
+          if (p.ldh != rc) continue;
           GemmDesc w;
-          w.A = p.W; w.lda = p.ldw;
-          w.B = p.W; w.ldb = p.ldw;
-          w.C = p.K; w.ldc = p.rank;
-          w.M = p.rank; w.N = p.rank; w.K = p.dim;
-          const int tiles = ((p.rank + 63) / 64) * ((p.rank + 63) / 64);
-          w.splits = choose_splits(tiles * n, (p.dim + BK - 1) / BK);
-          w.gate = &p.st->flags;
-          w.gate_mask = kFlagOrthCheck;
-          dg.push_back(w);
+          w.A = p.At; w.lda = p.ldh;
+          w.B = p.J; w.ldb = p.ldw;
+          w.C = p.W; w.ldc = p.ldw;
+          w.M = p.rank; w.N = p.dim; w.K = p.rank;
+          if (only_if_reorthogonalised) {
+            w.gate = &p.st->flags;
+            w.gate_mask = kFlagReorth;
+          }
+          d.push_back(w);
         }
-        HIP_TRY((launch_gemm_group<64, 64, BK, 2, 2, true, true, EPI_ATOMIC_F64, false, 0, true>(dg.data(),
-                                                                                               (int)dg.size(), s)));
-        hipLaunchKernelGGL(orth_fix_kernel, dim3(n), dim3(kSmallThreads), dyn, s, og);
-        LAUNCH_CHECK();
+        if (d.empty()) continue;
+        ProfScope prof(only_if_reorthogonalised ? NGSGD_PROF_PRECOND_MISC : NGSGD_PROF_PRECOND_WNEW, s);
+        HIP_TRY(by_rank_class(rc, [&] { return launch_wnew<32>(d.data(), (int)d.size(), s); },
+                              [&] { return launch_wnew<80>(d.data(), (int)d.size(), s); },
+                              [&] { return launch_wnew<96>(d.data(), (int)d.size(), s); }));
       }
-      // where the check failed the kernel has folded the fix into A_t: W_{t+1} = A_t B_t once more for those
-      NG_TRY(launch_new_factor(true));
-      done += n;
+      return NGSGD_OK;
+    };
+    NG_TRY(launch_new_factor(false));
+    {
+      // App. B.3.1: W W^T of the new factor, accumulated into K (cleared by the R x R kernel) only for the
+      // instances whose update asked for the check, then the check itself and, if needed, the Cholesky fix
+      ProfScope prof(NGSGD_PROF_PRECOND_MISC, s);
+      std::vector<GemmDesc> dg;
+      for (int i = 0; i < n; ++i) {
+        ngsgd_precond& p = *to_update[done + i].p;
+        GemmDesc w;
+        w.A = p.W; w.lda = p.ldw;
+        w.B = p.W; w.ldb = p.ldw;
+        w.C = p.K; w.ldc = p.rank;
+        w.M = p.rank; w.N = p.rank; w.K = p.dim;
+        const int tiles = ((p.rank + 63) / 64) * ((p.rank + 63) / 64);
+        w.splits = choose_splits(tiles * n, (p.dim + BK - 1) / BK);
+        w.gate = &p.st->flags;
+        w.gate_mask = kFlagOrthCheck;
+        dg.push_back(w);
+      }
+      HIP_TRY((launch_gemm_group<64, 64, BK, 2, 2, true, true, EPI_ATOMIC_F64, false, 0, true>(dg.data(),
+                                                                                             (int)dg.size(), s)));
+      hipLaunchKernelGGL(orth_fix_kernel, dim3(n), dim3(kSmallThreads), dyn, s, og);
+      LAUNCH_CHECK();
     }
-    if (on_side) {
-      HIP_TRY(hipEventRecord(side->done, side->stream));
-      side->pending = true;
-    }
+    // where the check failed the kernel has folded the fix into A_t: W_{t+1} = A_t B_t once more for those
+    NG_TRY(launch_new_factor(true));
+    done += n;
+  }
+  return NGSGD_OK;
+}
+
+// With `side` the work is enqueued on the side stream behind the two events of precond_apply; without it, on s.
+int precond_factor_update(std::vector<PrecondCall>& to_update, hipStream_t s, SideSync* side) {
+  if (to_update.empty()) return NGSGD_OK;
+  const bool on_side = side != nullptr;
+  if (on_side) {
+    HIP_TRY(hipStreamWaitEvent(side->stream, side->inputs_ready, 0));
+    s = side->stream;
+  }
+  NG_TRY(factor_begin(to_update, s));
+  if (on_side) HIP_TRY(hipStreamWaitEvent(side->stream, side->outputs_done, 0));
+  NG_TRY(factor_finish(to_update, s));
+  if (on_side) {
+    HIP_TRY(hipEventRecord(side->done, side->stream));
+    side->pending = true;
   }
   return NGSGD_OK;
 }
@@ -1138,10 +1192,18 @@ struct ngsgd_net {
   double* logprob = nullptr;
   int last_N = 0;
   float last_lr = 0.f;
-  SideSync side;
+  SideSync side[kSideStreams];
 };
 
 namespace {
+
+// Side stream of the output-side instance of layer l: the last layer's derivatives exist after the log-softmax
+// (group 0, with all input sides); the others appear in descending layer order during the backward pass, two
+// layers per group, everything below in the last group.
+int output_side_group(int l, int n_layers) {
+  if (l == n_layers - 1) return 0;
+  return std::min(kSideStreams - 1, 1 + (n_layers - 2 - l) / 2);
+}
 
 int net_check_config(const ngsgd_config* cfg) {
   if (cfg == nullptr || cfg->dims == nullptr || cfg->n_layers < 1 || cfg->n_layers > NGSGD_MAX_LAYERS)
@@ -1225,7 +1287,8 @@ void net_layout(ngsgd_net& net, const ngsgd_config* cfg, Carver& c) {
     precond_configure(L.pout, L.dout, simple ? 0 : cfg->rank_out, cfg->max_batch, cfg->alpha,
                       cfg->num_samples_history, cfg->epsilon, cfg->update_period, cfg->always_update_first);
     L.pin.owned_by_net = L.pout.owned_by_net = true;
-    L.pin.sync = L.pout.sync = &net.side;
+    L.pin.sync = &net.side[0];
+    L.pout.sync = &net.side[output_side_group((int)(&L - net.layers.data()), cfg->n_layers)];
     precond_layout(L.pin, c);
     precond_layout(L.pout, c);
     if (simple) {   // gamma and the row norms go where the online method leaves them (st->gamma, prow)
@@ -1289,10 +1352,13 @@ extern "C" int ngsgd_create(const ngsgd_config* cfg, void* dev_workspace, size_t
     if (e == hipSuccess) e = hipMemcpy(L.mc_scale, &one, sizeof(one), hipMemcpyHostToDevice);
   }
   // second stream for the factor updates: default priority, does not synchronise with the NULL stream
-  if (e == hipSuccess) e = hipStreamCreateWithFlags(&net->side.stream, hipStreamNonBlocking);
-  if (e == hipSuccess) e = hipEventCreateWithFlags(&net->side.inputs_ready, hipEventDisableTiming);
-  if (e == hipSuccess) e = hipEventCreateWithFlags(&net->side.outputs_done, hipEventDisableTiming);
-  if (e == hipSuccess) e = hipEventCreateWithFlags(&net->side.done, hipEventDisableTiming);
+  for (SideSync& sd : net->side) {
+    if (e == hipSuccess) e = hipStreamCreateWithFlags(&sd.stream, hipStreamNonBlocking);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&sd.inputs_ready, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&sd.hj_done, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&sd.outputs_done, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&sd.done, hipEventDisableTiming);
+  }
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e != hipSuccess) {
     g_last_hip_error = (int)e;
@@ -1305,13 +1371,14 @@ extern "C" int ngsgd_create(const ngsgd_config* cfg, void* dev_workspace, size_t
 
 extern "C" int ngsgd_destroy(ngsgd_net* net) {
   if (net == nullptr) return NGSGD_EINVAL;
-  if (net->side.stream != nullptr) {
-    (void)hipStreamSynchronize(net->side.stream);
-    (void)hipStreamDestroy(net->side.stream);
+  for (SideSync& sd : net->side) {
+    if (sd.stream != nullptr) {
+      (void)hipStreamSynchronize(sd.stream);
+      (void)hipStreamDestroy(sd.stream);
+    }
+    for (hipEvent_t ev : {sd.inputs_ready, sd.hj_done, sd.outputs_done, sd.done})
+      if (ev != nullptr) (void)hipEventDestroy(ev);
   }
-  if (net->side.inputs_ready != nullptr) (void)hipEventDestroy(net->side.inputs_ready);
-  if (net->side.outputs_done != nullptr) (void)hipEventDestroy(net->side.outputs_done);
-  if (net->side.done != nullptr) (void)hipEventDestroy(net->side.done);
   delete net;
   return NGSGD_OK;
 }
@@ -1367,6 +1434,36 @@ extern "C" int ngsgd_step(ngsgd_net* net, const float* dev_x, const int32_t* dev
   LAUNCH_CHECK();
   }
 
+  // On a step whose factors are all due for an update (and none needs initialising) the products H, J and the
+  // R x R work of each group of instances start on the group's side stream as soon as the group's matrices
+  // exist, next to the backward pass; W_t is replaced only after Xhat has read it (early_finish below).
+  bool early = net->method == NGSGD_METHOD_ONLINE;
+  for (auto& L : Ls)
+    for (const ngsgd_precond* p : {&L.pin, &L.pout})
+      if (p->rank > 0 && (p->t == 0 || !factor_due(*p))) early = false;
+  std::vector<PrecondCall> early_calls[kSideStreams];
+  if (early) {
+    NG_TRY(ensure_kernel_attributes());
+    for (int l = 0; l < nl; ++l) {
+      ngsgd_layer& L = Ls[l];
+      if (L.pout.rank > 0)
+        early_calls[output_side_group(l, nl)].push_back(PrecondCall{&L.pout, L.A, L.lda, N, nullptr, nullptr});
+      if (L.pin.rank > 0) early_calls[0].push_back(PrecondCall{&L.pin, L.Xin, L.ldx, N, nullptr, nullptr});
+    }
+  }
+  auto early_start = [&](const int k) -> int {
+    if (!early || early_calls[k].empty()) return NGSGD_OK;
+    SideSync& sd = net->side[k];
+    HIP_TRY(hipEventRecord(sd.inputs_ready, s));
+    HIP_TRY(hipStreamWaitEvent(sd.stream, sd.inputs_ready, 0));
+    NG_TRY(clear_accumulators(early_calls[k], sd.stream));
+    NG_TRY(launch_h_products(early_calls[k], sd.stream));
+    NG_TRY(launch_j_products(early_calls[k], sd.stream));
+    HIP_TRY(hipEventRecord(sd.hj_done, sd.stream));
+    return factor_begin(early_calls[k], sd.stream);
+  };
+  NG_TRY(early_start(0));
+
   // backward on the unmodified derivatives (App. C.3, last paragraph)
   for (int l = nl - 1; l >= 1; --l) {
     ngsgd_layer& L = Ls[l];
@@ -1392,10 +1489,45 @@ extern "C" int ngsgd_step(ngsgd_net* net, const float* dev_x, const int32_t* dev
                          L.Xin, L.ldx, P.sigma, P.A, P.lda, N, P.groups, net->pnorm_group, net->renorm);
     }
     LAUNCH_CHECK();
+    // the derivatives of layer l - 1 exist now: start their group once its lowest layer is there
+    const int k = output_side_group(l - 1, nl);
+    if (l - 1 == 0 || output_side_group(l - 2, nl) != k) {
+      NG_TRY(early_start(k));
+    }
   }
 
-  // natural gradient: both matrices of every layer (Sec. 4.6; 2I instances), one grouped call; the factor updates
-  // overlap the rest of this step and the next step's forward and backward passes on the side stream
+  // maximum parameter change (App. C.3), then W_l += lr a_l gamma_o gamma_x Ohat_l^T Xhat_l  (Sec. 4.6) for the
+  // listed layers, once both of their matrices are preconditioned
+  auto update_layers = [&](const std::vector<int>& layers) -> int {
+    if (layers.empty()) return NGSGD_OK;
+    if (net->max_change_per_sample > 0.0) {
+      MaxChangeGroup g;
+      g.count = (int)layers.size();
+      g.lr = lr;
+      g.max_change_per_sample = net->max_change_per_sample;
+      for (size_t i = 0; i < layers.size(); ++i) {
+        ngsgd_layer& L = Ls[layers[i]];
+        MaxChangeArgs& a = g.a[i];
+        a.prow_o = L.pout.prow;
+        a.prow_x = L.pin.prow;
+        a.gamma_o = &L.pout.st->gamma;
+        a.gamma_x = &L.pin.st->gamma;
+        a.scale_out = L.mc_scale;
+        a.N = N;
+      }
+      ProfScope prof(NGSGD_PROF_ELEMENTWISE, s);
+      hipLaunchKernelGGL(max_change_kernel, dim3(g.count), dim3(256), 0, s, g);
+      LAUNCH_CHECK();
+    }
+    std::vector<GemmDesc> upd;
+    for (const int l : layers) upd.push_back(update_desc(Ls[l], N, lr, 1.f, Ls[l].W, Ls[l].ldw));
+    return launch_layer_gemms(GEMM_UPD, upd.data(), (int)upd.size(), s);
+  };
+  std::vector<int> all_layers;
+  for (int l = 0; l < nl; ++l) all_layers.push_back(l);
+
+  // natural gradient: both matrices of every layer (Sec. 4.6; 2I instances), grouped calls; the factor updates
+  // overlap the rest of this step and the next step's forward and backward passes on the side streams
   if (net->method == NGSGD_METHOD_SIMPLE) {
     // App. A instead: the factors come from the other rows of this minibatch, no state
     std::vector<SimpleCall> calls;
@@ -1406,39 +1538,56 @@ extern "C" int ngsgd_step(ngsgd_net* net, const float* dev_x, const int32_t* dev
                                  &L.pin.st->gamma, nullptr, nullptr});
     }
     NG_TRY(simple_many(calls, false, s));
-  } else {
+    NG_TRY(update_layers(all_layers));
+  } else if (early) {
     std::vector<PrecondCall> calls;
     for (auto& L : Ls) {
       calls.push_back(PrecondCall{&L.pout, L.A, L.lda, N, nullptr, nullptr});
       calls.push_back(PrecondCall{&L.pin, L.Xin, L.ldx, N, nullptr, nullptr});
     }
-    NG_TRY(precondition_many(calls, false, s, &net->side));
-  }
-
-  // maximum parameter change (App. C.3), then W_l += lr a_l gamma_o gamma_x Ohat_l^T Xhat_l  (Sec. 4.6)
-  {
-    MaxChangeGroup g;
-    g.count = nl;
-    g.lr = lr;
-    g.max_change_per_sample = net->max_change_per_sample;
+    // Xhat and gamma behind every group's H and J; the second half of each group's factor update is enqueued
+    // after the rest of this step so that the caller's stream is never short of work
+    for (int k = 0; k < kSideStreams; ++k)
+      if (!early_calls[k].empty()) HIP_TRY(hipStreamWaitEvent(s, net->side[k].hj_done, 0));
+    std::vector<PrecondCall> due;
+    NG_TRY(precond_apply(calls, false, s, nullptr, due, true));
+    for (int k = 0; k < kSideStreams; ++k)
+      if (!early_calls[k].empty()) HIP_TRY(hipEventRecord(net->side[k].outputs_done, s));
+    for (auto& c : calls) c.p->t += 1;
+    NG_TRY(update_layers(all_layers));
+    for (int k = 0; k < kSideStreams; ++k) {
+      if (early_calls[k].empty()) continue;
+      SideSync& sd = net->side[k];
+      HIP_TRY(hipStreamWaitEvent(sd.stream, sd.outputs_done, 0));
+      NG_TRY(factor_finish(early_calls[k], sd.stream));
+      HIP_TRY(hipEventRecord(sd.done, sd.stream));
+      sd.pending = true;
+    }
+  } else {
+    // No factor is due, or the first call of an instance (initialisation): everything on the caller's stream.
+    // On the step after an update the group that started last may still be running: the layers that do not
+    // depend on it are preconditioned and updated first, the others behind them.
+    SideSync* const last_side = &net->side[kSideStreams - 1];
+    std::vector<PrecondCall> calls[2];
+    std::vector<int> layers[2];
+    const bool split = last_side->pending;
     for (int l = 0; l < nl; ++l) {
-      MaxChangeArgs& a = g.a[l];
-      a.prow_o = Ls[l].pout.prow;
-      a.prow_x = Ls[l].pin.prow;
-      a.gamma_o = &Ls[l].pout.st->gamma;
-      a.gamma_x = &Ls[l].pin.st->gamma;
-      a.scale_out = Ls[l].mc_scale;
-      a.N = N;
+      ngsgd_layer& L = Ls[l];
+      const int late = split && L.pout.sync == last_side ? 1 : 0;
+      calls[late].push_back(PrecondCall{&L.pout, L.A, L.lda, N, nullptr, nullptr});
+      calls[0].push_back(PrecondCall{&L.pin, L.Xin, L.ldx, N, nullptr, nullptr});
+      layers[late].push_back(l);
     }
-    if (net->max_change_per_sample > 0.0) {
-      ProfScope prof(NGSGD_PROF_ELEMENTWISE, s);
-      hipLaunchKernelGGL(max_change_kernel, dim3(nl), dim3(256), 0, s, g);
-      LAUNCH_CHECK();
+    for (int k = 0; k + 1 < kSideStreams; ++k) NG_TRY(join_side(&net->side[k], s));
+    if (!split) NG_TRY(join_side(last_side, s));
+    NG_TRY(precondition_many(calls[0], false, s, nullptr));
+    NG_TRY(update_layers(layers[0]));
+    if (split) {
+      NG_TRY(join_side(last_side, s));
+      if (!calls[1].empty()) NG_TRY(precondition_many(calls[1], false, s, nullptr));
+      NG_TRY(update_layers(layers[1]));
     }
   }
-  std::vector<GemmDesc> upd;
-  for (auto& L : Ls) upd.push_back(update_desc(L, N, lr, 1.f, L.W, L.ldw));
-  NG_TRY(launch_layer_gemms(GEMM_UPD, upd.data(), (int)upd.size(), s));
   net->last_N = N;
   net->last_lr = lr;
   return NGSGD_OK;
@@ -1447,7 +1596,8 @@ extern "C" int ngsgd_step(ngsgd_net* net, const float* dev_x, const int32_t* dev
 extern "C" int ngsgd_join(ngsgd_net* net, void* hip_stream) {
   if (net == nullptr) return NGSGD_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  return join_side(&net->side, s);
+  for (SideSync& sd : net->side) NG_TRY(join_side(&sd, s));
+  return NGSGD_OK;
 }
 
 extern "C" int ngsgd_average(ngsgd_net* const* nets, int32_t n, int32_t reset_preconditioners, void* hip_stream) {
@@ -1460,7 +1610,8 @@ extern "C" int ngsgd_average(ngsgd_net* const* nets, int32_t n, int32_t reset_pr
       if (nets[i]->layers[l].dout != nets[0]->layers[l].dout || nets[i]->layers[l].din != nets[0]->layers[l].din)
         return NGSGD_EINVAL;
   }
-  for (int i = 0; i < n; ++i) NG_TRY(join_side(&nets[i]->side, static_cast<hipStream_t>(hip_stream)));
+  for (int i = 0; i < n; ++i)
+    for (SideSync& sd : nets[i]->side) NG_TRY(join_side(&sd, static_cast<hipStream_t>(hip_stream)));
   AverageArgs a;
   a.n = n;
   a.count = nets[0]->n_params_padded;

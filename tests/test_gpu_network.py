@@ -134,6 +134,16 @@ def test_small_pnorm_net_plain(ngsgd):
     run_and_compare(ngsgd, spec, ora, gpu, 2, rows=spec.minibatch - 9)
 
 
+def test_small_pnorm_net_past_the_always_update_phase(ngsgd):
+    """Sixteen steps without any synchronisation of state: steps 10, 11 only apply the factors, step 12 is the first
+    periodic update and step 13 is the step that follows one, which the library orders around the factor updates
+    still in flight (the layers whose factors are ready are preconditioned and updated first)."""
+    spec = workloads.small_pnorm()
+    ora, gpu = make_pair(ngsgd, spec, renorm=True, max_change=0.075)
+    worst = run_and_compare(ngsgd, spec, ora, gpu, 16)
+    print("small p-norm net, 16 steps free running", worst)
+
+
 def test_rank_zero_is_plain_sgd(ngsgd):
     spec = workloads.c0_tiny()
     spec.rank_in = spec.rank_out = 0
