@@ -356,7 +356,7 @@ def run_replica_bench(replicas=8, rounds=4, steps_per_round=400):
     for r in range(replicas):
         net = ng.Network(spec.dims, spec.nonlin, n, spec.pnorm_group, spec.rank_in, spec.rank_out, spec.alpha,
                          spec.num_samples_history, spec.epsilon, spec.update_period, renorm=True,
-                         max_change_per_sample=0.075)
+                         max_change_per_sample=0.075, side_streams=1)   # many networks on one GPU: one stream each
         for l, w in enumerate(weights):
             net.set_params(l, torch.from_numpy(w).cuda())
         nets.append(net)

@@ -44,6 +44,7 @@ class ngsgd_config(ctypes.Structure):
         ("alpha", c_float), ("num_samples_history", c_float), ("epsilon", c_float),
         ("update_period", c_int32), ("always_update_first", c_int32), ("renorm", c_int32),
         ("max_change_per_sample", c_float), ("method", c_int32), ("simple_epsilon", c_float),
+        ("side_streams", c_int32),
     ]
 
 
@@ -217,7 +218,7 @@ class Network:
 
     def __init__(self, dims, nonlin, max_batch, pnorm_group=10, rank_in=20, rank_out=80, alpha=4.0,
                  num_samples_history=2000.0, epsilon=1e-10, update_period=4, always_update_first=10,
-                 renorm=False, max_change_per_sample=0.0, method="online", simple_epsilon=1e-20):
+                 renorm=False, max_change_per_sample=0.0, method="online", simple_epsilon=1e-20, side_streams=0):
         import torch
         self.lib = load_library()
         self.method = {"online": NGSGD_METHOD_ONLINE, "simple": NGSGD_METHOD_SIMPLE}[method]
@@ -237,7 +238,7 @@ class Network:
         self._nonlin_arr = (c_int32 * max(1, len(nonlin)))(*nonlin)
         cfg = ngsgd_config(self.n_layers, self._dims_arr, self._nonlin_arr, pnorm_group, max_batch, rank_in,
                            rank_out, alpha, num_samples_history, epsilon, update_period, always_update_first,
-                           1 if renorm else 0, max_change_per_sample, self.method, simple_epsilon)
+                           1 if renorm else 0, max_change_per_sample, self.method, simple_epsilon, side_streams)
         nbytes = c_size_t(0)
         _check(self.lib.ngsgd_workspace_bytes(byref(cfg), byref(nbytes)), "ngsgd_workspace_bytes")
         self.workspace_bytes = nbytes.value

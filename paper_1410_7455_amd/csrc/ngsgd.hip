@@ -1193,16 +1193,17 @@ struct ngsgd_net {
   int last_N = 0;
   float last_lr = 0.f;
   SideSync side[kSideStreams];
+  int n_side = kSideStreams;   // streams in use
 };
 
 namespace {
 
-// Side stream of the output-side instance of layer l: the last layer's derivatives exist after the log-softmax
-// (group 0, with all input sides); the others appear in descending layer order during the backward pass, two
-// layers per group, everything below in the last group.
-int output_side_group(int l, int n_layers) {
-  if (l == n_layers - 1) return 0;
-  return std::min(kSideStreams - 1, 1 + (n_layers - 2 - l) / 2);
+// Side stream of the output-side instance of layer l when n_side streams are in use: the last layer's derivatives
+// exist after the log-softmax (group 0, with all input sides); the others appear in descending layer order during
+// the backward pass, two layers per group, everything below in the last group.  With one stream there is one group.
+int output_side_group(int l, int n_layers, int n_side) {
+  if (n_side <= 1 || l == n_layers - 1) return 0;
+  return std::min(n_side - 1, 1 + (n_layers - 2 - l) / 2);
 }
 
 int net_check_config(const ngsgd_config* cfg) {
@@ -1214,6 +1215,7 @@ int net_check_config(const ngsgd_config* cfg) {
   if (!(cfg->max_change_per_sample >= 0.f)) return NGSGD_EINVAL;
   if (cfg->method != NGSGD_METHOD_ONLINE && cfg->method != NGSGD_METHOD_SIMPLE) return NGSGD_EINVAL;
   const bool simple = cfg->method == NGSGD_METHOD_SIMPLE;
+  if (cfg->side_streams < 0 || cfg->side_streams > kSideStreams) return NGSGD_EINVAL;
   if (simple && (cfg->max_batch < 2 || !(cfg->alpha > 0.f) || !(cfg->simple_epsilon > 0.f))) return NGSGD_EINVAL;
   int din = cfg->dims[0];
   for (int l = 0; l < cfg->n_layers; ++l) {
@@ -1247,6 +1249,7 @@ void net_layout(ngsgd_net& net, const ngsgd_config* cfg, Carver& c) {
   net.method = cfg->method;
   net.alpha = cfg->alpha;
   net.simple_epsilon = cfg->simple_epsilon;
+  net.n_side = cfg->side_streams > 0 ? cfg->side_streams : kSideStreams;
   const bool simple = cfg->method == NGSGD_METHOD_SIMPLE;
   net.layers.assign(cfg->n_layers, ngsgd_layer());
   int din = cfg->dims[0];
@@ -1288,7 +1291,7 @@ void net_layout(ngsgd_net& net, const ngsgd_config* cfg, Carver& c) {
                       cfg->num_samples_history, cfg->epsilon, cfg->update_period, cfg->always_update_first);
     L.pin.owned_by_net = L.pout.owned_by_net = true;
     L.pin.sync = &net.side[0];
-    L.pout.sync = &net.side[output_side_group((int)(&L - net.layers.data()), cfg->n_layers)];
+    L.pout.sync = &net.side[output_side_group((int)(&L - net.layers.data()), cfg->n_layers, net.n_side)];
     precond_layout(L.pin, c);
     precond_layout(L.pout, c);
     if (simple) {   // gamma and the row norms go where the online method leaves them (st->gamma, prow)
@@ -1442,12 +1445,15 @@ extern "C" int ngsgd_step(ngsgd_net* net, const float* dev_x, const int32_t* dev
     for (const ngsgd_precond* p : {&L.pin, &L.pout})
       if (p->rank > 0 && (p->t == 0 || !factor_due(*p))) early = false;
   std::vector<PrecondCall> early_calls[kSideStreams];
+  int ready_layer[kSideStreams];   // a group starts once the derivatives of this layer (its lowest) exist
+  for (int& r : ready_layer) r = nl - 1;
   if (early) {
     NG_TRY(ensure_kernel_attributes());
     for (int l = 0; l < nl; ++l) {
       ngsgd_layer& L = Ls[l];
-      if (L.pout.rank > 0)
-        early_calls[output_side_group(l, nl)].push_back(PrecondCall{&L.pout, L.A, L.lda, N, nullptr, nullptr});
+      const int k = output_side_group(l, nl, net->n_side);
+      ready_layer[k] = std::min(ready_layer[k], l);
+      if (L.pout.rank > 0) early_calls[k].push_back(PrecondCall{&L.pout, L.A, L.lda, N, nullptr, nullptr});
       if (L.pin.rank > 0) early_calls[0].push_back(PrecondCall{&L.pin, L.Xin, L.ldx, N, nullptr, nullptr});
     }
   }
@@ -1462,7 +1468,8 @@ extern "C" int ngsgd_step(ngsgd_net* net, const float* dev_x, const int32_t* dev
     HIP_TRY(hipEventRecord(sd.hj_done, sd.stream));
     return factor_begin(early_calls[k], sd.stream);
   };
-  NG_TRY(early_start(0));
+  for (int k = 0; k < kSideStreams; ++k)
+    if (ready_layer[k] == nl - 1) NG_TRY(early_start(k));   // (empty groups return at once)
 
   // backward on the unmodified derivatives (App. C.3, last paragraph)
   for (int l = nl - 1; l >= 1; --l) {
@@ -1489,11 +1496,9 @@ extern "C" int ngsgd_step(ngsgd_net* net, const float* dev_x, const int32_t* dev
                          L.Xin, L.ldx, P.sigma, P.A, P.lda, N, P.groups, net->pnorm_group, net->renorm);
     }
     LAUNCH_CHECK();
-    // the derivatives of layer l - 1 exist now: start their group once its lowest layer is there
-    const int k = output_side_group(l - 1, nl);
-    if (l - 1 == 0 || output_side_group(l - 2, nl) != k) {
-      NG_TRY(early_start(k));
-    }
+    // the derivatives of layer l - 1 exist now: start the group of which it is the lowest layer
+    for (int k = 0; k < kSideStreams; ++k)
+      if (ready_layer[k] == l - 1) NG_TRY(early_start(k));
   }
 
   // maximum parameter change (App. C.3), then W_l += lr a_l gamma_o gamma_x Ohat_l^T Xhat_l  (Sec. 4.6) for the
@@ -1567,10 +1572,10 @@ extern "C" int ngsgd_step(ngsgd_net* net, const float* dev_x, const int32_t* dev
     // No factor is due, or the first call of an instance (initialisation): everything on the caller's stream.
     // On the step after an update the group that started last may still be running: the layers that do not
     // depend on it are preconditioned and updated first, the others behind them.
-    SideSync* const last_side = &net->side[kSideStreams - 1];
+    SideSync* const last_side = &net->side[net->n_side - 1];
     std::vector<PrecondCall> calls[2];
     std::vector<int> layers[2];
-    const bool split = last_side->pending;
+    const bool split = net->n_side > 1 && last_side->pending;
     for (int l = 0; l < nl; ++l) {
       ngsgd_layer& L = Ls[l];
       const int late = split && L.pout.sync == last_side ? 1 : 0;
@@ -1578,8 +1583,8 @@ extern "C" int ngsgd_step(ngsgd_net* net, const float* dev_x, const int32_t* dev
       calls[0].push_back(PrecondCall{&L.pin, L.Xin, L.ldx, N, nullptr, nullptr});
       layers[late].push_back(l);
     }
-    for (int k = 0; k + 1 < kSideStreams; ++k) NG_TRY(join_side(&net->side[k], s));
-    if (!split) NG_TRY(join_side(last_side, s));
+    for (SideSync& sd : net->side)
+      if (!split || &sd != last_side) NG_TRY(join_side(&sd, s));
     NG_TRY(precondition_many(calls[0], false, s, nullptr));
     NG_TRY(update_layers(layers[0]));
     if (split) {

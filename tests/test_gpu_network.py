@@ -21,7 +21,7 @@ def rel(a, b):
     return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
 
 
-def make_pair(ngsgd, spec, renorm=False, max_change=0.0, weights=None, max_batch=None):
+def make_pair(ngsgd, spec, renorm=False, max_change=0.0, weights=None, max_batch=None, side_streams=0):
     import torch
     weights = workloads.initial_weights(spec) if weights is None else weights
     ora = NGSGDNetwork(spec.dims, spec.nonlin, weights, spec.pnorm_group, spec.rank_in, spec.rank_out, spec.alpha,
@@ -29,7 +29,7 @@ def make_pair(ngsgd, spec, renorm=False, max_change=0.0, weights=None, max_batch
                        max_change_per_sample=max_change)
     gpu = ngsgd.Network(spec.dims, spec.nonlin, max_batch or spec.minibatch, spec.pnorm_group, spec.rank_in,
                         spec.rank_out, spec.alpha, spec.num_samples_history, spec.epsilon, spec.update_period,
-                        renorm=renorm, max_change_per_sample=max_change)
+                        renorm=renorm, max_change_per_sample=max_change, side_streams=side_streams)
     for l, w in enumerate(weights):
         gpu.set_params(l, torch.from_numpy(np.ascontiguousarray(w, dtype=np.float32)).cuda())
     return ora, gpu
@@ -134,14 +134,16 @@ def test_small_pnorm_net_plain(ngsgd):
     run_and_compare(ngsgd, spec, ora, gpu, 2, rows=spec.minibatch - 9)
 
 
-def test_small_pnorm_net_past_the_always_update_phase(ngsgd):
+@pytest.mark.parametrize("side_streams", [0, 1, 2])
+def test_small_pnorm_net_past_the_always_update_phase(ngsgd, side_streams):
     """Sixteen steps without any synchronisation of state: steps 10, 11 only apply the factors, step 12 is the first
     periodic update and step 13 is the step that follows one, which the library orders around the factor updates
-    still in flight (the layers whose factors are ready are preconditioned and updated first)."""
+    still in flight (the layers whose factors are ready are preconditioned and updated first).  With the default
+    three internal streams, with one (a single group of factors) and with two."""
     spec = workloads.small_pnorm()
-    ora, gpu = make_pair(ngsgd, spec, renorm=True, max_change=0.075)
+    ora, gpu = make_pair(ngsgd, spec, renorm=True, max_change=0.075, side_streams=side_streams)
     worst = run_and_compare(ngsgd, spec, ora, gpu, 16)
-    print("small p-norm net, 16 steps free running", worst)
+    print("small p-norm net, 16 steps free running, side_streams", side_streams, worst)
 
 
 def test_rank_zero_is_plain_sgd(ngsgd):

@@ -80,12 +80,12 @@ def make_cfg(dims, nonlin, **kw):
     nl = (c_int32 * max(1, len(nonlin)))(*nonlin)
     vals = dict(pnorm_group=10, max_batch=512, rank_in=20, rank_out=80, alpha=4.0, num_samples_history=2000.0,
                 epsilon=1e-10, update_period=4, always_update_first=10, renorm=0, max_change_per_sample=0.0,
-                method=ng.NGSGD_METHOD_ONLINE, simple_epsilon=1e-20)
+                method=ng.NGSGD_METHOD_ONLINE, simple_epsilon=1e-20, side_streams=0)
     vals.update(kw)
     cfg = ng.ngsgd_config(len(dims) - 1, d, nl, vals["pnorm_group"], vals["max_batch"], vals["rank_in"],
                           vals["rank_out"], vals["alpha"], vals["num_samples_history"], vals["epsilon"],
                           vals["update_period"], vals["always_update_first"], vals["renorm"],
-                          vals["max_change_per_sample"], vals["method"], vals["simple_epsilon"])
+                          vals["max_change_per_sample"], vals["method"], vals["simple_epsilon"], vals["side_streams"])
     cfg._keep = (d, nl)
     return cfg
 
@@ -107,6 +107,8 @@ def test_network_workspace_sizing_and_config_validation(lib):
         make_cfg([360, 3000, 5000], [1], update_period=0),
         make_cfg([360, 3000, 5000], [1], max_change_per_sample=-1.0),
         make_cfg([360, 3000, 5000], [1], method=7),
+        make_cfg([360, 3000, 5000], [1], side_streams=4),
+        make_cfg([360, 3000, 5000], [1], side_streams=-1),
         make_cfg([360, 3000, 5000], [1], method=ng.NGSGD_METHOD_SIMPLE, max_batch=1),       # nothing to hold out
         make_cfg([360, 3000, 5000], [1], method=ng.NGSGD_METHOD_SIMPLE, simple_epsilon=0.0),
         make_cfg([360, 3000, 5000], [1], method=ng.NGSGD_METHOD_SIMPLE, alpha=0.0),
