@@ -22,9 +22,11 @@
  *     return without waiting for it.  Scalars results are written to device
  *     memory.  Calls on the same handle must be issued in order on one stream.
  *     Handles are not thread-safe.
- *   - A network also owns one internal stream (default priority): the factor
- *     updates of its preconditioners run there, so that they overlap the rest
- *     of the step and the following minibatch.  Every call on the handle
+ *   - A network also owns up to three internal streams (default priority;
+ *     ngsgd_config.side_streams): the factor updates of its preconditioners
+ *     run there, each group of factors starting as soon as its matrix exists,
+ *     so that they overlap the rest of the step and the following minibatch.
+ *     Every call on the handle
  *     orders itself after whatever it depends on; a caller that wants the
  *     stream it passed to cover all of a step's work (to time it, or to read
  *     the handle's device memory directly) calls ngsgd_join first.
@@ -176,7 +178,7 @@ int ngsgd_destroy(ngsgd_net* net);
 int ngsgd_step(ngsgd_net* net, const float* dev_x, const int32_t* dev_labels, int32_t N, float lr,
                double* dev_logprob_sum, void* hip_stream);
 
-/* Makes hip_stream wait for what the network still has in flight on its internal stream (the latest
+/* Makes hip_stream wait for what the network still has in flight on its internal streams (the latest
  * factor updates); enqueues nothing else. */
 int ngsgd_join(ngsgd_net* net, void* hip_stream);
 

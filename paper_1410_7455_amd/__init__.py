@@ -280,7 +280,7 @@ class Network:
         return out
 
     def join(self, stream=None):
-        """Makes the stream wait for the factor updates the network has in flight on its internal stream."""
+        """Makes the stream wait for the factor updates the network has in flight on its internal streams."""
         _check(self.lib.ngsgd_join(self.handle, _stream_ptr(stream)), "ngsgd_join")
 
     def precond(self, layer, side):

@@ -228,7 +228,7 @@ def test_average_replicas(ngsgd):
 
 
 def test_back_to_back_steps_equal_synchronised_steps(ngsgd):
-    """The factor updates of a step overlap the following steps on an internal stream: steps enqueued back to back
+    """The factor updates of a step overlap the following steps on internal streams: steps enqueued back to back
     must give what steps separated by a device synchronisation give.
     (Both are GPU runs; sums over split products use atomics, so they agree to rounding, not bit for bit.)"""
     import torch
