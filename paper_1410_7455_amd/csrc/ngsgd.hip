@@ -474,36 +474,34 @@ int clear_accumulators(const std::vector<PrecondCall>& list, hipStream_t s) {
   return NGSGD_OK;
 }
 
-// H = X W^T   (eq. ht) and the partial sums of tr(X X^T) for the listed instances, one launch per rank class.
+// H = X W^T   (eq. ht) and the partial sums of tr(X X^T) for the listed instances in one launch: the tile is as
+// wide as the widest rank class present (a narrower instance wastes matrix-unit work that is small next to the
+// cost of a launch of its own).
 int launch_h_products(std::vector<PrecondCall>& list, hipStream_t s) {
-  int class_count[3] = {0, 0, 0};   // instances per rank class (they share a launch)
-  for (auto& c : list) class_count[c.p->ldh == 32 ? 0 : (c.p->ldh == 80 ? 1 : 2)] += 1;
-  auto group_of = [&](const ngsgd_precond& p) { return class_count[p.ldh == 32 ? 0 : (p.ldh == 80 ? 1 : 2)]; };
-  for (int rc : {32, 80, 96}) {
-    std::vector<GemmDesc> d;
-    for (auto& c : list) {
-      ngsgd_precond& p = *c.p;
-      if (p.ldh != rc) continue;
-      GemmDesc g;
-      g.A = c.M; g.lda = c.ld;
-      g.B = p.W; g.ldb = p.ldw;
-      g.C = p.H; g.ldc = p.ldh;
-      g.M = c.N; g.N = p.rank; g.K = p.dim;
-      g.sumsq = p.sumsq_part;
-      g.splits = h_splits(c.N, p.dim, group_of(p));
-      p.last_N = c.N;
-      {
-        GemmDesc hd = g;
-        p.n_sumsq = planned_sumsq_partials<64, 32, HBK>(hd);   // independent of the tile width
-      }
-      d.push_back(g);
+  if (list.empty()) return NGSGD_OK;
+  int rc = 0;
+  for (auto& c : list) rc = std::max(rc, c.p->ldh);
+  std::vector<GemmDesc> d;
+  for (auto& c : list) {
+    ngsgd_precond& p = *c.p;
+    GemmDesc g;
+    g.A = c.M; g.lda = c.ld;
+    g.B = p.W; g.ldb = p.ldw;
+    g.C = p.H; g.ldc = p.ldh;
+    g.M = c.N; g.N = p.rank; g.K = p.dim;
+    g.sumsq = p.sumsq_part;
+    g.splits = h_splits(c.N, p.dim, (int)list.size());
+    p.last_N = c.N;
+    {
+      GemmDesc hd = g;
+      p.n_sumsq = planned_sumsq_partials<64, 32, HBK>(hd);   // independent of the tile width
     }
-    if (d.empty()) continue;
-    ProfScope prof(NGSGD_PROF_PRECOND_H, s);
-    HIP_TRY(by_rank_class(rc, [&] { return launch_h<32>(d.data(), (int)d.size(), s); },
-                          [&] { return launch_h<80>(d.data(), (int)d.size(), s); },
-                          [&] { return launch_h<96>(d.data(), (int)d.size(), s); }));
+    d.push_back(g);
   }
+  ProfScope prof(NGSGD_PROF_PRECOND_H, s);
+  HIP_TRY(by_rank_class(rc, [&] { return launch_h<32>(d.data(), (int)d.size(), s); },
+                        [&] { return launch_h<80>(d.data(), (int)d.size(), s); },
+                        [&] { return launch_h<96>(d.data(), (int)d.size(), s); }));
   return NGSGD_OK;
 }
 
