@@ -168,6 +168,29 @@ def test_parameter_averaging():
         assert all(p.t == 0 and p.R is None for p in net.precond_in + net.precond_out)
 
 
+def test_job_learning_rate_keeps_the_effective_rate():
+    """Sec. 3.1: with the jobs' rate n times the effective rate, one averaged SGD step of n jobs from common weights
+    equals one step at the effective rate on the sum of the jobs' gradients (checked on plain SGD, rank 0)."""
+    import paper_1410_7455_amd as ng
+    n_jobs, eff = 3, 0.004
+    lr = ng.job_learning_rate(eff, n_jobs)
+    assert lr == pytest.approx(0.012)
+    with pytest.raises(ValueError):
+        ng.job_learning_rate(eff, 0)
+    rng = np.random.default_rng(31)
+    nets = [tiny_net(np.random.default_rng(9), [TANH, PNORM], ng=False) for _ in range(n_jobs)]
+    start = [w.copy() for w in nets[0].W]
+    total = [np.zeros_like(w) for w in start]
+    for net in nets:
+        x, y = rng.standard_normal((8, 5)), rng.integers(0, 7, 8)
+        for l, g in enumerate(net.gradients(x, y)):
+            total[l] += g
+        net.step(x, y, lr)
+    average_parameters(nets, reset_preconditioners=False)
+    for l in range(3):
+        np.testing.assert_allclose(nets[0].W[l], start[l] + eff * total[l], atol=1e-14)
+
+
 def test_workload_generators_are_seeded_and_shaped():
     spec = workloads.c1_pnorm()
     assert spec.in_dims == [360, 300, 300, 300, 300] and spec.n_params() == 5_297_000
