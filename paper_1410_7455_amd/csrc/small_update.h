@@ -236,8 +236,8 @@ __global__ __launch_bounds__(NT) void eig_update_kernel(const SmallGroup g) {
   const double abs_tol2 = abs_tol * abs_tol;
 
   // The off-diagonal blocks (bi < bj) this thread owns (the threads after the first wavefront, row by row), where
-  // they are stored, and the (fixed) destinations of their four entries.  The diagonal blocks belong to the
-  // rotation lanes of the first wavefront, so the block waves run one branch-free code path.
+  // they are stored, and the (fixed) destinations of their four entries.  The diagonal blocks are handled apart
+  // (three entries, a different formula), so this path is branch-free.
   const int n_off = half * (half - 1) / 2;
   int blk_i[ITEMS], blk_j[ITEMS], blk_t[ITEMS];
   int dst[ITEMS][4];
@@ -257,13 +257,16 @@ __global__ __launch_bounds__(NT) void eig_update_kernel(const SmallGroup g) {
     for (int e = 0; e < 4; ++e)
       dst[it][e] = place(next_position(2 * bi + (e >> 1), half), next_position(2 * min(bj, half - 1) + (e & 1), half));
   }
-  // destinations of the diagonal block (rot_k, rot_k): entries (t,t), (t,b), (b,b)
+  // The diagonal block (k, k) is rotated by lane k of the second wavefront (on top of its off-diagonal block): the
+  // rotation lanes' chain bounds the round and is kept as short as possible.  Destinations of (t,t), (t,b), (b,b):
+  const int diag_k = tid - 64;
+  const bool diag_lane = diag_k >= 0 && diag_k < half;
   int diag_t = 0, diag_dst[3] = {0, 0, 0};
-  if (tid < half) {
-    diag_t = tri(tid);
-    diag_dst[0] = place(next_position(2 * tid, half), next_position(2 * tid, half));
-    diag_dst[1] = place(next_position(2 * tid, half), next_position(2 * tid + 1, half));
-    diag_dst[2] = place(next_position(2 * tid + 1, half), next_position(2 * tid + 1, half));
+  if (diag_lane) {
+    diag_t = tri(diag_k);
+    diag_dst[0] = place(next_position(2 * diag_k, half), next_position(2 * diag_k, half));
+    diag_dst[1] = place(next_position(2 * diag_k, half), next_position(2 * diag_k + 1, half));
+    diag_dst[2] = place(next_position(2 * diag_k + 1, half), next_position(2 * diag_k + 1, half));
   }
   const bool odd_pad = (R & 1) != 0;   // pair 0 then holds the padding player
 
@@ -334,8 +337,9 @@ __global__ __launch_bounds__(NT) void eig_update_kernel(const SmallGroup g) {
         s_rc[cur ^ 1][rot_k] = c;
         s_rs[cur ^ 1][rot_k] = s;
         rotlog[(size_t)(rounds + 1) * half + rot_k] = make_double2(c, s);
-        // this round's rotation of the lane's own pair, applied to its diagonal block
-        const double ck = rc[rot_k], sk = rs[rot_k];
+      }
+      if (diag_lane) {   // this round's rotation of pair diag_k, applied to its diagonal block
+        const double ck = rc[diag_k], sk = rs[diag_k];
         const double att = dyn[co + diag_t], atb = dyn[co + np + diag_t], abb = dyn[co + 3 * np + diag_t];
         dyn[no + diag_dst[0]] = ck * ck * att - 2.0 * ck * sk * atb + sk * sk * abb;
         dyn[no + diag_dst[2]] = sk * sk * att + 2.0 * ck * sk * atb + ck * ck * abb;
