@@ -438,8 +438,8 @@ int h_splits(int N, int D, int group) {
 // it they are left as Xhat and gamma stays in the instance's state for the caller to fold into a later product.
 // The instances whose factor is due for an update are appended to `to_update`.
 //
-// precond_factor_update: the R x R work and the new factor for those instances (App. B.3); it reads only what
-// the first phase left in the instances' buffers, so it can run on another stream while the caller goes on.
+// factor_begin / factor_finish: the R x R work and the new factor for those instances (App. B.3); they read only
+// what the first phase left in the instances' buffers, so a network runs them on side streams (ngsgd_step).
 int precond_validate(const std::vector<PrecondCall>& calls) {
   for (auto& c : calls) {
     const ngsgd_precond& p = *c.p;
@@ -528,13 +528,10 @@ int launch_j_products(std::vector<PrecondCall>& list, hipStream_t s) {
   return NGSGD_OK;
 }
 
-// With `side`, two events are recorded on s for a factor update that runs on the side stream: inputs_ready once
-// H, J and the partial sums of tr(X X^T) are final, outputs_done once the last reader of W_t has been enqueued.
 // With hj_ready the caller has already produced H and J of every instance (all due for an update, none at t = 0)
 // and ordered s behind them; only Xhat and gamma remain.
-int precond_apply(std::vector<PrecondCall>& calls, bool scale_output, hipStream_t s, SideSync* side,
+int precond_apply(std::vector<PrecondCall>& calls, bool scale_output, hipStream_t s,
                   std::vector<PrecondCall>& to_update_out, bool hj_ready = false) {
-  const hipStream_t main_stream = s;
   std::vector<PrecondCall> full, to_init, to_update;
   for (auto& c : calls) {
     ngsgd_precond& p = *c.p;
@@ -560,10 +557,6 @@ int precond_apply(std::vector<PrecondCall>& calls, bool scale_output, hipStream_
     NG_TRY(launch_h_products(full, s));
     NG_TRY(launch_j_products(to_update, s));
   }
-  // The factor update needs only H, J and the partial sums of tr(X X^T): with a side stream it starts here and
-  // overlaps the rest of this call; it must not replace W_t before Xhat has read it (second event below).
-  const bool on_side = side != nullptr && !to_update.empty();
-  if (on_side) HIP_TRY(hipEventRecord(side->inputs_ready, main_stream));
   // Xhat = X - H W   (eq. hatxt:compute:2), row-norm partials (eq. pi)
   {
     std::vector<GemmDesc> d;
@@ -613,7 +606,6 @@ int precond_apply(std::vector<PrecondCall>& calls, bool scale_output, hipStream_
       LAUNCH_CHECK();
     }
   }
-  if (on_side) HIP_TRY(hipEventRecord(side->outputs_done, main_stream));
   to_update_out.insert(to_update_out.end(), to_update.begin(), to_update.end());
   return NGSGD_OK;
 }
@@ -798,32 +790,14 @@ int factor_finish(std::vector<PrecondCall>& to_update, hipStream_t s) {
   return NGSGD_OK;
 }
 
-// With `side` the work is enqueued on the side stream behind the two events of precond_apply; without it, on s.
-int precond_factor_update(std::vector<PrecondCall>& to_update, hipStream_t s, SideSync* side) {
-  if (to_update.empty()) return NGSGD_OK;
-  const bool on_side = side != nullptr;
-  if (on_side) {
-    HIP_TRY(hipStreamWaitEvent(side->stream, side->inputs_ready, 0));
-    s = side->stream;
-  }
-  NG_TRY(factor_begin(to_update, s));
-  if (on_side) HIP_TRY(hipStreamWaitEvent(side->stream, side->outputs_done, 0));
-  NG_TRY(factor_finish(to_update, s));
-  if (on_side) {
-    HIP_TRY(hipEventRecord(side->done, side->stream));
-    side->pending = true;
-  }
-  return NGSGD_OK;
-}
-
-// Both phases for one list of instances; with `side` the second phase overlaps whatever the caller enqueues next.
-int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStream_t s, SideSync* side = nullptr) {
+// Both phases for one list of instances on one stream.
+int precondition_many(std::vector<PrecondCall>& calls, bool scale_output, hipStream_t s) {
   NG_TRY(ensure_kernel_attributes());
   NG_TRY(precond_validate(calls));
-  NG_TRY(join_side(side, s));
   std::vector<PrecondCall> to_update;
-  NG_TRY(precond_apply(calls, scale_output, s, side, to_update));
-  NG_TRY(precond_factor_update(to_update, s, side));
+  NG_TRY(precond_apply(calls, scale_output, s, to_update));
+  NG_TRY(factor_begin(to_update, s));
+  NG_TRY(factor_finish(to_update, s));
   for (auto& c : calls) c.p->t += 1;
   return NGSGD_OK;
 }
@@ -1553,7 +1527,7 @@ extern "C" int ngsgd_step(ngsgd_net* net, const float* dev_x, const int32_t* dev
     for (int k = 0; k < kSideStreams; ++k)
       if (!early_calls[k].empty()) HIP_TRY(hipStreamWaitEvent(s, net->side[k].hj_done, 0));
     std::vector<PrecondCall> due;
-    NG_TRY(precond_apply(calls, false, s, nullptr, due, true));
+    NG_TRY(precond_apply(calls, false, s, due, true));
     for (int k = 0; k < kSideStreams; ++k)
       if (!early_calls[k].empty()) HIP_TRY(hipEventRecord(net->side[k].outputs_done, s));
     for (auto& c : calls) c.p->t += 1;
@@ -1583,11 +1557,11 @@ extern "C" int ngsgd_step(ngsgd_net* net, const float* dev_x, const int32_t* dev
     }
     for (SideSync& sd : net->side)
       if (!split || &sd != last_side) NG_TRY(join_side(&sd, s));
-    NG_TRY(precondition_many(calls[0], false, s, nullptr));
+    NG_TRY(precondition_many(calls[0], false, s));
     NG_TRY(update_layers(layers[0]));
     if (split) {
       NG_TRY(join_side(last_side, s));
-      if (!calls[1].empty()) NG_TRY(precondition_many(calls[1], false, s, nullptr));
+      if (!calls[1].empty()) NG_TRY(precondition_many(calls[1], false, s));
       NG_TRY(update_layers(layers[1]));
     }
   }
