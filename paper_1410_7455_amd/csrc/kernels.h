@@ -124,42 +124,53 @@ __global__ void tanh_backward_kernel(const float* __restrict__ dY, int ldd, int 
   }
 }
 
-// Workgroup-wide float sum / max for 256-thread workgroups (4 wavefronts); `red` holds >= 4 floats.
-__device__ __forceinline__ float block256_sum(float v, float* red) {
+// Workgroup-wide float sum / max for NT-thread workgroups (NT / 64 wavefronts); `red` holds >= NT / 64 floats.
+template <int NT>
+__device__ __forceinline__ float block_sum_f(float v, float* red) {
   v = wave_sum(v);
   __syncthreads();
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
   __syncthreads();
-  return red[0] + red[1] + red[2] + red[3];
+  float r = red[0];
+#pragma unroll
+  for (int w = 1; w < NT / 64; ++w) r += red[w];
+  return r;
 }
-__device__ __forceinline__ float block256_max(float v, float* red) {
+template <int NT>
+__device__ __forceinline__ float block_max_f(float v, float* red) {
   v = wave_max(v);
   __syncthreads();
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
   __syncthreads();
-  return fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  float r = red[0];
+#pragma unroll
+  for (int w = 1; w < NT / 64; ++w) r = fmaxf(r, red[w]);
+  return r;
 }
+__device__ __forceinline__ float block256_sum(float v, float* red) { return block_sum_f<256>(v, red); }
+__device__ __forceinline__ float block256_max(float v, float* red) { return block_max_f<256>(v, red); }
 
-// p-norm (p = 2) over groups of G adjacent columns, one 256-thread workgroup per row:
+// p-norm (p = 2) over groups of G adjacent columns, one NT-thread workgroup per row:
 //   y_j = sqrt(sum_k a_{Gj+k}^2);  with renorm: y <- y / max(rms(y), floor), sigma[n] = that divisor.
 // Writes Y[n][0..groups), Y[n][groups] = 1, padding zero.
 constexpr float kRenormFloor = 1.0e-20f;
 
-__global__ __launch_bounds__(256) void pnorm_forward_kernel(const float* __restrict__ A, int lda,
+template <int NT>
+__global__ __launch_bounds__(NT) void pnorm_forward_kernel(const float* __restrict__ A, int lda,
                                                             float* __restrict__ Y, int ldy,
                                                             float* __restrict__ sigma, int N, int groups, int G,
                                                             int renorm) {
-  __shared__ float red[4];
+  __shared__ float red[NT / 64];
   const int row = blockIdx.x;
   const float* a = A + (size_t)row * lda;
   float* y = Y + (size_t)row * ldy;
   float ss = 0.f;
   // a thread keeps the (few) groups it computes in registers until the row's scale is known
-  constexpr int kMaxOwn = 8;   // groups per thread: rows of up to 2048 groups stay in registers
+  constexpr int kMaxOwn = 2048 / NT;   // groups per thread: rows of up to 2048 groups stay in registers
   float own[kMaxOwn];
 #pragma unroll
   for (int u = 0; u < kMaxOwn; ++u) {
-    const int j = threadIdx.x + u * 256;
+    const int j = threadIdx.x + u * NT;
     float s = 0.f;
     if (j < groups) {
       const float* g = a + (size_t)j * G;
@@ -175,7 +186,7 @@ __global__ __launch_bounds__(256) void pnorm_forward_kernel(const float* __restr
     own[u] = sqrtf(s);
     ss += s;
   }
-  for (int j = threadIdx.x + kMaxOwn * 256; j < groups; j += 256) {   // very wide rows: through memory
+  for (int j = threadIdx.x + kMaxOwn * NT; j < groups; j += NT) {   // very wide rows: through memory
     float s = 0.f;
     for (int k = 0; k < G; ++k) s += a[(size_t)j * G + k] * a[(size_t)j * G + k];
     y[j] = sqrtf(s);
@@ -183,34 +194,36 @@ __global__ __launch_bounds__(256) void pnorm_forward_kernel(const float* __restr
   }
   float inv = 1.f;
   if (renorm) {
-    ss = block256_sum(ss, red);
+    ss = block_sum_f<NT>(ss, red);
     const float sg = fmaxf(sqrtf(ss / (float)groups), kRenormFloor);
     inv = 1.f / sg;
     if (threadIdx.x == 0) sigma[row] = sg;
-    for (int j = threadIdx.x + kMaxOwn * 256; j < groups; j += 256) y[j] *= inv;   // written by this thread above
+    for (int j = threadIdx.x + kMaxOwn * NT; j < groups; j += NT) y[j] *= inv;   // written by this thread above
   }
 #pragma unroll
   for (int u = 0; u < kMaxOwn; ++u) {
-    const int j = threadIdx.x + u * 256;
+    const int j = threadIdx.x + u * NT;
     if (j < groups) y[j] = own[u] * inv;
   }
-  for (int c = groups + threadIdx.x; c < ldy; c += 256) y[c] = c == groups ? 1.f : 0.f;
+  for (int c = groups + threadIdx.x; c < ldy; c += NT) y[c] = c == groups ? 1.f : 0.f;
 }
 
-// Backward through (renorm o p-norm), one 256-thread workgroup per row, in place over the affine outputs:
+// Backward through (renorm o p-norm), one NT-thread workgroup per row, in place over the affine outputs:
 //   AO[n][Gj+k] <- dy_j * a_{Gj+k} / y_j   (0 where y_j = 0)
 // with dy = dYn, y = Yn without renorm; with renorm  y = Yn*sigma, dy = (dYn - Yn * mean_j(dYn_j Yn_j)) / sigma.
 // dYn arrives as n_slabs partial products (see slab_sum).  The per-group factor dy_j / y_j goes through LDS.
 constexpr int kPnormMaxGroupsLds = 4096;
-constexpr int kPnormPrefetch = 8;   // float2 per thread held across the reductions (rows of up to 4096 outputs)
+constexpr int kPnormPrefetchPairs = 2048;   // float2 per row held in registers across the reductions (4096 outputs)
 
-__global__ __launch_bounds__(256) void pnorm_backward_kernel(const float* __restrict__ dYn, int ldd, int n_slabs,
+template <int NT>
+__global__ __launch_bounds__(NT) void pnorm_backward_kernel(const float* __restrict__ dYn, int ldd, int n_slabs,
                                                              size_t slab_stride,
                                                              const float* __restrict__ Yn, int ldy,
                                                              const float* __restrict__ sigma,
                                                              float* __restrict__ AO, int lda, int N, int groups,
                                                              int G, int renorm) {
-  __shared__ float red[4];
+  constexpr int kPnormPrefetch = kPnormPrefetchPairs / NT;
+  __shared__ float red[NT / 64];
   __shared__ float s_f[kPnormMaxGroupsLds];   // first dy_j, then the factor dy_j / y_j
   const int row = blockIdx.x;
   const float* dy = dYn + (size_t)row * ldd;
@@ -224,24 +237,24 @@ __global__ __launch_bounds__(256) void pnorm_backward_kernel(const float* __rest
   if (vec2) {
 #pragma unroll
     for (int u = 0; u < kPnormPrefetch; ++u) {
-      const int c2 = threadIdx.x + u * 256;
+      const int c2 = threadIdx.x + u * NT;
       if (c2 < D / 2) pre[u] = ao2[c2];
     }
   }
   float dot = 0.f;
-  for (int j = threadIdx.x; j < groups; j += 256) {
+  for (int j = threadIdx.x; j < groups; j += NT) {
     const float d = slab_sum(dy + j, n_slabs, slab_stride);
     s_f[j] = d;
     dot += d * yn[j];
   }
   float proj = 0.f, sg = 1.f;
   if (renorm) {
-    dot = block256_sum(dot, red);
+    dot = block_sum_f<NT>(dot, red);
     sg = sigma[row];
     proj = sg > kRenormFloor ? dot / (float)groups : 0.f;
   }
   const float inv_sg = 1.f / sg;
-  for (int j = threadIdx.x; j < groups; j += 256) {   // each thread rewrites the entries it wrote above
+  for (int j = threadIdx.x; j < groups; j += NT) {   // each thread rewrites the entries it wrote above
     const float ynj = yn[j];
     const float d = (s_f[j] - ynj * proj) * inv_sg;
     const float yj = ynj * sg;
@@ -252,13 +265,13 @@ __global__ __launch_bounds__(256) void pnorm_backward_kernel(const float* __rest
     const int half_g = G / 2;
 #pragma unroll
     for (int u = 0; u < kPnormPrefetch; ++u) {
-      const int c2 = threadIdx.x + u * 256;
+      const int c2 = threadIdx.x + u * NT;
       if (c2 < D / 2) {
         const float f = s_f[c2 / half_g];
         ao2[c2] = make_float2(pre[u].x * f, pre[u].y * f);
       }
     }
-    for (int c2 = threadIdx.x + kPnormPrefetch * 256; c2 < D / 2; c2 += 256) {
+    for (int c2 = threadIdx.x + kPnormPrefetch * NT; c2 < D / 2; c2 += NT) {
       const float f = s_f[c2 / half_g];
       float2 v = ao2[c2];
       v.x *= f;
@@ -266,29 +279,31 @@ __global__ __launch_bounds__(256) void pnorm_backward_kernel(const float* __rest
       ao2[c2] = v;
     }
   } else {
-    for (int c = threadIdx.x; c < D; c += 256) ao[c] *= s_f[c / G];
+    for (int c = threadIdx.x; c < D; c += NT) ao[c] *= s_f[c / G];
   }
 }
 
 // ---- log-softmax, objective and its derivative (Sec. 2) ------------------------------------------
-// One 256-thread workgroup per row, in place: AO[n][c] <- [c == y_n] - softmax(a_n)_c;
-// rowobj[n] = log p(y_n | x_n), also added to *total.  Rows of up to 256*4*kSoftmaxVec classes are read once and kept in registers.
-constexpr int kSoftmaxVec = 8;   // float4 per thread
+// One NT-thread workgroup per row, in place: AO[n][c] <- [c == y_n] - softmax(a_n)_c;
+// rowobj[n] = log p(y_n | x_n), also added to *total.  Rows of up to 4 * kSoftmaxRowVec classes are read once and kept in registers.
+constexpr int kSoftmaxRowVec = 2048;   // float4 per row held in registers
 
-__global__ __launch_bounds__(256) void softmax_xent_kernel(float* __restrict__ AO, int ld,
+template <int NT>
+__global__ __launch_bounds__(NT) void softmax_xent_kernel(float* __restrict__ AO, int ld,
                                                            const int32_t* __restrict__ labels, int N, int C,
                                                            double* __restrict__ rowobj, double* __restrict__ total) {
-  __shared__ float red[4];
+  constexpr int kSoftmaxVec = kSoftmaxRowVec / NT;   // float4 per thread
+  __shared__ float red[NT / 64];
   const int row = blockIdx.x;
   float* a = AO + (size_t)row * ld;
   const int y = labels[row];
   const bool valid = y >= 0 && y < C;        // an out-of-range label yields NaN, never an out-of-bounds access
-  if (C <= 256 * 4 * kSoftmaxVec) {
+  if (C <= 4 * kSoftmaxRowVec) {
     float4 v[kSoftmaxVec];
     float m = -INFINITY;
 #pragma unroll
     for (int u = 0; u < kSoftmaxVec; ++u) {
-      const int c = (threadIdx.x + u * 256) * 4;
+      const int c = (threadIdx.x + u * NT) * 4;
       float4 t = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
       if (c + 3 < C) {
         t = *reinterpret_cast<const float4*>(a + c);
@@ -300,7 +315,7 @@ __global__ __launch_bounds__(256) void softmax_xent_kernel(float* __restrict__ A
       v[u] = t;
       m = fmaxf(fmaxf(m, fmaxf(t.x, t.y)), fmaxf(t.z, t.w));
     }
-    m = block256_max(m, red);
+    m = block_max_f<NT>(m, red);
     float s = 0.f;
 #pragma unroll
     for (int u = 0; u < kSoftmaxVec; ++u) {
@@ -310,7 +325,7 @@ __global__ __launch_bounds__(256) void softmax_xent_kernel(float* __restrict__ A
       v[u].w = expf(v[u].w - m);
       s += (v[u].x + v[u].y) + (v[u].z + v[u].w);
     }
-    s = block256_sum(s, red);
+    s = block_sum_f<NT>(s, red);
     if (threadIdx.x == 0) {
       const double lp = valid ? (double)a[y] - ((double)m + log((double)s)) : (double)NAN;
       rowobj[row] = lp;
@@ -320,7 +335,7 @@ __global__ __launch_bounds__(256) void softmax_xent_kernel(float* __restrict__ A
     const float inv = 1.f / s;
 #pragma unroll
     for (int u = 0; u < kSoftmaxVec; ++u) {
-      const int c = (threadIdx.x + u * 256) * 4;
+      const int c = (threadIdx.x + u * NT) * 4;
       float4 o;
       o.x = (c == y ? 1.f : 0.f) - v[u].x * inv;
       o.y = (c + 1 == y ? 1.f : 0.f) - v[u].y * inv;
@@ -338,11 +353,11 @@ __global__ __launch_bounds__(256) void softmax_xent_kernel(float* __restrict__ A
   }
   // wider rows: three passes over memory
   float m = -INFINITY;
-  for (int c = threadIdx.x; c < C; c += 256) m = fmaxf(m, a[c]);
-  m = block256_max(m, red);
+  for (int c = threadIdx.x; c < C; c += NT) m = fmaxf(m, a[c]);
+  m = block_max_f<NT>(m, red);
   float s = 0.f;
-  for (int c = threadIdx.x; c < C; c += 256) s += expf(a[c] - m);
-  s = block256_sum(s, red);
+  for (int c = threadIdx.x; c < C; c += NT) s += expf(a[c] - m);
+  s = block_sum_f<NT>(s, red);
   const float lse = m + logf(s);
   if (threadIdx.x == 0) {
     const double lp = valid ? (double)a[y] - ((double)m + log((double)s)) : (double)NAN;
@@ -350,7 +365,7 @@ __global__ __launch_bounds__(256) void softmax_xent_kernel(float* __restrict__ A
     unsafeAtomicAdd(total, lp);
   }
   __syncthreads();
-  for (int c = threadIdx.x; c < C; c += 256) a[c] = (c == y ? 1.f : 0.f) - expf(a[c] - lse);
+  for (int c = threadIdx.x; c < C; c += NT) a[c] = (c == y ? 1.f : 0.f) - expf(a[c] - lse);
 }
 
 // ---- preconditioner helpers -----------------------------------------------------------------------

@@ -93,6 +93,7 @@ struct ProfScope {
 };
 
 constexpr int kSumsqMax = 1024;   // partial sums of squares per preconditioner call
+constexpr int kWideRow = 2048;    // rows at least this wide get 512-thread workgroups in the row-wise kernels
 constexpr int kTargetBlocks = 512;
 
 inline int rank_class(int rank) { return rank <= 32 ? 32 : (rank <= 80 ? 80 : 96); }
@@ -1395,8 +1396,13 @@ extern "C" int ngsgd_step(ngsgd_net* net, const float* dev_x, const int32_t* dev
         hipLaunchKernelGGL(tanh_forward_kernel, dim3((Nx.ldx + 1023) / 1024, N), dim3(256), 0, s, L.A, L.lda, Nx.Xin,
                            Nx.ldx, N, L.dout);
       } else {
-        hipLaunchKernelGGL(pnorm_forward_kernel, dim3(N), dim3(256), 0, s, L.A, L.lda, Nx.Xin, Nx.ldx,
-                           L.sigma, N, L.groups, net->pnorm_group, net->renorm);
+        if (L.dout >= kWideRow) {
+          hipLaunchKernelGGL(pnorm_forward_kernel<512>, dim3(N), dim3(512), 0, s, L.A, L.lda, Nx.Xin, Nx.ldx,
+                             L.sigma, N, L.groups, net->pnorm_group, net->renorm);
+        } else {
+          hipLaunchKernelGGL(pnorm_forward_kernel<256>, dim3(N), dim3(256), 0, s, L.A, L.lda, Nx.Xin, Nx.ldx,
+                             L.sigma, N, L.groups, net->pnorm_group, net->renorm);
+        }
       }
       LAUNCH_CHECK();
     }
@@ -1404,8 +1410,13 @@ extern "C" int ngsgd_step(ngsgd_net* net, const float* dev_x, const int32_t* dev
   ngsgd_layer& last = Ls[nl - 1];
   {
   ProfScope prof(NGSGD_PROF_ELEMENTWISE, s);
-  hipLaunchKernelGGL(softmax_xent_kernel, dim3(N), dim3(256), 0, s, last.A, last.lda, dev_labels, N, last.dout,
-                     net->rowobj, objective);
+  if (last.dout >= kWideRow) {
+    hipLaunchKernelGGL(softmax_xent_kernel<512>, dim3(N), dim3(512), 0, s, last.A, last.lda, dev_labels, N, last.dout,
+                       net->rowobj, objective);
+  } else {
+    hipLaunchKernelGGL(softmax_xent_kernel<256>, dim3(N), dim3(256), 0, s, last.A, last.lda, dev_labels, N, last.dout,
+                       net->rowobj, objective);
+  }
   LAUNCH_CHECK();
   }
 
@@ -1464,8 +1475,13 @@ extern "C" int ngsgd_step(ngsgd_net* net, const float* dev_x, const int32_t* dev
       hipLaunchKernelGGL(tanh_backward_kernel, dim3((P.dout + 1023) / 1024, N), dim3(256), 0, s, net->dX, net->lddx,
                          n_slabs, slab, L.Xin, L.ldx, P.A, P.lda, N, P.dout);
     } else {
-      hipLaunchKernelGGL(pnorm_backward_kernel, dim3(N), dim3(256), 0, s, net->dX, net->lddx, n_slabs, slab,
-                         L.Xin, L.ldx, P.sigma, P.A, P.lda, N, P.groups, net->pnorm_group, net->renorm);
+      if (P.dout >= kWideRow) {
+        hipLaunchKernelGGL(pnorm_backward_kernel<512>, dim3(N), dim3(512), 0, s, net->dX, net->lddx, n_slabs, slab,
+                           L.Xin, L.ldx, P.sigma, P.A, P.lda, N, P.groups, net->pnorm_group, net->renorm);
+      } else {
+        hipLaunchKernelGGL(pnorm_backward_kernel<256>, dim3(N), dim3(256), 0, s, net->dX, net->lddx, n_slabs, slab,
+                           L.Xin, L.ldx, P.sigma, P.A, P.lda, N, P.groups, net->pnorm_group, net->renorm);
+      }
     }
     LAUNCH_CHECK();
     // the derivatives of layer l - 1 exist now: start the group of which it is the lowest layer
