@@ -128,9 +128,11 @@ def run_step_bench(args):
     if not np.isfinite(final_logp):
         raise RuntimeError("training diverged: the benchmark number would be meaningless")
 
-    # second pass with per-category HIP events on the launch stream (same steps, same shapes)
+    # second pass with per-category HIP events on the launch stream (same steps, same shapes); bounded so that the
+    # library's event pool (65536 events, about 70 per step) always holds every launch group of the pass
+    prof_steps = min(args.steps, 400)
     ng.profile_enable(True)
-    for _ in range(args.steps):
+    for _ in range(prof_steps):
         x, y = pool[step_no % POOL]
         net.step(x, y, spec.lr, logp)
         step_no += 1
@@ -143,21 +145,21 @@ def run_step_bench(args):
     for name, (ms, cnt) in prof.items():
         if cnt == 0:
             continue
-        entry = dict(ms_per_step=ms / args.steps, launches_per_step=cnt / args.steps, share=ms / total_ms)
+        entry = dict(ms_per_step=ms / prof_steps, launches_per_step=cnt / prof_steps, share=ms / total_ms)
         if name in flops:
-            entry["tflops"] = flops[name] * args.steps / (ms * 1e-3) / 1e12
+            entry["tflops"] = flops[name] * prof_steps / (ms * 1e-3) / 1e12
         breakdown[name] = entry
         log(f"[bench]   {name:14s} {entry['ms_per_step'] * 1e3:9.1f} us/step  {entry['share'] * 100:5.1f} %"
             + (f"  {entry['tflops']:6.1f} TFLOP/s" if "tflops" in entry else ""))
     dominant = max((k for k in breakdown if k in flops), key=lambda k: breakdown[k]["ms_per_step"])
     ms, cnt = prof[dominant]
-    achieved = flops[dominant] * args.steps / (ms * 1e-3) / 1e12
+    achieved = flops[dominant] * prof_steps / (ms * 1e-3) / 1e12
     roofline = dict(bound="mfma", kernel=dominant, achieved=achieved, peak=PEAK_MFMA_F32_TFLOPS, unit="TFLOP/s",
                     frac=achieved / PEAK_MFMA_F32_TFLOPS, traffic=measured_traffic_per_launch(dominant),
                     traffic_unit="bytes of HBM traffic per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, from profiles/)",
-                    algorithmic_bytes_per_launch=gemm_bytes_per_step(spec, n)[dominant] * args.steps / cnt,
-                    flops_per_launch=flops[dominant] * args.steps / cnt, avg_launch_us=ms * 1e3 / cnt,
-                    all_gemms_tflops=sum(flops.values()) * args.steps /
+                    algorithmic_bytes_per_launch=gemm_bytes_per_step(spec, n)[dominant] * prof_steps / cnt,
+                    flops_per_launch=flops[dominant] * prof_steps / cnt, avg_launch_us=ms * 1e3 / cnt,
+                    all_gemms_tflops=sum(flops.values()) * prof_steps /
                     (sum(prof[k][0] for k in flops) * 1e-3) / 1e12)
     return spec, ms_per_step, frames_per_s, roofline, breakdown, final_logp
 
