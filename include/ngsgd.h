@@ -209,7 +209,8 @@ int ngsgd_last_max_change_scale(ngsgd_net* net, int32_t layer, double* dev_out, 
  * recorded on the launch stream.  ngsgd_profile_read waits for the recorded events, adds the elapsed
  * milliseconds and the number of bracketed groups per category into ms_out / launches_out (arrays of
  * n_categories >= NGSGD_PROF_CATEGORIES entries, host memory) and clears the record.  Process-wide,
- * not thread-safe; at most 32768 groups are kept between reads. */
+ * not thread-safe; at most 32768 groups are kept between reads: if more were launched the call still
+ * fills the arrays with what was kept and returns NGSGD_ENOMEM. */
 #define NGSGD_PROF_GEMM_FWD 0        /* A_l = [X_l, 1] W_l^T                                     */
 #define NGSGD_PROF_GEMM_BWD 1        /* dX_l = O_l W_l                                           */
 #define NGSGD_PROF_GEMM_UPD 2        /* W_l += lr Obar_l^T Xbar_l (one grouped launch per step)  */

@@ -67,6 +67,7 @@ struct Profiler {
   };
   std::vector<Rec> recs;
   size_t used = 0;
+  size_t dropped = 0;   // launch groups that found the event pool full since the last read
 };
 Profiler g_prof;
 constexpr size_t kProfMaxEvents = 1 << 16;
@@ -76,7 +77,11 @@ struct ProfScope {
   bool active = false;
   size_t e0 = 0;
   ProfScope(int cat, hipStream_t stream) : s(stream) {
-    if (!g_prof.on || g_prof.used + 2 > kProfMaxEvents) return;
+    if (!g_prof.on) return;
+    if (g_prof.used + 2 > kProfMaxEvents) {
+      g_prof.dropped += 1;
+      return;
+    }
     while (g_prof.pool.size() < g_prof.used + 2) {
       hipEvent_t e;
       if (hipEventCreate(&e) != hipSuccess) return;
@@ -1681,6 +1686,7 @@ extern "C" const char* ngsgd_strerror(int code) {
 extern "C" int ngsgd_profile_enable(int32_t on) {
   g_prof.on = on != 0;
   g_prof.used = 0;
+  g_prof.dropped = 0;
   g_prof.recs.clear();
   return NGSGD_OK;
 }
@@ -1698,9 +1704,11 @@ extern "C" int ngsgd_profile_read(double* ms_out, int64_t* launches_out, int32_t
     ms_out[r.cat] += (double)ms;
     launches_out[r.cat] += 1;
   }
+  const bool complete = g_prof.dropped == 0;
   g_prof.used = 0;
+  g_prof.dropped = 0;
   g_prof.recs.clear();
-  return NGSGD_OK;
+  return complete ? NGSGD_OK : NGSGD_ENOMEM;   // the sums miss the groups that did not fit
 }
 
 extern "C" int ngsgd_last_hip_error(void) { return g_last_hip_error; }
