@@ -168,6 +168,11 @@ def test_c1_full_size_first_steps(ngsgd):
     sync_from_oracle(ngsgd, spec, ora, gpu)
     worst = run_and_compare(ngsgd, spec, ora, gpu, 10, first_step=4, sync_every_step=True)
     print("c1 worst errors, step by step", worst)
+    # steps 14..17 free running from shared state: 16 is a periodic update whose factor updates are still in flight
+    # when step 17 is enqueued, so step 17 takes the library's path around them at full size
+    sync_from_oracle(ngsgd, spec, ora, gpu)
+    worst = run_and_compare(ngsgd, spec, ora, gpu, 4, first_step=14)
+    print("c1 worst errors, steps 14..17 free running", worst)
 
 
 def test_c3_wide_tanh_first_steps(ngsgd):
