@@ -431,17 +431,17 @@ __global__ __launch_bounds__(NT) void eig_update_kernel(const SmallGroup g) {
 }
 
 // Whole-wavefront shifts by one lane through the DPP path of the vector ALU (no LDS traffic): lane i receives the
-// value of lane i-1 (up) or i+1 (down); the lane without a source keeps its own value.
+// value of lane i-1 (up) or i+1 (down); the lane without a source receives zero.
 __device__ __forceinline__ double wave_shift_up(double x) {
   int lo = __double2loint(x), hi = __double2hiint(x);
-  lo = __builtin_amdgcn_update_dpp(lo, lo, 0x138, 0xf, 0xf, false);   // wave_shr:1
-  hi = __builtin_amdgcn_update_dpp(hi, hi, 0x138, 0xf, 0xf, false);
+  lo = __builtin_amdgcn_update_dpp(0, lo, 0x138, 0xf, 0xf, true);   // wave_shr:1
+  hi = __builtin_amdgcn_update_dpp(0, hi, 0x138, 0xf, 0xf, true);
   return __hiloint2double(hi, lo);
 }
 __device__ __forceinline__ double wave_shift_down(double x) {
   int lo = __double2loint(x), hi = __double2hiint(x);
-  lo = __builtin_amdgcn_update_dpp(lo, lo, 0x130, 0xf, 0xf, false);   // wave_shl:1
-  hi = __builtin_amdgcn_update_dpp(hi, hi, 0x130, 0xf, 0xf, false);
+  lo = __builtin_amdgcn_update_dpp(0, lo, 0x130, 0xf, 0xf, true);   // wave_shl:1
+  hi = __builtin_amdgcn_update_dpp(0, hi, 0x130, 0xf, 0xf, true);
   return __hiloint2double(hi, lo);
 }
 
@@ -466,6 +466,7 @@ __global__ __launch_bounds__(kEigvecThreads) void eigvec_kernel(const SmallGroup
   double top = (active && lane == row) ? 1.0 : 0.0;
   double bot = (active && m - 1 - lane == row) ? 1.0 : 0.0;
   const bool last_lane = lane == half - 1, lane0 = lane == 0, lane1 = lane == 1;
+  const bool single = m == 2;   // one pair: nothing moves
 
   // the log is padded to whole chunks, and one chunk beyond the last round is allocated: staging needs no guards
   constexpr int kLoads = (kEigvecChunk * kMaxHalf + kEigvecThreads - 1) / kEigvecThreads;
@@ -493,18 +494,14 @@ __global__ __launch_bounds__(kEigvecThreads) void eigvec_kernel(const SmallGroup
     auto replay = [&](double2 cs) {
       // the logged rotation acts on (first, second) of the pair
       const double nt_ = top * cs.x - bot * cs.y, nb_ = top * cs.y + bot * cs.x;
-      if (m > 2) {
-        // players move: firsts shift one lane down (the last lane takes its own second), seconds shift one lane
-        // up (lane 1 takes lane 0's first); lane 0's second is fixed
-        const double t_dn = wave_shift_down(nt_);
-        const double b_up = wave_shift_up(nb_);
-        const double t_up = wave_shift_up(nt_);
-        top = last_lane ? nb_ : t_dn;
-        bot = lane0 ? nb_ : (lane1 ? t_up : b_up);
-      } else {
-        top = nt_;
-        bot = nb_;
-      }
+      // players move: firsts shift one lane down (the last lane takes its own second), seconds shift one lane
+      // up (lane 1 takes lane 0's first); lane 0's second is fixed.  With a single pair (m = 2) lane 0 is the
+      // last lane as well and both members stay.
+      const double t_dn = wave_shift_down(nt_);
+      const double b_up = wave_shift_up(nb_);
+      const double t_up = wave_shift_up(nt_);
+      top = last_lane ? (single ? nt_ : nb_) : t_dn;
+      bot = lane0 ? nb_ : (lane1 ? t_up : b_up);
     };
     int rr = 0;
     for (; rr + 4 <= len; rr += 4) {   // four rotations fetched ahead of their use
