@@ -411,7 +411,7 @@ def run_replica_bench(replicas=8, rounds=4, steps_per_round=400):
                 overall_frames_per_s=overall)
 
 
-def run_cpu_baseline(max_steps=20, budget_s=25.0):
+def run_cpu_baseline(max_steps=120, budget_s=20.0):
     """The float64 oracle as it stands, timed on the host cores on a bounded sample of the same workload."""
     import workloads
     from oracle.network import NGSGDNetwork
