@@ -146,6 +146,18 @@ def test_small_pnorm_net_past_the_always_update_phase(ngsgd, side_streams):
     print("small p-norm net, 16 steps free running, side_streams", side_streams, worst)
 
 
+@pytest.mark.parametrize("dims,nonlin", [([40, 50], []), ([40, 120, 50], [workloads.PNORM])])
+def test_shallow_networks(ngsgd, dims, nonlin):
+    """One affine layer (softmax regression: no backward pass, one group of factors) and two (the first layer's
+    derivatives are the only ones the backward pass produces): 14 steps free running, through the always-update
+    phase, a periodic update and the step after it."""
+    spec = workloads.NetSpec("shallow", 7, dims, nonlin, 10, 64, 4, 8, 0.01, 14, softmax_zero_init=False,
+                             label_law="uniform", splice=1, base_dim=40)
+    ora, gpu = make_pair(ngsgd, spec, renorm=True, max_change=0.075)
+    worst = run_and_compare(ngsgd, spec, ora, gpu, 14)
+    print("shallow network", dims, worst)
+
+
 def test_rank_zero_is_plain_sgd(ngsgd):
     spec = workloads.c0_tiny()
     spec.rank_in = spec.rank_out = 0
