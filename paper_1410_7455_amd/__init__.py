@@ -25,6 +25,7 @@ NGSGD_PNORM = 1
 NGSGD_SIDE_INPUT = 0
 NGSGD_SIDE_OUTPUT = 1
 NGSGD_MAX_RANK = 96
+NGSGD_MAX_LAYERS = 16
 NGSGD_METHOD_ONLINE = 0
 NGSGD_METHOD_SIMPLE = 1
 

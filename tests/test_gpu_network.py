@@ -158,6 +158,24 @@ def test_shallow_networks(ngsgd, dims, nonlin):
     print("shallow network", dims, worst)
 
 
+def test_deepest_network(ngsgd):
+    """The most layers the library takes (16, i.e. 32 factor instances: more than one grouped launch holds),
+    alternating tanh and p-norm layers: 6 steps free running, then step by step from shared state (rounding
+    differences grow through 16 layers: free running, the first layer's derivatives are 1.3e-4 apart after ten
+    steps)."""
+    dims = [40] + [64] * 15 + [30]
+    nonlin = [workloads.TANH, workloads.PNORM] * 7 + [workloads.TANH]
+    assert len(dims) - 1 == ngsgd.NGSGD_MAX_LAYERS
+    spec = workloads.NetSpec("deep", 8, dims, nonlin, 2, 64, 4, 8, 0.01, 14, softmax_zero_init=False,
+                             label_law="uniform", splice=1, base_dim=40)
+    ora, gpu = make_pair(ngsgd, spec, renorm=True, max_change=0.075)
+    worst = run_and_compare(ngsgd, spec, ora, gpu, 6)
+    print("16-layer network, free running", worst)
+    sync_from_oracle(ngsgd, spec, ora, gpu)
+    worst = run_and_compare(ngsgd, spec, ora, gpu, 8, first_step=6, sync_every_step=True)
+    print("16-layer network, step by step", worst)
+
+
 def test_rank_zero_is_plain_sgd(ngsgd):
     spec = workloads.c0_tiny()
     spec.rank_in = spec.rank_out = 0
