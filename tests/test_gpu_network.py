@@ -176,6 +176,19 @@ def test_deepest_network(ngsgd):
     print("16-layer network, step by step", worst)
 
 
+@pytest.mark.parametrize("rows", [1, 2, 5, 63])
+def test_tiny_minibatches_after_the_first(ngsgd, rows):
+    """Once the factors exist a minibatch may be as small as one row (less than one tile, fewer rows than the
+    rank): two such steps from shared state, the first of them an update step."""
+    spec = workloads.small_pnorm()
+    spec.update_period = 1
+    ora, gpu = make_pair(ngsgd, spec, renorm=True, max_change=0.075)
+    run_and_compare(ngsgd, spec, ora, gpu, 2)
+    sync_from_oracle(ngsgd, spec, ora, gpu)
+    worst = run_and_compare(ngsgd, spec, ora, gpu, 2, first_step=2, rows=rows, sync_every_step=True)
+    print("minibatch of", rows, "rows", worst)
+
+
 def test_rank_zero_is_plain_sgd(ngsgd):
     spec = workloads.c0_tiny()
     spec.rank_in = spec.rank_out = 0
