@@ -1414,20 +1414,21 @@ extern "C" int ngsgd_step(ngsgd_net* net, const float* dev_x, const int32_t* dev
   }
   ngsgd_layer& last = Ls[nl - 1];
   {
-  ProfScope prof(NGSGD_PROF_ELEMENTWISE, s);
-  if (last.dout >= kWideRow) {
-    hipLaunchKernelGGL(softmax_xent_kernel<512>, dim3(N), dim3(512), 0, s, last.A, last.lda, dev_labels, N, last.dout,
-                       net->rowobj, objective);
-  } else {
-    hipLaunchKernelGGL(softmax_xent_kernel<256>, dim3(N), dim3(256), 0, s, last.A, last.lda, dev_labels, N, last.dout,
-                       net->rowobj, objective);
-  }
-  LAUNCH_CHECK();
+    ProfScope prof(NGSGD_PROF_ELEMENTWISE, s);
+    if (last.dout >= kWideRow) {
+      hipLaunchKernelGGL(softmax_xent_kernel<512>, dim3(N), dim3(512), 0, s, last.A, last.lda, dev_labels, N,
+                         last.dout, net->rowobj, objective);
+    } else {
+      hipLaunchKernelGGL(softmax_xent_kernel<256>, dim3(N), dim3(256), 0, s, last.A, last.lda, dev_labels, N,
+                         last.dout, net->rowobj, objective);
+    }
+    LAUNCH_CHECK();
   }
 
   // On a step whose factors are all due for an update (and none needs initialising) the products H, J and the
   // R x R work of each group of instances start on the group's side stream as soon as the group's matrices
-  // exist, next to the backward pass; W_t is replaced only after Xhat has read it (early_finish below).
+  // exist, next to the backward pass; W_t is replaced only after Xhat has read it (the second half of each group's
+  // update is enqueued at the end of the step).
   bool early = net->method == NGSGD_METHOD_ONLINE;
   for (auto& L : Ls)
     for (const ngsgd_precond* p : {&L.pin, &L.pout})
