@@ -199,17 +199,21 @@ __global__ __launch_bounds__(NT) void eig_update_kernel(const SmallGroup g) {
   __syncthreads();
 
   // Z_t from K_t and L_t (eq. zt:compute), symmetrised, laid out by position in four planes: plane 2a+b holds the
-  // entry (2 bi + a, 2 bj + b) of every 2x2 block bi <= bj, blocks numbered row by row, so that lane t of the block
-  // update reads element t of each plane (conflict-free 8-byte reads).  The padding player of an odd R has an
-  // all-zero row and column and is never rotated.
+  // entry (2 bi + a, 2 bj + b) of every 2x2 block bi <= bj.  Blocks are numbered diagonal by diagonal (first the
+  // blocks (k, k), then (k, k+1), ...): the permutation between rounds moves a block along its diagonal or to
+  // the second next one, the block waves own runs of one diagonal, and the rotation lanes need the blocks (k, k)
+  // and (k-1, k+1); with this numbering neighbouring lanes touch neighbouring addresses in all of these accesses
+  // (8-byte LDS accesses without bank conflicts).  The padding player of an odd R has an all-zero row and column
+  // and is never rotated.
   const int n_blocks = half * (half + 1) / 2;
   const int np = n_blocks;        // plane stride
   const int zcopy = 4 * np;       // offset of the second copy (offsets, not pointers: accesses stay LDS instructions)
-  auto tri = [half](int bi) { return bi * half - bi * (bi - 1) / 2; };   // number of the block (bi, bi)
+  auto diag_start = [half](int d) { return d * half - d * (d - 1) / 2; };   // number of the block (0, d)
+  auto slot = [&](int bi, int bj) { return diag_start(bj - bi) + bi; };    // number of the block (bi, bj), bi <= bj
   auto place = [&](int pa, int pb) {   // LDS offset of the entry at positions (pa, pb) within a copy
     const int lo = pa < pb ? pa : pb, hi = pa < pb ? pb : pa;
     const int bi = lo >> 1, bj = hi >> 1;
-    return (2 * (lo & 1) + (hi & 1)) * np + tri(bi) + bj - bi;
+    return (2 * (lo & 1) + (hi & 1)) * np + slot(bi, bj);
   };
   for (int idx = tid; idx < 2 * zcopy; idx += nt) dyn[idx] = 0.0;
   __syncthreads();
@@ -235,24 +239,24 @@ __global__ __launch_bounds__(NT) void eig_update_kernel(const SmallGroup g) {
   const double abs_tol = kJacobiAbsTol * zmax;
   const double abs_tol2 = abs_tol * abs_tol;
 
-  // The off-diagonal blocks (bi < bj) this thread owns (the threads after the first wavefront, row by row), where
-  // they are stored, and the (fixed) destinations of their four entries.  The diagonal blocks are handled apart
-  // (three entries, a different formula), so this path is branch-free.
+  // The off-diagonal blocks (bi < bj) this thread owns (the threads after the first wavefront, diagonal by
+  // diagonal), where they are stored, and the (fixed) destinations of their four entries.  The diagonal blocks
+  // are handled apart (three entries, a different formula), so this path is branch-free.
   const int n_off = half * (half - 1) / 2;
   int blk_i[ITEMS], blk_j[ITEMS], blk_t[ITEMS];
   int dst[ITEMS][4];
 #pragma unroll
   for (int it = 0; it < ITEMS; ++it) {
     const int item = (tid - 64) + it * (nt - 64);
-    int bi = 0, rem = (item >= 0 && item < n_off) ? item : 0;
-    while (half - 1 - bi > 0 && rem >= half - 1 - bi) {   // row bi holds the blocks (bi, bi+1), ..., (bi, half-1)
-      rem -= half - 1 - bi;
-      ++bi;
+    int d = 1, rem = (item >= 0 && item < n_off) ? item : 0;
+    while (half - d > 0 && rem >= half - d) {   // diagonal d holds the blocks (0, d), ..., (half-1-d, half-1)
+      rem -= half - d;
+      ++d;
     }
-    const int bj = bi + 1 + rem;
+    const int bi = rem, bj = min(rem + d, half - 1);   // (an idle thread of a single-pair problem: bj = bi = 0)
     blk_i[it] = bi;
     blk_j[it] = bj;
-    blk_t[it] = (item >= 0 && item < n_off) ? tri(bi) + bj - bi : -1;
+    blk_t[it] = (item >= 0 && item < n_off) ? slot(bi, bj) : -1;
 #pragma unroll
     for (int e = 0; e < 4; ++e)
       dst[it][e] = place(next_position(2 * bi + (e >> 1), half), next_position(2 * min(bj, half - 1) + (e & 1), half));
@@ -263,7 +267,7 @@ __global__ __launch_bounds__(NT) void eig_update_kernel(const SmallGroup g) {
   const bool diag_lane = diag_k >= 0 && diag_k < half;
   int diag_t = 0, diag_dst[3] = {0, 0, 0};
   if (diag_lane) {
-    diag_t = tri(diag_k);
+    diag_t = slot(diag_k, diag_k);
     diag_dst[0] = place(next_position(2 * diag_k, half), next_position(2 * diag_k, half));
     diag_dst[1] = place(next_position(2 * diag_k, half), next_position(2 * diag_k + 1, half));
     diag_dst[2] = place(next_position(2 * diag_k + 1, half), next_position(2 * diag_k + 1, half));
@@ -286,16 +290,16 @@ __global__ __launch_bounds__(NT) void eig_update_kernel(const SmallGroup g) {
     rz_pb = pb;
     rz_sa0 = sa == 0;
     rz_sb0 = sb == 0;
-    rz_blk = tri(pb) + pa - pb;
-    rz_da = tri(pa);
-    rz_db = tri(pb);
+    rz_blk = slot(pb, pa);
+    rz_da = slot(pa, pa);
+    rz_db = slot(pb, pb);
   }
   double2* __restrict__ rotlog = a.rotlog;
   if (tid < 64) __builtin_amdgcn_s_setprio(3);   // the rotation wave's dependent chain bounds the round
   if (tid < 2) s_rotated[tid] = 0;
   __syncthreads();
   if (rot_lane) {   // rotations of the very first round
-    const int t = tri(rot_k);
+    const int t = slot(rot_k, rot_k);
     double c = 1.0, s = 0.0;
     bool large = false;
     if (!(odd_pad && rot_k == 0)) jacobi_rotation(dyn[t], dyn[3 * np + t], dyn[np + t], abs_tol2, c, s, large);
