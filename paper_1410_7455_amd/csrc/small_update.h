@@ -162,7 +162,7 @@ __global__ __launch_bounds__(NT) void eig_update_kernel(const SmallGroup g) {
   extern __shared__ __attribute__((aligned(16))) double dyn[];   // two copies of Z (upper triangle, four planes)
   __shared__ double scratch[16];
   __shared__ double s_d[kMaxRank], s_ise[kMaxRank], s_dr[kMaxRank], s_c[kMaxRank + 1], s_enew[kMaxRank];
-  __shared__ double s_rc[2][kMaxHalf], s_rs[2][kMaxHalf];   // (c, s) of the pairs, this round's and the next's
+  __shared__ __attribute__((aligned(16))) double2 s_cs[2][kMaxHalf];   // (c, s) of the pairs, this round's and the next's
   __shared__ int s_perm[kMaxRank];
   __shared__ double s_scal[8];
   __shared__ int s_flag[2];
@@ -304,8 +304,7 @@ __global__ __launch_bounds__(NT) void eig_update_kernel(const SmallGroup g) {
     bool large = false;
     if (!(odd_pad && rot_k == 0)) jacobi_rotation(dyn[t], dyn[3 * np + t], dyn[np + t], abs_tol2, c, s, large);
     if (large) s_rotated[0] = 1;
-    s_rc[0][rot_k] = c;
-    s_rs[0][rot_k] = s;
+    s_cs[0][rot_k] = make_double2(c, s);
     rotlog[rot_k] = make_double2(c, s);
   }
   __syncthreads();
@@ -316,12 +315,12 @@ __global__ __launch_bounds__(NT) void eig_update_kernel(const SmallGroup g) {
   for (; sweeps < kMaxSweeps && !converged; ++sweeps) {
     for (int r = 0; r < m - 1; ++r, ++rounds, cur ^= 1) {
       const int co = cur ? zcopy : 0, no = cur ? 0 : zcopy;
-      const double* rc = s_rc[cur];
-      const double* rs = s_rs[cur];
+      const double2* cs = s_cs[cur];
       if (rot_lane) {
         double c = 1.0, s = 0.0;
         if (half >= 2 && !(odd_pad && rot_k == 0)) {
-          const double ci = rc[rz_pb], si = rs[rz_pb], cj = rc[rz_pa], sj = rs[rz_pa];
+          const double2 csi = cs[rz_pb], csj = cs[rz_pa];
+          const double ci = csi.x, si = csi.y, cj = csj.x, sj = csj.y;
           const double x00 = dyn[co + rz_blk], x01 = dyn[co + np + rz_blk];
           const double x10 = dyn[co + 2 * np + rz_blk], x11 = dyn[co + 3 * np + rz_blk];
           const double da_tt = dyn[co + rz_da], da_tb = dyn[co + np + rz_da], da_bb = dyn[co + 3 * np + rz_da];
@@ -338,12 +337,12 @@ __global__ __launch_bounds__(NT) void eig_update_kernel(const SmallGroup g) {
           jacobi_rotation(zaa, zbb, zab, abs_tol2, c, s, large);
           if (large) s_rotated[(sweeps + (r == m - 2 ? 1 : 0)) & 1] = 1;
         }
-        s_rc[cur ^ 1][rot_k] = c;
-        s_rs[cur ^ 1][rot_k] = s;
+        s_cs[cur ^ 1][rot_k] = make_double2(c, s);
         rotlog[(size_t)(rounds + 1) * half + rot_k] = make_double2(c, s);
       }
       if (diag_lane) {   // this round's rotation of pair diag_k, applied to its diagonal block
-        const double ck = rc[diag_k], sk = rs[diag_k];
+        const double2 csk = cs[diag_k];
+        const double ck = csk.x, sk = csk.y;
         const double att = dyn[co + diag_t], atb = dyn[co + np + diag_t], abb = dyn[co + 3 * np + diag_t];
         dyn[no + diag_dst[0]] = ck * ck * att - 2.0 * ck * sk * atb + sk * sk * abb;
         dyn[no + diag_dst[2]] = sk * sk * att + 2.0 * ck * sk * atb + ck * ck * abb;
@@ -354,7 +353,8 @@ __global__ __launch_bounds__(NT) void eig_update_kernel(const SmallGroup g) {
         const int t = blk_t[it];
         if (t < 0) continue;
         const int bi = blk_i[it], bj = blk_j[it];
-        const double ci = rc[bi], si = rs[bi], cj = rc[bj], sj = rs[bj];
+        const double2 csi = cs[bi], csj = cs[bj];
+        const double ci = csi.x, si = csi.y, cj = csj.x, sj = csj.y;
         const double x00 = dyn[co + t], x01 = dyn[co + np + t], x10 = dyn[co + 2 * np + t], x11 = dyn[co + 3 * np + t];
         const double y00 = ci * x00 - si * x10, y01 = ci * x01 - si * x11;
         const double y10 = si * x00 + ci * x10, y11 = si * x01 + ci * x11;
