@@ -427,7 +427,7 @@ __global__ __launch_bounds__(256) void init_rows_kernel(const InitGroup* __restr
   if (i >= a.R) return;
   const int col = blockIdx.x * 64 + (threadIdx.x & 63);
   const int part = threadIdx.x >> 6;   // 4 slices of the row range
-  if (blockIdx.x * 64 >= a.ldw) return;
+  if ((int)blockIdx.x * 64 >= a.ldw) return;
   __shared__ double s_acc[4][64];
   const int src_col = a.idx[i];
   const double* V = a.V;

@@ -74,6 +74,7 @@ __global__ void fill_zero_group_kernel(const FillGroup g) {
 __global__ void copy_append_ones_kernel(const float* __restrict__ x, int ldx, float* __restrict__ out, int ldo,
                                         int N, int D, double* __restrict__ clear) {
   const int row = blockIdx.y;
+  if (row >= N) return;   // the grid's second dimension is the row count
   if (clear != nullptr && row == 0 && blockIdx.x == 0 && threadIdx.x == 0) *clear = 0.0;
   for (int c = blockIdx.x * blockDim.x + threadIdx.x; c < ldo; c += gridDim.x * blockDim.x)
     out[(size_t)row * ldo + c] = c < D ? x[(size_t)row * ldx + c] : (c == D ? 1.f : 0.f);
@@ -83,6 +84,7 @@ __global__ void copy_append_ones_kernel(const float* __restrict__ x, int ldx, fl
 __global__ void copy2d_kernel(const float* __restrict__ src, int lds_, float* __restrict__ dst, int ldd, int rows,
                               int cols, float scale, const double* scale_dev) {
   const int row = blockIdx.y;
+  if (row >= rows) return;   // the grid's second dimension is the row count
   float s = scale;
   if (scale_dev != nullptr) s *= (float)(*scale_dev);
   for (int c = blockIdx.x * blockDim.x + threadIdx.x; c < cols; c += gridDim.x * blockDim.x)
@@ -91,6 +93,7 @@ __global__ void copy2d_kernel(const float* __restrict__ src, int lds_, float* __
 
 __global__ void scale_rows_kernel(float* __restrict__ M, int ld, int N, int D, const double* __restrict__ gamma) {
   const int row = blockIdx.y;
+  if (row >= N) return;   // the grid's second dimension is the row count
   const float s = (float)(*gamma);
   for (int c = blockIdx.x * blockDim.x + threadIdx.x; c < D; c += gridDim.x * blockDim.x)
     M[(size_t)row * ld + c] *= s;
@@ -101,6 +104,7 @@ __global__ void scale_rows_kernel(float* __restrict__ M, int ld, int N, int D, c
 __global__ void tanh_forward_kernel(const float* __restrict__ A, int lda, float* __restrict__ Y, int ldy, int N,
                                     int D) {
   const int row = blockIdx.y;
+  if (row >= N) return;   // the grid's second dimension is the row count
   for (int c = blockIdx.x * blockDim.x + threadIdx.x; c < ldy; c += gridDim.x * blockDim.x)
     Y[(size_t)row * ldy + c] = c < D ? tanhf(A[(size_t)row * lda + c]) : (c == D ? 1.f : 0.f);
 }
@@ -118,6 +122,7 @@ __global__ void tanh_backward_kernel(const float* __restrict__ dY, int ldd, int 
                                      const float* __restrict__ Y, int ldy, float* __restrict__ O, int ldo, int N,
                                      int D) {
   const int row = blockIdx.y;
+  if (row >= N) return;   // the grid's second dimension is the row count
   for (int c = blockIdx.x * blockDim.x + threadIdx.x; c < D; c += gridDim.x * blockDim.x) {
     const float y = Y[(size_t)row * ldy + c];
     O[(size_t)row * ldo + c] = slab_sum(dY + (size_t)row * ldd + c, n_slabs, slab_stride) * (1.f - y * y);
@@ -162,6 +167,7 @@ __global__ __launch_bounds__(NT) void pnorm_forward_kernel(const float* __restri
                                                             int renorm) {
   __shared__ float red[NT / 64];
   const int row = blockIdx.x;
+  if (row >= N) return;   // one workgroup per row (uniform over the workgroup)
   const float* a = A + (size_t)row * lda;
   float* y = Y + (size_t)row * ldy;
   float ss = 0.f;
@@ -226,6 +232,7 @@ __global__ __launch_bounds__(NT) void pnorm_backward_kernel(const float* __restr
   __shared__ float red[NT / 64];
   __shared__ float s_f[kPnormMaxGroupsLds];   // first dy_j, then the factor dy_j / y_j
   const int row = blockIdx.x;
+  if (row >= N) return;   // one workgroup per row (uniform over the workgroup)
   const float* dy = dYn + (size_t)row * ldd;
   const float* yn = Yn + (size_t)row * ldy;
   float* ao = AO + (size_t)row * lda;
@@ -295,6 +302,7 @@ __global__ __launch_bounds__(NT) void softmax_xent_kernel(float* __restrict__ AO
   constexpr int kSoftmaxVec = kSoftmaxRowVec / NT;   // float4 per thread
   __shared__ float red[NT / 64];
   const int row = blockIdx.x;
+  if (row >= N) return;   // one workgroup per row (uniform over the workgroup)
   float* a = AO + (size_t)row * ld;
   const int y = labels[row];
   const bool valid = y >= 0 && y < C;        // an out-of-range label yields NaN, never an out-of-bounds access

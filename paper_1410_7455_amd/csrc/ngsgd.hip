@@ -237,15 +237,6 @@ int ensure_kernel_attributes() {
   return NGSGD_OK;
 }
 
-int fill_zero(void* p, size_t n_u32, hipStream_t s) {
-  if (n_u32 == 0) return NGSGD_OK;
-  size_t blocks = (n_u32 + 256 * 8 - 1) / (256 * 8);
-  if (blocks > 2048) blocks = 2048;
-  hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)blocks), dim3(256), 0, s, static_cast<uint32_t*>(p), n_u32, 0u);
-  LAUNCH_CHECK();
-  return NGSGD_OK;
-}
-
 inline int choose_splits(int tiles, int ksteps) {
   int s = kTargetBlocks / (tiles > 0 ? tiles : 1);
   if (s < 1) s = 1;
