@@ -477,7 +477,11 @@ int clear_accumulators(const std::vector<PrecondCall>& list, hipStream_t s) {
 int launch_h_products(std::vector<PrecondCall>& list, hipStream_t s) {
   if (list.empty()) return NGSGD_OK;
   int rc = 0;
-  for (auto& c : list) rc = std::max(rc, c.p->ldh);
+  int class_count[3] = {0, 0, 0};   // the split of an instance is chosen for the instances of its own rank class:
+  for (auto& c : list) {            // they carry comparable work, the narrower classes add little to the launch
+    rc = std::max(rc, c.p->ldh);
+    class_count[c.p->ldh == 32 ? 0 : (c.p->ldh == 80 ? 1 : 2)] += 1;
+  }
   std::vector<GemmDesc> d;
   for (auto& c : list) {
     ngsgd_precond& p = *c.p;
@@ -487,7 +491,7 @@ int launch_h_products(std::vector<PrecondCall>& list, hipStream_t s) {
     g.C = p.H; g.ldc = p.ldh;
     g.M = c.N; g.N = p.rank; g.K = p.dim;
     g.sumsq = p.sumsq_part;
-    g.splits = h_splits(c.N, p.dim, (int)list.size());
+    g.splits = h_splits(c.N, p.dim, class_count[p.ldh == 32 ? 0 : (p.ldh == 80 ? 1 : 2)]);
     p.last_N = c.N;
     {
       GemmDesc hd = g;
