@@ -369,7 +369,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmGroup g) 
   constexpr bool SUB = EPI == EPI_SUB_ROWNORM;
   constexpr bool SUB_V2 = SUB && !B_KC && TN == 2;
   float c_old[SUB ? TM : 1][SUB ? 4 : 1][SUB ? TN : 1];
-  if (SUB) {
+  auto request_c_old = [&]() {
     const float* C = static_cast<const float*>(P.C);
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -389,7 +389,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmGroup g) 
           }
         }
       }
-  }
+  };
 
   float* const As = lds;                             // two buffers of StageA::LDS_FLOATS
   float* const Bs = lds + 2 * StageA::LDS_FLOATS;    // two buffers of StageB::LDS_FLOATS
@@ -443,11 +443,13 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmGroup g) 
   };
   if (nk > 0) {
     fetch(0, 0);
+    if (SUB) request_c_old();   // behind the first operand block: the K loop starts while the tile of C streams in
     commit(0, 0, 0);
 #pragma unroll
     for (int u = 0; u < PF; ++u)
       if (1 + u < nk) fetch(1 + u, u);
   }
+  if (SUB && nk <= 0) request_c_old();
   __syncthreads();
   // one K-block: multiply block i out of LDS, then pass block i+1 from register set u to LDS and refill the set
   auto block_step = [&](const int i, const int u, const bool steady) {
