@@ -243,6 +243,35 @@ def test_step_argument_errors(ngsgd):
     torch.cuda.synchronize()
 
 
+def test_kernel_group_timing(ngsgd):
+    """The event brackets of ngsgd_profile_*: categories and launch counts of a step, and the error that a read
+    returns when more launch groups ran than the library keeps (instead of sums that silently miss some)."""
+    import torch
+    spec = workloads.c0_tiny()
+    _, gpu = make_pair(ngsgd, spec)
+    x, y = workloads.minibatch(spec, 0)
+    x, y = torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda()
+    out = torch.zeros(1, dtype=torch.float64, device="cuda")
+    for _ in range(12):                      # past the always-update phase
+        gpu.step(x, y, spec.lr, out)
+    ngsgd.profile_enable(True)
+    gpu.step(x, y, spec.lr, out)             # t = 12: an update step
+    gpu.step(x, y, spec.lr, out)             # t = 13: apply only
+    gpu.join()
+    prof = ngsgd.profile_read()
+    assert prof["gemm_fwd"][1] == 2 * spec.n_layers and prof["gemm_bwd"][1] == 2 * (spec.n_layers - 1)
+    assert prof["precond_small"][1] >= 1 and prof["precond_xhat"][1] >= 2
+    assert all(ms >= 0.0 for ms, _ in prof.values()) and prof["gemm_fwd"][0] > 0.0
+    assert sum(c for _, c in ngsgd.profile_read().values()) == 0          # a read clears the record
+    for _ in range(2000):                    # about 20 groups per step: more than the 32768 the library keeps
+        gpu.step(x, y, spec.lr, out)
+    gpu.join()
+    with pytest.raises(ngsgd.NgsgdError):
+        ngsgd.profile_read()
+    ngsgd.profile_enable(False)
+    torch.cuda.synchronize()
+
+
 def test_average_replicas(ngsgd):
     """Sec. 3.1: every replica ends with the arithmetic mean; preconditioners restart as new processes do."""
     import torch
