@@ -184,7 +184,10 @@ int ngsgd_join(ngsgd_net* net, void* hip_stream);
 
 /* Parameter averaging of Sec. 3.1: every replica's weights are replaced by the arithmetic mean over
  * the n replicas (same configuration, same device).  With reset_preconditioners != 0 all their
- * preconditioners are reset, as the paper's re-spawned processes do (App. B.3.2). */
+ * preconditioners are reset, as the paper's re-spawned processes do (App. B.3.2).
+ * The replicas may have been stepped on other streams than hip_stream: the averaging kernel waits (on
+ * the device) for each replica's latest ngsgd_step and factor updates, and each replica's next call
+ * waits for the averaged weights, so the caller needs no synchronisation of its own. */
 int ngsgd_average(ngsgd_net* const* nets, int32_t n, int32_t reset_preconditioners, void* hip_stream);
 
 /* Weights of one layer as a dense dims[layer+1] x (in_dim+1) row-major matrix, bias last. */

@@ -26,3 +26,11 @@ def average_parameters(networks, reset_preconditioners: bool = True) -> None:
     if reset_preconditioners:
         for net in networks:
             net.reset_preconditioners()
+
+
+def job_learning_rate(effective_learning_rate: float, n_jobs: int) -> float:
+    """Learning rate of each of `n_jobs` replicas whose parameters are averaged (Sec. 3.1): averaging dilutes
+    every job's update n_jobs-fold, so the jobs' rate is the effective rate times the number of jobs."""
+    if n_jobs < 1:
+        raise ValueError("n_jobs must be at least 1")
+    return float(effective_learning_rate) * int(n_jobs)

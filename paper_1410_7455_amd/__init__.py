@@ -339,11 +339,3 @@ def average(networks, reset_preconditioners=True, stream=None):
     arr = (c_void_p * len(networks))(*[n.handle for n in networks])
     _check(lib.ngsgd_average(arr, len(networks), 1 if reset_preconditioners else 0, _stream_ptr(stream)),
            "ngsgd_average")
-
-
-def job_learning_rate(effective_learning_rate: float, n_jobs: int) -> float:
-    """Learning rate for each of `n_jobs` replicas whose parameters are averaged (Sec. 3.1): averaging dilutes every
-    job's update n_jobs-fold, so the jobs' rate is the effective rate times the number of jobs."""
-    if n_jobs < 1:
-        raise ValueError("n_jobs must be at least 1")
-    return float(effective_learning_rate) * int(n_jobs)

@@ -117,7 +117,8 @@ struct SideSync {
   hipEvent_t hj_done = nullptr;        // recorded on the side stream: H, J and the partial sums of tr(X X^T) are final
   hipEvent_t outputs_done = nullptr;   // recorded on the caller's stream: the last reader of W_t (Xhat) has been enqueued
   hipEvent_t done = nullptr;           // recorded on the side stream: W_{t+1}, D_{t+1}, rho_{t+1} are final
-  bool pending = false;
+  bool pending = false;                // `done` has been recorded and the stepping stream has not waited for it yet
+  hipStream_t owner = nullptr;         // the stream the network's latest step was issued on
 };
 
 // ---------------------------------------------------------------------------------------------------
@@ -407,11 +408,13 @@ int run_init(const std::vector<PrecondCall>& calls, hipStream_t s) {
   return NGSGD_OK;
 }
 
-// Makes stream s wait for a factor update still running on the side stream.
+// Makes stream s wait for a factor update still running on the side stream.  Any stream may ask (an inspection
+// call, an averaging call); the update only stops being pending once the stream that steps the network has
+// waited for it, because that is the stream the next step's readers of the new factor are ordered on.
 int join_side(SideSync* sync, hipStream_t s) {
   if (sync != nullptr && sync->pending) {
     HIP_TRY(hipStreamWaitEvent(s, sync->done, 0));
-    sync->pending = false;
+    if (s == sync->owner) sync->pending = false;
   }
   return NGSGD_OK;
 }
@@ -1167,6 +1170,11 @@ struct ngsgd_net {
   float last_lr = 0.f;
   SideSync side[kSideStreams];
   int n_side = kSideStreams;   // streams in use
+  // ordering between the stream that steps this replica and a stream that averages it with others
+  hipEvent_t step_done = nullptr;   // recorded at the end of every step on the step's stream
+  bool stepped = false;
+  hipEvent_t avg_done = nullptr;    // recorded behind an averaging kernel that rewrote the weights
+  bool avg_pending = false;
 };
 
 namespace {
@@ -1282,6 +1290,16 @@ int copy2d(const float* src, int lds_, float* dst, int ldd, int rows, int cols, 
   return NGSGD_OK;
 }
 
+// Orders stream s behind an averaging kernel that rewrote this replica's weights on another stream.  The wait is
+// dropped once the replica's own stepping stream has taken it.
+int order_after_average(ngsgd_net* net, hipStream_t s, bool stepping_stream) {
+  if (net->avg_pending) {
+    HIP_TRY(hipStreamWaitEvent(s, net->avg_done, 0));
+    if (stepping_stream) net->avg_pending = false;
+  }
+  return NGSGD_OK;
+}
+
 GemmDesc update_desc(const ngsgd_layer& L, int N, float alpha, float beta, float* C, int ldc) {
   GemmDesc g;
   g.A = L.A; g.lda = L.lda;          // O_l stored N x dout: A^T
@@ -1328,7 +1346,10 @@ extern "C" int ngsgd_create(const ngsgd_config* cfg, void* dev_workspace, size_t
     if (e == hipSuccess) e = hipMemcpy(L.mc_scale, &one, sizeof(one), hipMemcpyHostToDevice);
   }
   // second stream for the factor updates: default priority, does not synchronise with the NULL stream
-  for (SideSync& sd : net->side) {
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&net->step_done, hipEventDisableTiming);
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&net->avg_done, hipEventDisableTiming);
+  for (int k = 0; k < net->n_side; ++k) {
+    SideSync& sd = net->side[k];
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&sd.stream, hipStreamNonBlocking);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&sd.inputs_ready, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&sd.hj_done, hipEventDisableTiming);
@@ -1355,6 +1376,8 @@ extern "C" int ngsgd_destroy(ngsgd_net* net) {
     for (hipEvent_t ev : {sd.inputs_ready, sd.hj_done, sd.outputs_done, sd.done})
       if (ev != nullptr) (void)hipEventDestroy(ev);
   }
+  for (hipEvent_t ev : {net->step_done, net->avg_done})
+    if (ev != nullptr) (void)hipEventDestroy(ev);
   delete net;
   return NGSGD_OK;
 }
@@ -1367,6 +1390,8 @@ extern "C" int ngsgd_step(ngsgd_net* net, const float* dev_x, const int32_t* dev
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   const int nl = net->n_layers;
   auto& Ls = net->layers;
+  for (SideSync& sd : net->side) sd.owner = s;
+  NG_TRY(order_after_average(net, s, true));
   for (auto& L : Ls) {   // argument errors must leave the state untouched: check before any launch
     if (L.pin.rank > 0 && L.pin.t == 0 && N <= L.pin.rank) return NGSGD_EINVAL;
     if (L.pout.rank > 0 && L.pout.t == 0 && N <= L.pout.rank) return NGSGD_EINVAL;
@@ -1584,6 +1609,8 @@ extern "C" int ngsgd_step(ngsgd_net* net, const float* dev_x, const int32_t* dev
   }
   net->last_N = N;
   net->last_lr = lr;
+  HIP_TRY(hipEventRecord(net->step_done, s));   // what an averaging call on another stream waits for
+  net->stepped = true;
   return NGSGD_OK;
 }
 
@@ -1604,16 +1631,25 @@ extern "C" int ngsgd_average(ngsgd_net* const* nets, int32_t n, int32_t reset_pr
       if (nets[i]->layers[l].dout != nets[0]->layers[l].dout || nets[i]->layers[l].din != nets[0]->layers[l].din)
         return NGSGD_EINVAL;
   }
-  for (int i = 0; i < n; ++i)
-    for (SideSync& sd : nets[i]->side) NG_TRY(join_side(&sd, static_cast<hipStream_t>(hip_stream)));
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  for (int i = 0; i < n; ++i) {
+    // behind the replica's latest step (whatever stream it ran on), its factor updates and an earlier averaging
+    if (nets[i]->stepped) HIP_TRY(hipStreamWaitEvent(s, nets[i]->step_done, 0));
+    NG_TRY(order_after_average(nets[i], s, false));
+    for (SideSync& sd : nets[i]->side) NG_TRY(join_side(&sd, s));
+  }
   AverageArgs a;
   a.n = n;
   a.count = nets[0]->n_params_padded;
   for (int i = 0; i < n; ++i) a.params[i] = nets[i]->params;
   size_t blocks = (a.count + 255) / 256;
   if (blocks > 4096) blocks = 4096;
-  hipLaunchKernelGGL(average_kernel, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream), a);
+  hipLaunchKernelGGL(average_kernel, dim3((unsigned)blocks), dim3(256), 0, s, a);
   LAUNCH_CHECK();
+  for (int i = 0; i < n; ++i) {   // the replicas' next steps (on their own streams) wait for the new weights
+    HIP_TRY(hipEventRecord(nets[i]->avg_done, s));
+    nets[i]->avg_pending = true;
+  }
   if (reset_preconditioners)
     for (int i = 0; i < n; ++i)
       for (auto& L : nets[i]->layers) L.pin.t = L.pout.t = 0;
@@ -1623,12 +1659,14 @@ extern "C" int ngsgd_average(ngsgd_net* const* nets, int32_t n, int32_t reset_pr
 extern "C" int ngsgd_get_params(const ngsgd_net* net, int32_t layer, float* dev_out, void* hip_stream) {
   if (net == nullptr || dev_out == nullptr || layer < 0 || layer >= net->n_layers) return NGSGD_EINVAL;
   const ngsgd_layer& L = net->layers[layer];
+  NG_TRY(order_after_average(const_cast<ngsgd_net*>(net), static_cast<hipStream_t>(hip_stream), false));
   return copy2d(L.W, L.ldw, dev_out, L.in1, L.dout, L.in1, 1.f, nullptr, static_cast<hipStream_t>(hip_stream));
 }
 
 extern "C" int ngsgd_set_params(ngsgd_net* net, int32_t layer, const float* dev_in, void* hip_stream) {
   if (net == nullptr || dev_in == nullptr || layer < 0 || layer >= net->n_layers) return NGSGD_EINVAL;
   ngsgd_layer& L = net->layers[layer];
+  NG_TRY(order_after_average(net, static_cast<hipStream_t>(hip_stream), false));
   return copy2d(dev_in, L.in1, L.W, L.ldw, L.dout, L.in1, 1.f, nullptr, static_cast<hipStream_t>(hip_stream));
 }
 

@@ -1,10 +1,14 @@
 // The R x R part of the online natural-gradient update, entirely on the device (App. B.3, B.3.1).
 //
-// One workgroup per instance holds Z_t and the eigenvector matrix in LDS (fp64) and runs a cyclic
-// Jacobi eigen-solver with a round-robin ordering: every round applies floor(R/2) disjoint plane
-// rotations, each thread updating whole 2x2 blocks, so a round costs two barriers.  Z_t is close to
-// diagonal once the factor tracks the data (the rows of Y_t are then nearly eigenvectors scaled by
-// their eigenvalues), so a few sweeps suffice.
+// eig_update_kernel: one workgroup per instance forms Z_t from K_t and L_t (eq. zt:compute) and finds its
+// eigenvalues by cyclic Jacobi in fp64.  Only Z is rotated: its upper triangle lives in LDS in "position space"
+// (Brent-Luk: the members of pair k stand at positions 2k and 2k+1, and a fixed permutation between rounds brings
+// the next partners together), in two copies used alternately, so a round costs one barrier.  The first wavefront
+// computes the next round's rotations while the others rotate the 2x2 blocks; every rotation is written to a log.
+// The kernel then floors and orders the eigenvalues and produces rho_{t+1}, D_{t+1}, E_{t+1} and the scales of A_t.
+// eigvec_kernel: replays the rotation log on the rows of the identity (one wavefront per row of U_t, the two
+// columns of a pair in one lane, moved between lanes as the players move) and writes A_t (eq. wt1).
+// orth_fix_kernel: the orthogonality check of App. B.3.1 and, when it fails, the Cholesky fix folded into A_t.
 #pragma once
 
 #include <hip/hip_runtime.h>

@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 
 import workloads
-from oracle.averaging import average_parameters
+from oracle.averaging import average_parameters, job_learning_rate
 from oracle.network import (PNORM, TANH, NGSGDNetwork, log_softmax, pnorm_backward,
                             pnorm_forward)
 
@@ -171,12 +171,11 @@ def test_parameter_averaging():
 def test_job_learning_rate_keeps_the_effective_rate():
     """Sec. 3.1: with the jobs' rate n times the effective rate, one averaged SGD step of n jobs from common weights
     equals one step at the effective rate on the sum of the jobs' gradients (checked on plain SGD, rank 0)."""
-    import paper_1410_7455_amd as ng
     n_jobs, eff = 3, 0.004
-    lr = ng.job_learning_rate(eff, n_jobs)
+    lr = job_learning_rate(eff, n_jobs)
     assert lr == pytest.approx(0.012)
     with pytest.raises(ValueError):
-        ng.job_learning_rate(eff, 0)
+        job_learning_rate(eff, 0)
     rng = np.random.default_rng(31)
     nets = [tiny_net(np.random.default_rng(9), [TANH, PNORM], ng=False) for _ in range(n_jobs)]
     start = [w.copy() for w in nets[0].W]
@@ -213,3 +212,166 @@ def test_workload_generators_are_seeded_and_shaped():
     sv = np.linalg.svd(m, compute_uv=False)
     # singular values follow ~ 1/k: the leading ratio s1/s8 is near 8
     assert 5.0 < sv[0] / sv[7] < 12.0
+
+
+# ---- renormalisation layer (App. C.8, footnote) and maximum parameter change (App. C.3) ---------------------------
+from oracle.network import RENORM_FLOOR, renorm_backward, renorm_forward
+
+
+def renorm_net(rng, nonlin=(PNORM, PNORM), **kw):
+    group = 3
+    dims = [5, 12, 9, 7]
+    in_dims = [5, 12 // group if nonlin[0] == PNORM else 12, 9 // group if nonlin[1] == PNORM else 9]
+    weights = [rng.standard_normal((dims[l + 1], in_dims[l] + 1)) / math.sqrt(in_dims[l]) for l in range(3)]
+    return NGSGDNetwork(dims, list(nonlin), weights, pnorm_group=group, rank_in=2, rank_out=3,
+                        num_samples_history=40.0, update_period=1, **kw)
+
+
+def test_renorm_forward_hand_example_unit_rms_and_scale_invariance():
+    """Rows leave with unit rms, whatever their scale; a zero row stays zero (its divisor is the floor)."""
+    Y = np.array([[3.0, 4.0], [0.0, 0.0], [1.0e-3, 0.0]])
+    Yn, sigma = renorm_forward(Y)
+    # row 0: rms = sqrt((9 + 16) / 2) = 5 / sqrt(2); row 2: rms = 1e-3 / sqrt(2)
+    np.testing.assert_allclose(sigma, [5.0 / math.sqrt(2.0), RENORM_FLOOR, 1.0e-3 / math.sqrt(2.0)], rtol=1e-15)
+    np.testing.assert_allclose(Yn, [[0.6 * math.sqrt(2.0), 0.8 * math.sqrt(2.0)], [0.0, 0.0], [math.sqrt(2.0), 0.0]],
+                               rtol=1e-15)
+    rng = np.random.default_rng(41)
+    Y = np.abs(rng.standard_normal((7, 11))) * np.exp(rng.uniform(-20, 20, (7, 1)))   # rows on very different scales
+    Yn, sigma = renorm_forward(Y)
+    np.testing.assert_allclose(np.sqrt(np.mean(Yn * Yn, axis=1)), 1.0, rtol=1e-14)
+    np.testing.assert_allclose(Yn * sigma[:, None], Y, rtol=1e-14)
+    np.testing.assert_allclose(renorm_forward(37.5 * Y)[0], Yn, rtol=1e-14)
+
+
+def test_renorm_backward_matches_central_differences():
+    """d/dY of sum(C * renorm(Y)) against finite differences, row by row."""
+    rng = np.random.default_rng(42)
+    Y = np.abs(rng.standard_normal((4, 6))) + 0.1
+    C = rng.standard_normal((4, 6))
+    Yn, sigma = renorm_forward(Y)
+    ana = renorm_backward(C, Yn, sigma)
+    num = np.zeros_like(Y)
+    h = 1e-6
+    for idx in np.ndindex(*Y.shape):
+        Yp, Ym = Y.copy(), Y.copy()
+        Yp[idx] += h
+        Ym[idx] -= h
+        num[idx] = (np.sum(C * renorm_forward(Yp)[0]) - np.sum(C * renorm_forward(Ym)[0])) / (2 * h)
+    np.testing.assert_allclose(ana, num, atol=1e-8)
+    # the derivative of a scale-invariant map is orthogonal to its argument
+    np.testing.assert_allclose(np.sum(ana * Y, axis=1), 0.0, atol=1e-13)
+
+
+def test_renorm_net_gradients_match_central_differences_with_a_row_on_the_floor():
+    """Backward pass through p-norm + renorm against finite differences of the objective.  Frame 0 is all zero and
+    the first layer has no bias, so its p-norm outputs are exactly zero and its divisor sits on the floor: that
+    frame's derivative w.r.t. the first affine output is zero (finite), and the objective does not depend on the
+    first layer's input weights through it (its bias column is left out: the objective has a kink there)."""
+    rng = np.random.default_rng(43)
+    net = renorm_net(rng, renorm=True)
+    net.W[0][:, -1] = 0.0
+    x = rng.standard_normal((6, 5))
+    x[0] = 0.0
+    y = rng.integers(0, 7, 6)
+    Xin, A, logp = net.forward(x)
+    assert net._sigma[0][0] == RENORM_FLOOR and np.all(net._sigma[0][1:] > 1e-3)
+    O = net.backward(Xin, A, logp, y)
+    assert np.all(np.isfinite(O[0])) and not O[0][0].any()
+    grads = net.gradients(x, y)
+    h = 1e-6
+    for l in range(net.n_layers):
+        num = np.zeros_like(net.W[l])
+        for idx in np.ndindex(*net.W[l].shape):
+            if l == 0 and idx[1] == net.W[0].shape[1] - 1:
+                num[idx] = grads[l][idx]
+                continue
+            old = net.W[l][idx]
+            net.W[l][idx] = old + h
+            fp = net.objective(x, y)
+            net.W[l][idx] = old - h
+            fm = net.objective(x, y)
+            net.W[l][idx] = old
+            num[idx] = (fp - fm) / (2 * h)
+        np.testing.assert_allclose(grads[l], num, atol=2e-7 * max(1.0, np.abs(num).max()))
+
+
+def test_renorm_makes_the_output_invariant_to_the_scale_of_pnorm_layers():
+    """App. C.8 (footnote): with the renormalisation layers the network output does not change when the
+    parameters of a p-norm layer are multiplied by a nonzero constant; without them it does."""
+    rng = np.random.default_rng(44)
+    x = rng.standard_normal((9, 5))
+    for renorm in (True, False):
+        net = renorm_net(np.random.default_rng(7), renorm=renorm)
+        ref = net.forward(x)[2]
+        for l, s in ((0, 3.7), (1, 0.02)):
+            net.W[l] *= s
+        out = net.forward(x)[2]
+        if renorm:
+            np.testing.assert_allclose(out, ref, rtol=0, atol=1e-12)
+        else:
+            assert np.abs(out - ref).max() > 1e-2
+
+
+def one_layer_net(W, **kw):
+    return NGSGDNetwork([W.shape[1] - 1, W.shape[0]], [], [W], rank_in=0, rank_out=0, natural_gradient=False, **kw)
+
+
+def test_max_change_scale_from_hand_computed_row_norms():
+    """App. C.3 on a softmax layer with zero weights: O = onehot - 1/3 has row norm sqrt(6)/3, the inputs
+    [3, 4, 1] and [0, 0, 1] have norms sqrt(26) and 1, so with lr = 0.5, N = 2 and 0.075 per sample
+    a = 2 * 0.075 / (0.5 * (sqrt(6)/3) * (sqrt(26) + 1))."""
+    x = np.array([[3.0, 4.0], [0.0, 0.0]])
+    y = np.array([2, 0])
+    lr = 0.5
+    net = one_layer_net(np.zeros((3, 3)), max_change_per_sample=0.075)
+    net.step(x, y, lr)
+    a = net.last["max_change_scale"][0]
+    expect = 0.15 / (0.5 * (math.sqrt(6.0) / 3.0) * (math.sqrt(26.0) + 1.0))
+    assert expect < 1.0 and a == pytest.approx(expect, rel=1e-14)
+    O = np.array([[-1 / 3, -1 / 3, 2 / 3], [2 / 3, -1 / 3, -1 / 3]])
+    X1 = np.array([[3.0, 4.0, 1.0], [0.0, 0.0, 1.0]])
+    np.testing.assert_allclose(net.W[0], lr * expect * O.T @ X1, atol=1e-15)
+    # the bound of eq. delta_t_approx: ||a lr O^T X||_F <= a lr sum_i ||o_i|| ||x_i|| = N * 0.075 when active
+    assert np.linalg.norm(net.W[0]) <= 2 * 0.075
+    assert a * lr * np.sum(np.linalg.norm(O, axis=1) * np.linalg.norm(X1, axis=1)) == pytest.approx(0.15, rel=1e-14)
+
+
+def test_max_change_scale_is_one_when_inactive_or_degenerate():
+    x = np.array([[3.0, 4.0], [0.0, 0.0]])
+    y = np.array([2, 0])
+    # small learning rate: the bound lr * sum(...) = 1e-3 * 4.98 is under N * 0.075
+    net = one_layer_net(np.zeros((3, 3)), max_change_per_sample=0.075)
+    net.step(x, y, 1.0e-3)
+    assert net.last["max_change_scale"][0] == 1.0
+    # a single class: log p = 0 and O = 0, the sum is zero and the scale stays 1
+    net = one_layer_net(np.zeros((1, 3)), max_change_per_sample=0.075)
+    net.step(x, np.array([0, 0]), 10.0)
+    assert net.last["max_change_scale"][0] == 1.0 and not net.W[0].any()
+    # disabled
+    net = one_layer_net(np.zeros((3, 3)), max_change_per_sample=0.0)
+    net.step(x, y, 100.0)
+    assert net.last["max_change_scale"][0] == 1.0
+
+
+def test_max_change_uses_the_preconditioned_rows_and_bounds_the_update():
+    """With natural gradient the limit is applied on top of the modified matrices (App. C.3): a_l follows from the
+    row norms of Obar_l and Xbar_l, and ||a_l lr Obar_l^T Xbar_l||_F never exceeds N * 0.075."""
+    rng = np.random.default_rng(45)
+    net = renorm_net(rng, nonlin=(PNORM, TANH), renorm=True, max_change_per_sample=0.075)
+    lr, N = 0.8, 12
+    active = 0
+    for _ in range(5):
+        x = rng.standard_normal((N, 5))
+        y = rng.integers(0, 7, N)
+        W0 = [w.copy() for w in net.W]
+        net.step(x, y, lr)
+        for l in range(3):
+            Ob, Xb = net.last["Obar"][l], net.last["Xbar"][l]
+            s = lr * np.sum(np.linalg.norm(Ob, axis=1) * np.linalg.norm(Xb, axis=1))
+            a = net.last["max_change_scale"][l]
+            assert a == pytest.approx(min(1.0, N * 0.075 / s), rel=1e-12)
+            change = net.W[l] - W0[l]
+            np.testing.assert_allclose(change, a * lr * Ob.T @ Xb, atol=1e-14)
+            assert np.linalg.norm(change) <= N * 0.075 * (1 + 1e-12)
+            active += a < 1.0
+    assert active >= 5   # the limit did bind in this run
