@@ -159,6 +159,20 @@ int ngsgd_precondition_simple(float* dev_M, int32_t N, int32_t D, int32_t ld, fl
                               void* dev_workspace, size_t workspace_bytes, float* dev_gamma,
                               float* dev_rownorm2, void* hip_stream);
 
+/* The same call for callers that cannot allocate device memory or bring a workspace (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): the scratch is a fixed array of
+ * NGSGD_SIMPLE_STATIC_BYTES in the library's device image, one copy per GPU, held until the process
+ * ends.  Allocates nothing, on the device or through any library.  Same arguments, results and
+ * errors as ngsgd_precondition_simple; in addition NGSGD_ENOMEM when
+ * ngsgd_simple_workspace_bytes(N, D) exceeds NGSGD_SIMPLE_STATIC_BYTES (16 MiB: up to 512 x 5000, or
+ * any shape whose scratch fits), before anything is enqueued.  All calls on one GPU share the array:
+ * calls that overlap in time on the same GPU (different streams, different threads) race; issue them
+ * on one stream or order them yourself.  Must be called with the target device current. */
+#define NGSGD_SIMPLE_STATIC_BYTES (16 * 1024 * 1024)
+int ngsgd_precondition_simple_static(float* dev_M, int32_t N, int32_t D, int32_t ld, float alpha,
+                                     float epsilon, float* dev_gamma, float* dev_rownorm2,
+                                     void* hip_stream);
+
 /* ---- one replica of the network -------------------------------------------------------------- */
 
 int ngsgd_workspace_bytes(const ngsgd_config* cfg, size_t* out_bytes);

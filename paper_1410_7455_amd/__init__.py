@@ -63,6 +63,8 @@ _SIGNATURES = {
     "ngsgd_simple_workspace_bytes": (c_int, [c_int32, c_int32, POINTER(c_size_t)]),
     "ngsgd_precondition_simple": (c_int, [c_void_p, c_int32, c_int32, c_int32, c_float, c_float, c_void_p, c_size_t,
                                           c_void_p, c_void_p, c_void_p]),
+    "ngsgd_precondition_simple_static": (c_int, [c_void_p, c_int32, c_int32, c_int32, c_float, c_float, c_void_p,
+                                                 c_void_p, c_void_p]),
     "ngsgd_workspace_bytes": (c_int, [POINTER(ngsgd_config), POINTER(c_size_t)]),
     "ngsgd_create": (c_int, [POINTER(ngsgd_config), c_void_p, c_size_t, POINTER(c_void_p)]),
     "ngsgd_destroy": (c_int, [c_void_p]),
@@ -212,6 +214,15 @@ class SimplePreconditioner:
                                                   self.epsilon, _ptr(self.workspace), self.workspace_bytes,
                                                   _ptr(gamma), _ptr(rownorm2), _stream_ptr(stream)),
                "ngsgd_precondition_simple")
+
+
+def precondition_simple_static(M, alpha=4.0, epsilon=1e-20, gamma=None, rownorm2=None, stream=None):
+    """ngsgd_precondition_simple_static: the simple method in place on M with the library's fixed scratch."""
+    assert M.is_cuda and M.element_size() == 4 and M.stride(1) == 1
+    _check(load_library().ngsgd_precondition_simple_static(_ptr(M), M.shape[0], M.shape[1], M.stride(0), alpha,
+                                                           epsilon, _ptr(gamma), _ptr(rownorm2),
+                                                           _stream_ptr(stream)),
+           "ngsgd_precondition_simple_static")
 
 
 class Network:

@@ -1018,6 +1018,47 @@ extern "C" int ngsgd_precondition_simple(float* dev_M, int32_t N, int32_t D, int
   return simple_many(calls, true, static_cast<hipStream_t>(hip_stream));
 }
 
+// ---- the simple method without a workspace argument ------------------------------------------------------
+// Scratch of ngsgd_precondition_simple_static: a fixed array in the library's device image instead of memory the
+// caller brings, for callers that cannot allocate.  Every GPU holds its own copy at its own address; in host
+// code the array's name is only a handle for hipGetSymbolAddress, the address it returns is what kernels get.
+static __device__ __align__(256) unsigned char scratch[NGSGD_SIMPLE_STATIC_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device, looked up once per device.
+int static_scratch(void** out) {
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return NGSGD_EUNSUPPORTED;
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* ptr = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (ptr == nullptr || (reinterpret_cast<uintptr_t>(ptr) & 255u)) return NGSGD_EHIP;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return NGSGD_OK;
+}
+}  // namespace
+
+extern "C" int ngsgd_precondition_simple_static(float* dev_M, int32_t N, int32_t D, int32_t ld, float alpha,
+                                                float epsilon, float* dev_gamma, float* dev_rownorm2,
+                                                void* hip_stream) {
+  if (dev_M == nullptr) return NGSGD_EINVAL;
+  size_t need = 0;
+  NG_TRY(ngsgd_simple_workspace_bytes(N, D, &need));
+  if (need > (size_t)NGSGD_SIMPLE_STATIC_BYTES) return NGSGD_ENOMEM;   // the matrix is too large for the fixed scratch
+  void* ptr = nullptr;
+  NG_TRY(static_scratch(&ptr));
+  // the scratch keeps the previous call's contents: the kernels clear what they accumulate into (the Gram
+  // matrix) and write every other buffer before reading it, exactly as with a caller's reused workspace
+  return ngsgd_precondition_simple(dev_M, N, D, ld, alpha, epsilon, ptr, (size_t)NGSGD_SIMPLE_STATIC_BYTES, dev_gamma,
+                                   dev_rownorm2, hip_stream);
+}
+
 extern "C" int ngsgd_precond_workspace_bytes(int32_t dim, int32_t rank, int32_t max_batch, size_t* out_bytes) {
   if (out_bytes == nullptr) return NGSGD_EINVAL;
   NG_TRY(precond_check_config(dim, rank, max_batch, 4.f, 2000.f, 1e-10f, 4, 10));
