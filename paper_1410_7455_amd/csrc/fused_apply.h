@@ -1,0 +1,298 @@
+// Fused apply path of the online natural-gradient preconditioner (App. B.3, eq. ht and hatxt:compute:2; App. B.3.3,
+// eq. pi): Xhat = X - (X W^T) W with the squared row norms of Xhat and tr(X X^T), reading X once and writing Xhat
+// once.  Used when the factor is not updated by the call (App. B.5, "without updating").
+//
+// A 256-thread workgroup owns a patch of 64 rows x BC columns.  Every lane loads its share of the patch straight
+// into registers, laid out as the A operand of v_mfma_f32_16x16x4_f32 (lane (r, g) of a wavefront holds row r,
+// columns 16 kk + 4 g .. + 3), and the workgroup stages the matching BC columns of W in LDS.
+//   phase 1: the patch's contribution to H = X W^T (rows x rank) on the matrix unit, added to H in memory with
+//            float atomics; the patch's sum of squares.
+//   wait:    an arrival counter per block of 64 rows tells when all column chunks of the block have contributed.
+//   phase 2: Xhat^T = X^T - W^T H^T, computed transposed: the accumulator layout of the product (column index from
+//            the register, row index from the lane) is then exactly the layout the patch already has in registers,
+//            so the registers holding X are the accumulator and leave as Xhat.  Row norms from the same registers.
+// The workgroups of a row block only wait for each other, and the grid is ordered row block by row block, so a
+// launch on its own always makes progress: on every die workgroups are started in index order, hence the oldest
+// unfinished row block has all its workgroups running or next in line.  With other kernels competing for the
+// compute units the wait is still bounded: after `spin_limit` ticks of the constant-rate clock a workgroup stops
+// waiting and forms the H rows of its block by itself from X and W (slow, but it ends), so every wave exits.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "gemm.h"
+#include "state.h"
+
+namespace ngsgd {
+
+constexpr int kFusedRows = 64;       // rows of a patch: four wavefronts of 16
+constexpr int kFusedThreads = 256;
+constexpr int kFusedChunk = 160;     // columns of a patch (BC): 40 registers per lane hold it
+
+struct FusedArgs {
+  const float* X;          // N x D, leading dimension ldx
+  float* Xout;             // N x D, leading dimension ldo (may be X itself)
+  const float* W;          // R x D, leading dimension ldw; entries beyond D in a row are never used
+  float* H;                // N x ldh, all zero on entry; X W^T on exit
+  int* arrive;             // one arrival counter per row block, zero on entry
+  float* rownorm_part;     // [n_chunks][N] squared row norms of Xhat per column chunk
+  double* sumsq_part;      // [n_chunks * n_rb] sums of squares of X per patch
+  int ldx, ldo, ldw, ldh;
+  int N, D, R;
+  int n_rb, n_chunks, n_chunks_pad;   // the chunk count is padded to a multiple of the die count
+  int unit_begin;                     // first workgroup index of this instance (a multiple of the die count)
+};
+struct FusedGroup {
+  int count;
+  int total_units;
+  long long spin_limit;    // ticks of wall_clock64() a workgroup waits for its row block; <= 0: does not wait at all
+  FusedArgs a[kMaxInstances];
+};
+
+template <int RC, int BC>
+__global__ __launch_bounds__(kFusedThreads) void fused_apply_kernel(const FusedGroup g) {
+  constexpr int TJ = RC / 16;        // 16-wide tiles of the rank dimension
+  constexpr int KK = BC / 16;        // 16-column groups of the patch
+  constexpr int LDW = BC + 4;        // LDS row stride of the W chunk: 16-byte reads along a row and 4-byte reads down a
+                                     // column are both free of bank conflicts when BC is a multiple of 32
+  static_assert(RC % 16 == 0 && BC % 32 == 0, "tile shape");
+  static_assert(RC * LDW >= kFusedRows * (RC + 1), "the W chunk's LDS also serves the H rows of the slow path");
+  __shared__ __attribute__((aligned(16))) float Ws[RC * LDW];
+  __shared__ double red[kFusedThreads / 64];
+  __shared__ int s_arrived;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r16 = lane & 15, g4 = lane >> 4;
+
+  const int unit = blockIdx.x;
+  if (unit >= g.total_units) return;
+  int pi = 0;
+  for (int i = 1; i < g.count; ++i)
+    if (unit >= g.a[i].unit_begin) pi = i;
+  const FusedArgs& P = g.a[pi];
+  const int local = unit - P.unit_begin;
+  const int rb = local / P.n_chunks_pad, chunk = local % P.n_chunks_pad;
+  if (rb >= P.n_rb || chunk >= P.n_chunks) return;   // padding units (uniform over the workgroup)
+  const int N = P.N, D = P.D, R = P.R;
+  const int c0 = chunk * BC;
+  const int row = rb * kFusedRows + wave * 16 + r16;       // the row this lane holds
+  const bool row_ok = row < N;
+  const int last_f4 = (D - 1) & ~3;                        // the last 16-byte piece of a row that holds a column < D
+
+  // ---- the patch of X into registers (columns beyond D and rows beyond N as zeros) -----------------------
+  float4 xr[KK];
+  {
+    const float* xrow = P.X + (size_t)min(row, N - 1) * P.ldx;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      const int col = c0 + 16 * kk + 4 * g4;
+      xr[kk] = *reinterpret_cast<const float4*>(xrow + min(col, last_f4));
+    }
+  }
+  // ---- the chunk of W into LDS: Ws[j][c] = W[j][c0 + c], zero for j >= R or c0 + c >= D ------------------------
+  auto stage_w = [&]() {
+    constexpr int F4_PER_ROW = BC / 4;
+    constexpr int TOTAL = RC * F4_PER_ROW;
+    constexpr int ITER = (TOTAL + kFusedThreads - 1) / kFusedThreads;
+    float4 wr[ITER];
+#pragma unroll
+    for (int i = 0; i < ITER; ++i) {
+      const int f = min(tid + i * kFusedThreads, TOTAL - 1);
+      const int j = f / F4_PER_ROW, c4 = (f % F4_PER_ROW) * 4;
+      wr[i] = *reinterpret_cast<const float4*>(P.W + (size_t)min(j, R - 1) * P.ldw + min(c0 + c4, last_f4));
+    }
+#pragma unroll
+    for (int i = 0; i < ITER; ++i) {
+      const int f = tid + i * kFusedThreads;
+      if (TOTAL % kFusedThreads != 0 && f >= TOTAL) continue;
+      const int j = f / F4_PER_ROW, c4 = (f % F4_PER_ROW) * 4;
+      const int left = (j < R) ? D - (c0 + c4) : 0;
+      float4 v = wr[i];
+      v.x = left > 0 ? v.x : 0.f;
+      v.y = left > 1 ? v.y : 0.f;
+      v.z = left > 2 ? v.z : 0.f;
+      v.w = left > 3 ? v.w : 0.f;
+      *reinterpret_cast<float4*>(&Ws[j * LDW + c4]) = v;
+    }
+  };
+  stage_w();
+  float ssq = 0.f;
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) {
+    const int left = row_ok ? D - (c0 + 16 * kk + 4 * g4) : 0;
+    xr[kk].x = left > 0 ? xr[kk].x : 0.f;
+    xr[kk].y = left > 1 ? xr[kk].y : 0.f;
+    xr[kk].z = left > 2 ? xr[kk].z : 0.f;
+    xr[kk].w = left > 3 ? xr[kk].w : 0.f;
+    ssq += xr[kk].x * xr[kk].x + xr[kk].y * xr[kk].y + xr[kk].z * xr[kk].z + xr[kk].w * xr[kk].w;
+  }
+  __syncthreads();
+
+  // ---- phase 1: this patch's part of H = X W^T, in two MFMA chains summed with an ordinary add ---------------
+  floatx4 acc[TJ], tot[TJ];
+#pragma unroll
+  for (int tj = 0; tj < TJ; ++tj) acc[tj] = tot[tj] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) {
+    float4 bf[TJ];
+#pragma unroll
+    for (int tj = 0; tj < TJ; ++tj)
+      bf[tj] = *reinterpret_cast<const float4*>(&Ws[(16 * tj + r16) * LDW + 16 * kk + 4 * g4]);
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+      for (int tj = 0; tj < TJ; ++tj)
+        if (16 * tj < R) acc[tj] = __builtin_amdgcn_mfma_f32_16x16x4f32(pick4(xr[kk], q), pick4(bf[tj], q), acc[tj], 0, 0, 0);
+    if (kk == KK / 2 - 1 || kk == KK - 1) {
+#pragma unroll
+      for (int tj = 0; tj < TJ; ++tj) {
+        tot[tj] += acc[tj];
+        acc[tj] = floatx4{0.f, 0.f, 0.f, 0.f};
+      }
+    }
+  }
+  // register q of lane (r16, g4) holds H[row block row 16 wave + 4 g4 + q][16 tj + r16]
+#pragma unroll
+  for (int tj = 0; tj < TJ; ++tj) {
+    const int j = 16 * tj + r16;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int hrow = rb * kFusedRows + wave * 16 + 4 * g4 + q;
+      if (hrow < N && j < R) unsafeAtomicAdd(P.H + (size_t)hrow * P.ldh + j, tot[tj][q]);
+    }
+  }
+  {
+    double s = (double)ssq;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
+    if (lane == 0) red[wave] = s;
+  }
+  __threadfence();     // this thread's additions to H are visible to the device before the arrival is counted
+  __syncthreads();
+  if (tid == 0) {
+    P.sumsq_part[chunk * P.n_rb + rb] = (red[0] + red[1]) + (red[2] + red[3]);
+    __hip_atomic_fetch_add(&P.arrive[rb], 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    int arrived = 0;
+    const long long t0 = wall_clock64();
+    for (;;) {
+      if (__hip_atomic_load(&P.arrive[rb], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) >= P.n_chunks) {
+        arrived = 1;
+        break;
+      }
+      if (wall_clock64() - t0 >= g.spin_limit) break;   // bounded: the slow path below needs nobody else
+      __builtin_amdgcn_s_sleep(2);
+    }
+    s_arrived = arrived;
+  }
+  __syncthreads();
+  const bool arrived = s_arrived != 0;   // uniform over the workgroup
+  __threadfence();     // what the other workgroups added to H is visible to the loads below
+
+  // ---- the H rows of this wavefront's 16 rows, as the second operand of phase 2 ---------------------------------
+  // hb[jj] = -H[row][16 jj + 4 g4 .. + 3]
+  float4 hb[TJ];
+  if (arrived) {
+    const float* hrow = P.H + (size_t)min(row, N - 1) * P.ldh;
+#pragma unroll
+    for (int jj = 0; jj < TJ; ++jj) hb[jj] = *reinterpret_cast<const float4*>(hrow + 16 * jj + 4 * g4);
+  } else {
+    // Slow path: the whole of H for this row block from X and W in memory, 16 columns at a time.
+#pragma unroll
+    for (int tj = 0; tj < TJ; ++tj) tot[tj] = floatx4{0.f, 0.f, 0.f, 0.f};
+    const float* xrow = P.X + (size_t)min(row, N - 1) * P.ldx;
+    for (int c = 0; c < D; c += 16) {
+      const int col = c + 4 * g4;
+      float4 a = *reinterpret_cast<const float4*>(xrow + min(col, last_f4));
+      const int left = row_ok ? D - col : 0;
+      a.x = left > 0 ? a.x : 0.f;
+      a.y = left > 1 ? a.y : 0.f;
+      a.z = left > 2 ? a.z : 0.f;
+      a.w = left > 3 ? a.w : 0.f;
+      float4 bf[TJ];
+#pragma unroll
+      for (int tj = 0; tj < TJ; ++tj) {
+        const int j = 16 * tj + r16;
+        float4 b = *reinterpret_cast<const float4*>(P.W + (size_t)min(j, R - 1) * P.ldw + min(col, last_f4));
+        const int lw = j < R ? D - col : 0;
+        b.x = lw > 0 ? b.x : 0.f;
+        b.y = lw > 1 ? b.y : 0.f;
+        b.z = lw > 2 ? b.z : 0.f;
+        b.w = lw > 3 ? b.w : 0.f;
+        bf[tj] = b;
+      }
+#pragma unroll
+      for (int tj = 0; tj < TJ; ++tj) acc[tj] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int tj = 0; tj < TJ; ++tj)
+          acc[tj] = __builtin_amdgcn_mfma_f32_16x16x4f32(pick4(a, q), pick4(bf[tj], q), acc[tj], 0, 0, 0);
+#pragma unroll
+      for (int tj = 0; tj < TJ; ++tj) tot[tj] += acc[tj];
+    }
+    // from the product's layout to the operand layout through LDS (the W chunk is staged again afterwards)
+    __syncthreads();
+    float* Hs = Ws;   // [64][RC + 1]
+#pragma unroll
+    for (int tj = 0; tj < TJ; ++tj)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) Hs[(wave * 16 + 4 * g4 + q) * (RC + 1) + 16 * tj + r16] = tot[tj][q];
+    __syncthreads();
+#pragma unroll
+    for (int jj = 0; jj < TJ; ++jj) {
+      const float* p = &Hs[(wave * 16 + r16) * (RC + 1) + 16 * jj + 4 * g4];
+      hb[jj] = make_float4(p[0], p[1], p[2], p[3]);
+    }
+    __syncthreads();
+    stage_w();
+    __syncthreads();
+  }
+#pragma unroll
+  for (int jj = 0; jj < TJ; ++jj) hb[jj] = make_float4(-hb[jj].x, -hb[jj].y, -hb[jj].z, -hb[jj].w);
+
+  // ---- phase 2: Xhat^T = X^T - W^T H^T with the registers of X as the accumulator -----------------------------
+  floatx4 xa[KK];
+#pragma unroll
+  for (int cc = 0; cc < KK; ++cc) xa[cc] = floatx4{xr[cc].x, xr[cc].y, xr[cc].z, xr[cc].w};
+#pragma unroll
+  for (int jj = 0; jj < TJ; ++jj) {
+    if (16 * jj >= R) continue;   // uniform
+#pragma unroll
+    for (int cc = 0; cc < KK; ++cc) {
+      const float* wp = &Ws[(16 * jj + 4 * g4) * LDW + 16 * cc + r16];
+      const float w0 = wp[0], w1 = wp[LDW], w2 = wp[2 * LDW], w3 = wp[3 * LDW];
+      xa[cc] = __builtin_amdgcn_mfma_f32_16x16x4f32(w0, hb[jj].x, xa[cc], 0, 0, 0);
+      xa[cc] = __builtin_amdgcn_mfma_f32_16x16x4f32(w1, hb[jj].y, xa[cc], 0, 0, 0);
+      xa[cc] = __builtin_amdgcn_mfma_f32_16x16x4f32(w2, hb[jj].z, xa[cc], 0, 0, 0);
+      xa[cc] = __builtin_amdgcn_mfma_f32_16x16x4f32(w3, hb[jj].w, xa[cc], 0, 0, 0);
+    }
+  }
+
+  // ---- Xhat out, squared row norms over this chunk (eq. pi) -----------------------------------------------------
+  float sq = 0.f;
+  if (row_ok) {
+    float* orow = P.Xout + (size_t)row * P.ldo;
+#pragma unroll
+    for (int cc = 0; cc < KK; ++cc) {
+      const int col = c0 + 16 * cc + 4 * g4;
+      const floatx4 v = xa[cc];
+      if (col + 3 < D) {
+        *reinterpret_cast<float4*>(orow + col) = make_float4(v[0], v[1], v[2], v[3]);
+        sq += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+      } else {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          if (col + q < D) {
+            orow[col + q] = v[q];
+            sq += v[q] * v[q];
+          }
+      }
+    }
+  }
+  sq += __shfl_xor(sq, 16);
+  sq += __shfl_xor(sq, 32);
+  if (row_ok && g4 == 0) P.rownorm_part[(size_t)chunk * N + row] = sq;
+}
+
+}  // namespace ngsgd
