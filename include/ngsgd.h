@@ -243,12 +243,20 @@ int ngsgd_last_max_change_scale(ngsgd_net* net, int32_t layer, double* dev_out, 
 #define NGSGD_PROF_SIMPLE_GRAM 12    /* simple method: X^T X or X X^T                            */
 #define NGSGD_PROF_SIMPLE_INVERSE 13 /* simple method: (beta I + Gram / (N-1))^{-1}              */
 #define NGSGD_PROF_SIMPLE_APPLY 14   /* simple method: Q, per-row factors, gamma                 */
-#define NGSGD_PROF_CATEGORIES 15
+#define NGSGD_PROF_PRECOND_FUSED 15  /* H, Xhat and row norms in one pass (calls without factor update) */
+#define NGSGD_PROF_CATEGORIES 16
 int ngsgd_profile_enable(int32_t on);
 int ngsgd_profile_read(double* ms_out, int64_t* launches_out, int32_t n_categories);
 
 /* ---- diagnostics -------------------------------------------------------------------------- */
 const char* ngsgd_strerror(int code);
+/* The fused apply kernel (Xhat = X - (X W^T) W in one pass, used by calls that do not update their
+ * factor) lets the workgroups that share a block of rows wait for each other's part of X W^T.  The wait
+ * is bounded: after this many microseconds (default 2000) a workgroup stops waiting and leaves its part
+ * of the matrix to the (slow) completion step of the following kernel, so the kernel ends whatever else
+ * occupies the GPU.  0 makes every workgroup take that route at once unless its partners have already
+ * finished (used by the tests of that route).  Process-wide. */
+int ngsgd_set_wait_limit_us(int64_t microseconds);
 /* hipError_t value of the most recent failed HIP call on this thread (0 if none). */
 int ngsgd_last_hip_error(void);
 /* Library version: major * 10000 + minor * 100 + patch. */

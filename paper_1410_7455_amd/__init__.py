@@ -80,6 +80,7 @@ _SIGNATURES = {
     "ngsgd_profile_enable": (c_int, [c_int32]),
     "ngsgd_profile_read": (c_int, [POINTER(c_double), POINTER(c_int64), c_int32]),
     "ngsgd_strerror": (c_char_p, [c_int]),
+    "ngsgd_set_wait_limit_us": (c_int, [c_int64]),
     "ngsgd_last_hip_error": (c_int, []),
     "ngsgd_version": (c_int, []),
 }
@@ -328,7 +329,7 @@ class Network:
 
 PROFILE_CATEGORIES = ["gemm_fwd", "gemm_bwd", "gemm_upd", "precond_h", "precond_j", "precond_xhat", "precond_kl",
                       "precond_small", "precond_wnew", "elementwise", "precond_misc", "init", "simple_gram",
-                      "simple_inverse", "simple_apply"]
+                      "simple_inverse", "simple_apply", "precond_fused"]
 
 
 def profile_enable(on: bool) -> None:
@@ -342,6 +343,11 @@ def profile_read():
     cnt = (c_int64 * n)()
     _check(load_library().ngsgd_profile_read(ms, cnt, n), "ngsgd_profile_read")
     return {name: (ms[i], cnt[i]) for i, name in enumerate(PROFILE_CATEGORIES)}
+
+
+def set_wait_limit_us(microseconds: int) -> None:
+    """ngsgd_set_wait_limit_us: bound of the fused apply kernel's wait between workgroups."""
+    _check(load_library().ngsgd_set_wait_limit_us(int(microseconds)), "ngsgd_set_wait_limit_us")
 
 
 def average(networks, reset_preconditioners=True, stream=None):

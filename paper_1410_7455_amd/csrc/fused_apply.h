@@ -15,7 +15,11 @@
 // launch on its own always makes progress: on every die workgroups are started in index order, hence the oldest
 // unfinished row block has all its workgroups running or next in line.  With other kernels competing for the
 // compute units the wait is still bounded: after `spin_limit` ticks of the constant-rate clock a workgroup stops
-// waiting and forms the H rows of its block by itself from X and W (slow, but it ends), so every wave exits.
+// waiting, leaves its patch of X untouched, puts the patch on the instance's list of deferred patches and exits; the
+// kernel that reduces the partial sums afterwards (finish_apply_kernel) completes those patches from H, which is
+// final by then.  So every wave exits whatever else occupies the GPU.  (The patch cannot be completed here without
+// H, and H cannot be recomputed here from X: the matrix is updated in place, and other workgroups may already have
+// replaced their columns of these rows.)
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -36,6 +40,8 @@ struct FusedArgs {
   const float* W;          // R x D, leading dimension ldw; entries beyond D in a row are never used
   float* H;                // N x ldh, all zero on entry; X W^T on exit
   int* arrive;             // one arrival counter per row block, zero on entry
+  int* deferred_count;     // zero on entry; number of patches put on the list below
+  int* deferred;           // [n_rb * n_chunks] patches left for the finishing kernel: rb * n_chunks + chunk
   float* rownorm_part;     // [n_chunks][N] squared row norms of Xhat per column chunk
   double* sumsq_part;      // [n_chunks * n_rb] sums of squares of X per patch
   int ldx, ldo, ldw, ldh;
@@ -51,13 +57,12 @@ struct FusedGroup {
 };
 
 template <int RC, int BC>
-__global__ __launch_bounds__(kFusedThreads) void fused_apply_kernel(const FusedGroup g) {
+__global__ __launch_bounds__(kFusedThreads, (RC <= 80 ? 3 : 2)) void fused_apply_kernel(const FusedGroup g) {
   constexpr int TJ = RC / 16;        // 16-wide tiles of the rank dimension
   constexpr int KK = BC / 16;        // 16-column groups of the patch
   constexpr int LDW = BC + 4;        // LDS row stride of the W chunk: 16-byte reads along a row and 4-byte reads down a
                                      // column are both free of bank conflicts when BC is a multiple of 32
   static_assert(RC % 16 == 0 && BC % 32 == 0, "tile shape");
-  static_assert(RC * LDW >= kFusedRows * (RC + 1), "the W chunk's LDS also serves the H rows of the slow path");
   __shared__ __attribute__((aligned(16))) float Ws[RC * LDW];
   __shared__ double red[kFusedThreads / 64];
   __shared__ int s_arrived;
@@ -143,7 +148,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_apply_kernel(const FusedG
     for (int q = 0; q < 4; ++q)
 #pragma unroll
       for (int tj = 0; tj < TJ; ++tj)
-        if (16 * tj < R) acc[tj] = __builtin_amdgcn_mfma_f32_16x16x4f32(pick4(xr[kk], q), pick4(bf[tj], q), acc[tj], 0, 0, 0);
+        acc[tj] = __builtin_amdgcn_mfma_f32_16x16x4f32(pick4(xr[kk], q), pick4(bf[tj], q), acc[tj], 0, 0, 0);
     if (kk == KK / 2 - 1 || kk == KK - 1) {
 #pragma unroll
       for (int tj = 0; tj < TJ; ++tj) {
@@ -151,6 +156,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_apply_kernel(const FusedG
         acc[tj] = floatx4{0.f, 0.f, 0.f, 0.f};
       }
     }
+    __builtin_amdgcn_sched_barrier(0);   // one 16-column group at a time: keeps the operand fragments of later groups out of registers
   }
   // register q of lane (r16, g4) holds H[row block row 16 wave + 4 g4 + q][16 tj + r16]
 #pragma unroll
@@ -189,67 +195,30 @@ __global__ __launch_bounds__(kFusedThreads) void fused_apply_kernel(const FusedG
   const bool arrived = s_arrived != 0;   // uniform over the workgroup
   __threadfence();     // what the other workgroups added to H is visible to the loads below
 
+  if (!arrived) {   // give up: the patch stays as it is and is completed by the finishing kernel
+    if (tid == 0) {
+      const int slot = __hip_atomic_fetch_add(P.deferred_count, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      P.deferred[slot] = rb * P.n_chunks + chunk;
+    }
+    return;
+  }
+
   // ---- the H rows of this wavefront's 16 rows, as the second operand of phase 2 ---------------------------------
-  // hb[jj] = -H[row][16 jj + 4 g4 .. + 3]
+  // hb[jj] = -H[row][16 jj + 4 g4 .. + 3]; columns beyond the rank carry nothing (an instance narrower than the
+  // launch's rank class has fewer than RC columns of H: the reads stay inside its rows)
   float4 hb[TJ];
-  if (arrived) {
+  {
     const float* hrow = P.H + (size_t)min(row, N - 1) * P.ldh;
 #pragma unroll
-    for (int jj = 0; jj < TJ; ++jj) hb[jj] = *reinterpret_cast<const float4*>(hrow + 16 * jj + 4 * g4);
-  } else {
-    // Slow path: the whole of H for this row block from X and W in memory, 16 columns at a time.
-#pragma unroll
-    for (int tj = 0; tj < TJ; ++tj) tot[tj] = floatx4{0.f, 0.f, 0.f, 0.f};
-    const float* xrow = P.X + (size_t)min(row, N - 1) * P.ldx;
-    for (int c = 0; c < D; c += 16) {
-      const int col = c + 4 * g4;
-      float4 a = *reinterpret_cast<const float4*>(xrow + min(col, last_f4));
-      const int left = row_ok ? D - col : 0;
-      a.x = left > 0 ? a.x : 0.f;
-      a.y = left > 1 ? a.y : 0.f;
-      a.z = left > 2 ? a.z : 0.f;
-      a.w = left > 3 ? a.w : 0.f;
-      float4 bf[TJ];
-#pragma unroll
-      for (int tj = 0; tj < TJ; ++tj) {
-        const int j = 16 * tj + r16;
-        float4 b = *reinterpret_cast<const float4*>(P.W + (size_t)min(j, R - 1) * P.ldw + min(col, last_f4));
-        const int lw = j < R ? D - col : 0;
-        b.x = lw > 0 ? b.x : 0.f;
-        b.y = lw > 1 ? b.y : 0.f;
-        b.z = lw > 2 ? b.z : 0.f;
-        b.w = lw > 3 ? b.w : 0.f;
-        bf[tj] = b;
-      }
-#pragma unroll
-      for (int tj = 0; tj < TJ; ++tj) acc[tj] = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int q = 0; q < 4; ++q)
-#pragma unroll
-        for (int tj = 0; tj < TJ; ++tj)
-          acc[tj] = __builtin_amdgcn_mfma_f32_16x16x4f32(pick4(a, q), pick4(bf[tj], q), acc[tj], 0, 0, 0);
-#pragma unroll
-      for (int tj = 0; tj < TJ; ++tj) tot[tj] += acc[tj];
-    }
-    // from the product's layout to the operand layout through LDS (the W chunk is staged again afterwards)
-    __syncthreads();
-    float* Hs = Ws;   // [64][RC + 1]
-#pragma unroll
-    for (int tj = 0; tj < TJ; ++tj)
-#pragma unroll
-      for (int q = 0; q < 4; ++q) Hs[(wave * 16 + 4 * g4 + q) * (RC + 1) + 16 * tj + r16] = tot[tj][q];
-    __syncthreads();
+    for (int jj = 0; jj < TJ; ++jj)
+      hb[jj] = *reinterpret_cast<const float4*>(hrow + min(16 * jj + 4 * g4, P.ldh - 4));
 #pragma unroll
     for (int jj = 0; jj < TJ; ++jj) {
-      const float* p = &Hs[(wave * 16 + r16) * (RC + 1) + 16 * jj + 4 * g4];
-      hb[jj] = make_float4(p[0], p[1], p[2], p[3]);
+      const int left = R - (16 * jj + 4 * g4);
+      hb[jj] = make_float4(left > 0 ? -hb[jj].x : 0.f, left > 1 ? -hb[jj].y : 0.f, left > 2 ? -hb[jj].z : 0.f,
+                           left > 3 ? -hb[jj].w : 0.f);
     }
-    __syncthreads();
-    stage_w();
-    __syncthreads();
   }
-#pragma unroll
-  for (int jj = 0; jj < TJ; ++jj) hb[jj] = make_float4(-hb[jj].x, -hb[jj].y, -hb[jj].z, -hb[jj].w);
 
   // ---- phase 2: Xhat^T = X^T - W^T H^T with the registers of X as the accumulator -----------------------------
   floatx4 xa[KK];
@@ -257,7 +226,6 @@ __global__ __launch_bounds__(kFusedThreads) void fused_apply_kernel(const FusedG
   for (int cc = 0; cc < KK; ++cc) xa[cc] = floatx4{xr[cc].x, xr[cc].y, xr[cc].z, xr[cc].w};
 #pragma unroll
   for (int jj = 0; jj < TJ; ++jj) {
-    if (16 * jj >= R) continue;   // uniform
 #pragma unroll
     for (int cc = 0; cc < KK; ++cc) {
       const float* wp = &Ws[(16 * jj + 4 * g4) * LDW + 16 * cc + r16];
@@ -266,6 +234,7 @@ __global__ __launch_bounds__(kFusedThreads) void fused_apply_kernel(const FusedG
       xa[cc] = __builtin_amdgcn_mfma_f32_16x16x4f32(w1, hb[jj].y, xa[cc], 0, 0, 0);
       xa[cc] = __builtin_amdgcn_mfma_f32_16x16x4f32(w2, hb[jj].z, xa[cc], 0, 0, 0);
       xa[cc] = __builtin_amdgcn_mfma_f32_16x16x4f32(w3, hb[jj].w, xa[cc], 0, 0, 0);
+      if (cc & 1) __builtin_amdgcn_sched_barrier(0);   // two column groups at a time (see phase 1)
     }
   }
 

@@ -389,6 +389,13 @@ struct FinishArgs {
   double* prow;              // out: p_i (eq. pi), N doubles
   float* gamma_out;          // optional
   float* rownorm2_out;       // optional, gamma^2 p_i
+  // patches the fused apply kernel left undone (its bounded wait ran out): Xhat = X - H W is completed here
+  const int* deferred_count; // nullptr: none
+  const int* deferred;       // rb * n_col_tiles + chunk for each such patch of 64 rows x chunk_cols columns
+  float* X;                  // N x D, in place
+  const float* W;            // R x D
+  const float* H;            // N x ldh, final
+  int ldx, ldw, ldh, D, R, chunk_cols;
 };
 struct FinishGroup {
   int count;
@@ -398,6 +405,36 @@ struct FinishGroup {
 __global__ __launch_bounds__(1024) void finish_apply_kernel(const FinishGroup g) {
   __shared__ double scratch[16];
   const FinishArgs& a = g.a[blockIdx.x];
+  const int n_deferred = a.deferred_count != nullptr ? *a.deferred_count : 0;
+  if (n_deferred > 0) {
+    // 16 threads per row of a 64-row patch; plain dot products over the rank (this path is rare and small)
+    const int sub = threadIdx.x & 15;
+    for (int e = 0; e < n_deferred; ++e) {
+      const int id = a.deferred[e];
+      const int rb = id / a.n_col_tiles, chunk = id % a.n_col_tiles;
+      const int r = rb * 64 + (threadIdx.x >> 4);
+      const int c_end = min(a.D, (chunk + 1) * a.chunk_cols);
+      float sq = 0.f;
+      if (r < a.N && threadIdx.x < 1024) {
+        const float* h = a.H + (size_t)r * a.ldh;
+        float* x = a.X + (size_t)r * a.ldx;
+        for (int c = chunk * a.chunk_cols + sub; c < c_end; c += 16) {
+          float s = 0.f;
+          for (int j = 0; j < a.R; ++j) s = fmaf(h[j], a.W[(size_t)j * a.ldw + c], s);
+          const float v = x[c] - s;
+          x[c] = v;
+          sq = fmaf(v, v, sq);
+        }
+      }
+      sq += __shfl_xor(sq, 1);
+      sq += __shfl_xor(sq, 2);
+      sq += __shfl_xor(sq, 4);
+      sq += __shfl_xor(sq, 8);
+      if (r < a.N && sub == 0) const_cast<float*>(a.rownorm_part)[(size_t)chunk * a.N + r] = sq;
+    }
+    __threadfence();
+    __syncthreads();   // the partial row norms written above are read below by other lanes
+  }
   double t = 0.0;
   for (int i = threadIdx.x; i < a.n_sumsq; i += blockDim.x) t += a.sumsq_part[i];
   const double tr_M = block_sum(t, scratch);

@@ -5,12 +5,14 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstdint>
 #include <cstring>
 #include <new>
 #include <vector>
 
+#include "fused_apply.h"
 #include "gemm.h"
 #include "init.h"
 #include "kernels.h"
@@ -130,8 +132,11 @@ struct ngsgd_precond {
   int ldw = 0;   // leading dimension of W and J
   int ldh = 0;   // leading dimension of H and A_t (= rank class)
   PrecondScalars* st = nullptr;
-  float* zero_region = nullptr;   // [H | K | L], cleared before each call
+  float* zero_region = nullptr;   // [arrival counters, deferred count | H | K | L], cleared before each call
   size_t zero_floats_all = 0;
+  size_t arrive_slots = 0;        // arrival counters of the fused apply kernel, one per block of 64 rows, and
+  int* arrive = nullptr;          // (last slot) the number of patches it deferred; padded to 256 bytes
+  int* deferred = nullptr;        // list of deferred patches
   float* H = nullptr;
   float* J = nullptr;
   double* K = nullptr;
@@ -170,10 +175,12 @@ void precond_layout(ngsgd_precond& p, Carver& c) {
   p.prow = c.take<double>(NB);
   if (R == 0) return;
   const size_t h_floats = (size_t)NB * p.ldh, kl_floats = (size_t)4 * R * R;   // ldh is a multiple of 16
-  p.zero_floats_all = h_floats + kl_floats;
+  p.arrive_slots = align_up((size_t)(NB + kFusedRows - 1) / kFusedRows + 1, 64);
+  p.zero_floats_all = p.arrive_slots + h_floats + kl_floats;
   p.zero_region = c.take<float>(p.zero_floats_all);
   if (p.zero_region) {
-    p.H = p.zero_region;
+    p.arrive = reinterpret_cast<int*>(p.zero_region);
+    p.H = p.zero_region + p.arrive_slots;
     p.K = reinterpret_cast<double*>(p.H + h_floats);
     p.L = p.K + (size_t)R * R;
   }
@@ -183,6 +190,7 @@ void precond_layout(ngsgd_precond& p, Carver& c) {
   p.max_col_tiles = (D + 63) / 64;
   p.rownorm_part = c.take<float>((size_t)p.max_col_tiles * NB);
   p.sumsq_part = c.take<double>(kSumsqMax);
+  p.deferred = c.take<int>(kSumsqMax);
   p.n_init_max = NB < D ? NB : D;
   const size_t np_init = (size_t)(p.n_init_max + kInitPair - 1) / kInitPair * kInitPair;
   p.Ai = c.take<double>(np_init * np_init);
@@ -463,7 +471,7 @@ int clear_accumulators(const std::vector<PrecondCall>& list, hipStream_t s) {
       const PrecondCall& c = list[done + i];
       ngsgd_precond& p = *c.p;
       fg.ptr[i] = reinterpret_cast<uint32_t*>(p.zero_region);
-      fg.n[i] = factor_due(p) ? p.zero_floats_all : (size_t)c.N * p.ldh;
+      fg.n[i] = factor_due(p) ? p.zero_floats_all : p.arrive_slots + (size_t)c.N * p.ldh;
       n_max = std::max(n_max, fg.n[i]);
     }
     const unsigned blocks = (unsigned)std::min<size_t>((n_max + 2047) / 2048, 64);
@@ -532,6 +540,65 @@ int launch_j_products(std::vector<PrecondCall>& list, hipStream_t s) {
   return NGSGD_OK;
 }
 
+// How long a workgroup of the fused apply kernel waits for the other column chunks of its row block before it
+// forms the H rows itself (microseconds; the kernel's clock runs at 100 MHz).
+std::atomic<long long> g_fused_wait_us{2000};
+
+inline int fused_chunks(int D) { return (D + kFusedChunk - 1) / kFusedChunk; }
+inline int fused_row_blocks(int N) { return (N + kFusedRows - 1) / kFusedRows; }
+
+// Whether the fused kernel's bookkeeping has room for this call (partial sums of tr(X X^T) per patch).
+inline bool fused_fits(const ngsgd_precond& p, int N) {
+  return fused_chunks(p.dim) * fused_row_blocks(N) <= kSumsqMax && (size_t)fused_row_blocks(N) < p.arrive_slots;
+}
+
+// Xhat = X - (X W^T) W, row-norm partials and the partial sums of tr(X X^T) in one pass over each matrix
+// (eq. ht, hatxt:compute:2, pi), for instances whose factor is not updated by this call.
+int launch_fused_apply(std::vector<PrecondCall>& list, hipStream_t s) {
+  for (size_t done = 0; done < list.size();) {
+    FusedGroup g;
+    const int n = (int)std::min<size_t>(kMaxInstances, list.size() - done);
+    g.count = n;
+    g.spin_limit = g_fused_wait_us.load() * 100;
+    int units = 0, rc = 0;
+    for (int i = 0; i < n; ++i) {
+      const PrecondCall& c = list[done + i];
+      ngsgd_precond& p = *c.p;
+      FusedArgs& a = g.a[i];
+      a.X = c.M; a.ldx = c.ld;
+      a.Xout = c.M; a.ldo = c.ld;
+      a.W = p.W; a.ldw = p.ldw;
+      a.H = p.H; a.ldh = p.ldh;
+      a.arrive = p.arrive;
+      a.deferred_count = p.arrive + (p.arrive_slots - 1);
+      a.deferred = p.deferred;
+      a.rownorm_part = p.rownorm_part;
+      a.sumsq_part = p.sumsq_part;
+      a.N = c.N; a.D = p.dim; a.R = p.rank;
+      a.n_rb = fused_row_blocks(c.N);
+      a.n_chunks = fused_chunks(p.dim);
+      a.n_chunks_pad = (a.n_chunks + kXcds - 1) / kXcds * kXcds;
+      a.unit_begin = units;
+      units += a.n_rb * a.n_chunks_pad;
+      p.last_N = c.N;
+      p.n_sumsq = a.n_chunks * a.n_rb;
+      rc = std::max(rc, p.ldh);
+    }
+    g.total_units = units;
+    ProfScope prof(NGSGD_PROF_PRECOND_FUSED, s);
+    if (rc == 32) {
+      hipLaunchKernelGGL((fused_apply_kernel<32, kFusedChunk>), dim3(units), dim3(kFusedThreads), 0, s, g);
+    } else if (rc == 80) {
+      hipLaunchKernelGGL((fused_apply_kernel<80, kFusedChunk>), dim3(units), dim3(kFusedThreads), 0, s, g);
+    } else {
+      hipLaunchKernelGGL((fused_apply_kernel<96, kFusedChunk>), dim3(units), dim3(kFusedThreads), 0, s, g);
+    }
+    LAUNCH_CHECK();
+    done += n;
+  }
+  return NGSGD_OK;
+}
+
 // With hj_ready the caller has already produced H and J of every instance (all due for an update, none at t = 0)
 // and ordered s behind them; only Xhat and gamma remain.
 int precond_apply(std::vector<PrecondCall>& calls, bool scale_output, hipStream_t s,
@@ -555,14 +622,20 @@ int precond_apply(std::vector<PrecondCall>& calls, bool scale_output, hipStream_
     if (p.t == 0) to_init.push_back(c);
     if (factor_due(p)) to_update.push_back(c);
   }
-  if (!hj_ready) {
+  // No factor is updated by this call: one fused pass per matrix instead of the H and Xhat products.
+  bool fused = !hj_ready && to_update.empty() && !full.empty();
+  for (auto& c : full) fused = fused && fused_fits(*c.p, c.N);
+  if (fused) {
+    NG_TRY(clear_accumulators(full, s));
+    NG_TRY(launch_fused_apply(full, s));
+  } else if (!hj_ready) {
     if (!to_init.empty()) NG_TRY(run_init(to_init, s));
     NG_TRY(clear_accumulators(full, s));
     NG_TRY(launch_h_products(full, s));
     NG_TRY(launch_j_products(to_update, s));
   }
   // Xhat = X - H W   (eq. hatxt:compute:2), row-norm partials (eq. pi)
-  {
+  if (!fused) {
     std::vector<GemmDesc> d;
     for (auto& c : full) {
       ngsgd_precond& p = *c.p;
@@ -591,11 +664,18 @@ int precond_apply(std::vector<PrecondCall>& calls, bool scale_output, hipStream_
       a.sumsq_part = p.sumsq_part;
       a.n_sumsq = p.n_sumsq;
       a.rownorm_part = p.rownorm_part;
-      a.n_col_tiles = (p.dim + 63) / 64;
+      a.n_col_tiles = fused ? fused_chunks(p.dim) : (p.dim + 63) / 64;
       a.N = c.N;
       a.prow = p.prow;
       a.gamma_out = c.gamma_out;
       a.rownorm2_out = c.rownorm2_out;
+      a.deferred_count = fused ? p.arrive + (p.arrive_slots - 1) : nullptr;
+      a.deferred = p.deferred;
+      a.X = c.M; a.ldx = c.ld;
+      a.W = p.W; a.ldw = p.ldw;
+      a.H = p.H; a.ldh = p.ldh;
+      a.D = p.dim; a.R = p.rank;
+      a.chunk_cols = kFusedChunk;
     }
     hipLaunchKernelGGL(finish_apply_kernel, dim3(n), dim3(1024), 0, s, g);
     LAUNCH_CHECK();
@@ -1784,6 +1864,12 @@ extern "C" int ngsgd_profile_read(double* ms_out, int64_t* launches_out, int32_t
   g_prof.dropped = 0;
   g_prof.recs.clear();
   return complete ? NGSGD_OK : NGSGD_ENOMEM;   // the sums miss the groups that did not fit
+}
+
+extern "C" int ngsgd_set_wait_limit_us(int64_t microseconds) {
+  if (microseconds < 0) return NGSGD_EINVAL;
+  g_fused_wait_us.store((long long)microseconds);
+  return NGSGD_OK;
 }
 
 extern "C" int ngsgd_last_hip_error(void) { return g_last_hip_error; }

@@ -260,7 +260,8 @@ def test_kernel_group_timing(ngsgd):
     gpu.join()
     prof = ngsgd.profile_read()
     assert prof["gemm_fwd"][1] == 2 * spec.n_layers and prof["gemm_bwd"][1] == 2 * (spec.n_layers - 1)
-    assert prof["precond_small"][1] >= 1 and prof["precond_xhat"][1] >= 2
+    # the update step takes H, J and Xhat as separate products, the apply-only step the fused pass
+    assert prof["precond_small"][1] >= 1 and prof["precond_xhat"][1] >= 1 and prof["precond_fused"][1] >= 1
     assert all(ms >= 0.0 for ms, _ in prof.values()) and prof["gemm_fwd"][0] > 0.0
     assert sum(c for _, c in ngsgd.profile_read().values()) == 0          # a read clears the record
     for _ in range(2000):                    # about 20 groups per step: more than the 32768 the library keeps
