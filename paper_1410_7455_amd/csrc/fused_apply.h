@@ -11,9 +11,18 @@
 //   phase 2: Xhat^T = X^T - W^T H^T, computed transposed: the accumulator layout of the product (column index from
 //            the register, row index from the lane) is then exactly the layout the patch already has in registers,
 //            so the registers holding X are the accumulator and leave as Xhat.  Row norms from the same registers.
-// The workgroups of a row block only wait for each other, and the grid is ordered row block by row block, so a
-// launch on its own always makes progress: on every die workgroups are started in index order, hence the oldest
-// unfinished row block has all its workgroups running or next in line.  With other kernels competing for the
+//
+// Exchange between workgroups.  The dies of the chip have separate L2 caches, and a device-wide fence writes the
+// die's L2 back and invalidates it: measured here, two such fences per thread cost 27 us of a 58 us launch, and even
+// one release / acquire pair per workgroup cost 8 us.  The exchange therefore uses nothing but operations that are
+// performed at the memory side: float atomics for H, an atomic counter, and loads of H that bypass the caches
+// (system-coherent buffer loads).  Order is kept by construction: every wavefront waits until its atomics have been
+// acknowledged (s_waitcnt) before the workgroup's barrier, the counter is incremented after that barrier, and H is
+// loaded after the counter has been seen complete.
+//
+// Progress.  The workgroups of a row block only wait for each other, and the grid is ordered row block by row
+// block, so a launch on its own always makes progress: on every die workgroups are started in index order, hence the
+// oldest unfinished row block has all its workgroups running or next in line.  With other kernels competing for the
 // compute units the wait is still bounded: after `spin_limit` ticks of the constant-rate clock a workgroup stops
 // waiting, leaves its patch of X untouched, puts the patch on the instance's list of deferred patches and exits; the
 // kernel that reduces the partial sums afterwards (finish_apply_kernel) completes those patches from H, which is
@@ -56,7 +65,17 @@ struct FusedGroup {
   FusedArgs a[kMaxInstances];
 };
 
-template <int RC, int BC>
+// 16-byte load at device scope (sc1): served from where the atomics of all dies are performed, never from a stale
+// line of this die's caches.  The compiler does not track the load: wait_coherent_loads() must follow before use.
+__device__ __forceinline__ void load_coherent_f4(floatx4& dst, const float* p) {
+  asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(dst) : "v"(p) : "memory");
+}
+__device__ __forceinline__ void wait_coherent_loads(floatx4& dst) {
+  asm volatile("s_waitcnt vmcnt(0)" : "+v"(dst) : : "memory");
+}
+
+// TIMING is for microbenchmarks only (bit 0: no atomics on H, bit 1: no wait); production code uses 0.
+template <int RC, int BC, int TIMING = 0>
 __global__ __launch_bounds__(kFusedThreads, (RC <= 80 ? 3 : 2)) void fused_apply_kernel(const FusedGroup g) {
   constexpr int TJ = RC / 16;        // 16-wide tiles of the rank dimension
   constexpr int KK = BC / 16;        // 16-column groups of the patch
@@ -96,7 +115,7 @@ __global__ __launch_bounds__(kFusedThreads, (RC <= 80 ? 3 : 2)) void fused_apply
     }
   }
   // ---- the chunk of W into LDS: Ws[j][c] = W[j][c0 + c], zero for j >= R or c0 + c >= D ------------------------
-  auto stage_w = [&]() {
+  {
     constexpr int F4_PER_ROW = BC / 4;
     constexpr int TOTAL = RC * F4_PER_ROW;
     constexpr int ITER = (TOTAL + kFusedThreads - 1) / kFusedThreads;
@@ -120,8 +139,7 @@ __global__ __launch_bounds__(kFusedThreads, (RC <= 80 ? 3 : 2)) void fused_apply
       v.w = left > 3 ? v.w : 0.f;
       *reinterpret_cast<float4*>(&Ws[j * LDW + c4]) = v;
     }
-  };
-  stage_w();
+  }
   float ssq = 0.f;
 #pragma unroll
   for (int kk = 0; kk < KK; ++kk) {
@@ -159,13 +177,15 @@ __global__ __launch_bounds__(kFusedThreads, (RC <= 80 ? 3 : 2)) void fused_apply
     __builtin_amdgcn_sched_barrier(0);   // one 16-column group at a time: keeps the operand fragments of later groups out of registers
   }
   // register q of lane (r16, g4) holds H[row block row 16 wave + 4 g4 + q][16 tj + r16]
+  if (!(TIMING & 1)) {
 #pragma unroll
-  for (int tj = 0; tj < TJ; ++tj) {
-    const int j = 16 * tj + r16;
+    for (int tj = 0; tj < TJ; ++tj) {
+      const int j = 16 * tj + r16;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int hrow = rb * kFusedRows + wave * 16 + 4 * g4 + q;
-      if (hrow < N && j < R) unsafeAtomicAdd(P.H + (size_t)hrow * P.ldh + j, tot[tj][q]);
+      for (int q = 0; q < 4; ++q) {
+        const int hrow = rb * kFusedRows + wave * 16 + 4 * g4 + q;
+        if (hrow < N && j < R) unsafeAtomicAdd(P.H + (size_t)hrow * P.ldh + j, tot[tj][q]);
+      }
     }
   }
   {
@@ -174,28 +194,24 @@ __global__ __launch_bounds__(kFusedThreads, (RC <= 80 ? 3 : 2)) void fused_apply
     for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
     if (lane == 0) red[wave] = s;
   }
-  __threadfence();     // this thread's additions to H are visible to the device before the arrival is counted
+  // every atomic of this wavefront has been acknowledged by the memory side before the barrier lets thread 0 count
+  // the workgroup's arrival (a workgroup-scope release: a wait on the memory counters, no cache maintenance)
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
   __syncthreads();
   if (tid == 0) {
     P.sumsq_part[chunk * P.n_rb + rb] = (red[0] + red[1]) + (red[2] + red[3]);
-    __hip_atomic_fetch_add(&P.arrive[rb], 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-    int arrived = 0;
+    const int before = __hip_atomic_fetch_add(&P.arrive[rb], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    int arrived = (before + 1 >= P.n_chunks || (TIMING & 2)) ? 1 : 0;   // the last to arrive need not look again
     const long long t0 = wall_clock64();
-    for (;;) {
-      if (__hip_atomic_load(&P.arrive[rb], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) >= P.n_chunks) {
-        arrived = 1;
-        break;
-      }
-      if (wall_clock64() - t0 >= g.spin_limit) break;   // bounded: the slow path below needs nobody else
+    while (!arrived) {
+      if (wall_clock64() - t0 >= g.spin_limit) break;   // bounded: the patch is deferred below
       __builtin_amdgcn_s_sleep(2);
+      arrived = __hip_atomic_load(&P.arrive[rb], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= P.n_chunks ? 1 : 0;
     }
     s_arrived = arrived;
   }
   __syncthreads();
-  const bool arrived = s_arrived != 0;   // uniform over the workgroup
-  __threadfence();     // what the other workgroups added to H is visible to the loads below
-
-  if (!arrived) {   // give up: the patch stays as it is and is completed by the finishing kernel
+  if (s_arrived == 0) {   // (uniform) give up: the patch stays as it is and is completed by the finishing kernel
     if (tid == 0) {
       const int slot = __hip_atomic_fetch_add(P.deferred_count, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       P.deferred[slot] = rb * P.n_chunks + chunk;
@@ -209,14 +225,18 @@ __global__ __launch_bounds__(kFusedThreads, (RC <= 80 ? 3 : 2)) void fused_apply
   float4 hb[TJ];
   {
     const float* hrow = P.H + (size_t)min(row, N - 1) * P.ldh;
+    floatx4 hv[TJ];
+    {
 #pragma unroll
-    for (int jj = 0; jj < TJ; ++jj)
-      hb[jj] = *reinterpret_cast<const float4*>(hrow + min(16 * jj + 4 * g4, P.ldh - 4));
+      for (int jj = 0; jj < TJ; ++jj) load_coherent_f4(hv[jj], hrow + min(16 * jj + 4 * g4, P.ldh - 4));
+#pragma unroll
+      for (int jj = 0; jj < TJ; ++jj) wait_coherent_loads(hv[jj]);
+    }
 #pragma unroll
     for (int jj = 0; jj < TJ; ++jj) {
       const int left = R - (16 * jj + 4 * g4);
-      hb[jj] = make_float4(left > 0 ? -hb[jj].x : 0.f, left > 1 ? -hb[jj].y : 0.f, left > 2 ? -hb[jj].z : 0.f,
-                           left > 3 ? -hb[jj].w : 0.f);
+      hb[jj] = make_float4(left > 0 ? -hv[jj][0] : 0.f, left > 1 ? -hv[jj][1] : 0.f, left > 2 ? -hv[jj][2] : 0.f,
+                           left > 3 ? -hv[jj][3] : 0.f);
     }
   }
 
