@@ -231,3 +231,99 @@ def test_c2_full_size_shapes(ngsgd, which):
         assert flags & 8 == 0, f"step {step}: the Jacobi iteration did not converge (flags {flags})"
         assert 1 <= sweeps <= 20
     compare_states(torch, pre, ora, rng)
+
+
+@pytest.mark.parametrize("which", ["input", "output"])
+def test_c2_thousand_successive_updates(ngsgd, which):
+    """BASELINE configs[2] as stated: 1000 successive online updates at full size, free running on both sides
+    (each builds its state from the first matrix and then follows its own recursion), the factor updated on every
+    call.  A pool of 16 matrices is cycled, as in bench.py.  Every 50th call the preconditioned matrix, gamma, rho,
+    the sorted D and the action of the factor on a probe are compared; the first mismatch stops the test."""
+    import torch
+    spec = workloads.c2_input_side() if which == "input" else workloads.c2_output_side()
+    kw = dict(num_samples_history=spec.num_samples_history, update_period=spec.update_period)
+    ora = OnlineNaturalGradient(spec.dim, spec.rank, **kw)
+    pre = ngsgd.Preconditioner(spec.dim, spec.rank, max_batch=spec.rows, **kw)
+    pool = [workloads.spectrum_matrix(spec, t) for t in range(16)]
+    ld = (spec.dim + 3) // 4 * 4
+    dev_pool = []
+    for M in pool:
+        buf = torch.zeros((spec.rows, ld), dtype=torch.float32, device="cuda")
+        buf[:, :spec.dim] = torch.from_numpy(M).cuda()
+        dev_pool.append(buf)
+    work = torch.empty_like(dev_pool[0])
+    gamma = torch.zeros(1, dtype=torch.float32, device="cuda")
+    rng = np.random.default_rng(8)
+    worst = 0.0
+    for step in range(spec.steps):
+        expect, g_o, _ = ora.precondition(pool[step % 16])
+        work.copy_(dev_pool[step % 16])
+        pre.precondition(work, gamma)
+        if step % 50 == 49 or step == spec.steps - 1:
+            print(f"c2 long run {spec.name} call {step}", flush=True)
+            torch.cuda.synchronize()
+            err = rel(work[:, :spec.dim].cpu().numpy(), expect)
+            worst = max(worst, err)
+            assert err < TOL, f"call {step}"
+            assert float(gamma.item()) == pytest.approx(g_o, rel=1e-4)
+            compare_states(torch, pre, ora, rng)
+            flags, sweeps = pre.diagnostics()
+            assert flags & 8 == 0 and 1 <= sweeps <= 20, f"call {step}: flags {flags}, sweeps {sweeps}"
+    assert ora.t == spec.steps == 1000
+    print(f"c2 long run {spec.name}: worst relative error of the preconditioned matrix {worst:.2e}")
+
+
+def test_eigenvalues_under_the_floor(ngsgd):
+    """The eigenvalues of Z_t cannot fall below (1 - eta)^2 rho_t^2 for a factor with orthonormal rows (App. B.3), so
+    with consistent state the floor only catches rounding.  It fires for real when the stored factor has lost its
+    orthogonality: eq. zt:compute then no longer describes a Gram matrix and Z_t can even be indefinite.  A mixed
+    (non-orthonormal) factor is installed for which the oracle's W-space routine reports a floored eigenvalue, and
+    the device must then raise its floor flag (bit 1), run the orthogonality check the floor asks for, repair the
+    factor (bit 2) and agree with that routine on the output, on the state and on the calls that follow.  (As in
+    the forced re-orthogonalisation test, the reference is the efficient form: with R R^T != I the definitional
+    form is a different map.)"""
+    import torch
+    from oracle.online_ng_efficient import OnlineNaturalGradientEfficient
+    rng = np.random.default_rng(4)
+    N, D, R = 96, 200, 6
+    kw = dict(num_samples_history=300.0, update_period=1)
+    warm = OnlineNaturalGradient(D, R, **kw)
+    for _ in range(3):
+        warm.precondition(data(rng, N, D))
+    M = data(rng, N, D)
+    eta = 1.0 - math.exp(-N / 300.0)
+    search = np.random.default_rng(40)
+    chosen = None
+    for _ in range(400):        # seeded search on the CPU for a mildly indefinite case
+        R_bad = (np.eye(R) + 1.5 * search.standard_normal((R, R))) @ warm.R
+        d_bad = warm.d * np.exp(search.uniform(-3.0, 3.0, R))
+        rho_bad = warm.rho * math.exp(search.uniform(-1.0, 2.0))
+        eff = OnlineNaturalGradientEfficient(D, R, **kw)
+        _, e = smoothing_and_scales(d_bad, rho_bad, 4.0, D)
+        eff.W, eff.d, eff.rho, eff.t = np.sqrt(e)[:, None] * R_bad, d_bad.copy(), rho_bad, warm.t
+        expect, _, _ = eff.precondition(M)
+        if eff.last["floored"] and eff.last["reorthogonalised"]:
+            chosen = (R_bad, d_bad, rho_bad, eff, expect)
+            break
+    assert chosen is not None, "the search found no floored case"
+    R_bad, d_bad, rho_bad, eff, expect = chosen
+    pre = ngsgd.Preconditioner(D, R, max_batch=N, **kw)
+    pre.set_state(torch.from_numpy(R_bad.copy()).cuda(), torch.from_numpy(d_bad.copy()).cuda(), rho_bad, warm.t)
+    got, _, _ = gpu_call(torch, pre, M)
+    flags, sweeps = pre.diagnostics()
+    assert flags & 2, "the device did not floor an eigenvalue of Z_t"
+    assert flags & 4 and not flags & 1, "the floor must trigger the orthogonality check, which repairs this factor"
+    assert flags & 8 == 0 and 1 <= sweeps <= 20
+    assert rel(got, expect) < TOL
+    W, d, rho, _ = pre.get_state()
+    W = W.cpu().numpy().astype(np.float64)
+    assert rho == pytest.approx(eff.rho, rel=2e-4)
+    live = np.sort(eff.d)[::-1] > 1e-6 * eff.d.max()      # (a floored eigenvalue leaves d_i at epsilon)
+    np.testing.assert_allclose(np.sort(d.cpu().numpy())[::-1][live], np.sort(eff.d)[::-1][live], rtol=5e-4)
+    P = rng.standard_normal((16, D))
+    assert rel(P - (P @ W.T) @ W, P - (P @ eff.W.T) @ eff.W) < TOL
+    for _ in range(3):
+        M = data(rng, N, D)
+        expect, _, _ = eff.precondition(M)
+        got, _, _ = gpu_call(torch, pre, M)
+        assert rel(got, expect) < TOL
