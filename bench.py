@@ -647,11 +647,10 @@ def main():
     ap.add_argument("--no-simple", action="store_true", help="skip the simple-method leg (App. A)")
     ap.add_argument("--precond-only", action="store_true",
                     help="run only the preconditioner microbenchmark (BASELINE configs[2]); used for its profile")
+    ap.add_argument("--wide-only", action="store_true",
+                    help="run only the configs[3] leg (wider tanh DNN); used for its profile")
     ap.add_argument("--simple-only", action="store_true",
                     help="run only the simple-method leg (App. A); used for its profile")
-    ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run one plain 256 MiB device-to-device copy (the known-size reference for scaling "
-                         "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py measures one GPU: this build has no multi-GPU path (replicas only exchange parameters "
@@ -662,21 +661,19 @@ def main():
         log("bench.py needs a GPU")
         sys.exit(1)
     torch.cuda.set_device(0)
+    # (the 1 GiB device-to-device copy timed here is also the known-size reference for scaling the FETCH_SIZE /
+    # WRITE_SIZE counters of a rocprofv3 --pmc run of this file: it reads 1 GiB and writes 1 GiB)
+    peaks = machine_peaks()
     if args.precond_only:
-        print(json.dumps({"precondition_roofline": run_precond_bench()}), flush=True)
+        print(json.dumps({"precondition_roofline": run_precond_bench(), "machine_peaks": peaks}), flush=True)
+        return
+    if args.wide_only:
+        print(json.dumps({"wide_tanh_net": run_wide_bench(), "machine_peaks": peaks}), flush=True)
         return
     if args.simple_only:
-        print(json.dumps({"simple_method": run_simple_bench()}), flush=True)
+        print(json.dumps({"simple_method": run_simple_bench(), "machine_peaks": peaks}), flush=True)
         return
-    peaks = machine_peaks()
     spec, ms_per_step, frames_per_s, roofline, breakdown, final_logp, timing, step_roofline = run_step_bench(args)
-    if args.calibrate_copy:
-        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
-        dst = torch.empty_like(src)
-        torch.cuda.synchronize()
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
     precond = None if args.no_precond else run_precond_bench()
     tiny = run_c0_bench()
     wide = None if args.no_wide else run_wide_bench()

@@ -91,12 +91,19 @@ __global__ void copy2d_kernel(const float* __restrict__ src, int lds_, float* __
     dst[(size_t)row * ldd + c] = s * src[(size_t)row * lds_ + c];
 }
 
+// Rows are 16-byte aligned and ld is a multiple of 4 (checked by the callers): 16 bytes per lane, tail by elements.
 __global__ void scale_rows_kernel(float* __restrict__ M, int ld, int N, int D, const double* __restrict__ gamma) {
   const int row = blockIdx.y;
   if (row >= N) return;   // the grid's second dimension is the row count
   const float s = (float)(*gamma);
-  for (int c = blockIdx.x * blockDim.x + threadIdx.x; c < D; c += gridDim.x * blockDim.x)
-    M[(size_t)row * ld + c] *= s;
+  float* m = M + (size_t)row * ld;
+  const int d4 = D & ~3;
+  for (int c = 4 * (blockIdx.x * blockDim.x + threadIdx.x); c < d4; c += 4 * gridDim.x * blockDim.x) {
+    float4 v = *reinterpret_cast<float4*>(m + c);
+    v.x *= s; v.y *= s; v.z *= s; v.w *= s;
+    *reinterpret_cast<float4*>(m + c) = v;
+  }
+  if (blockIdx.x == 0 && threadIdx.x < D - d4) m[d4 + threadIdx.x] *= s;
 }
 
 // ---- nonlinearities ------------------------------------------------------------------------------
@@ -437,7 +444,6 @@ __global__ __launch_bounds__(1024) void finish_apply_kernel(const FinishGroup g)
   }
   double t = 0.0;
   for (int i = threadIdx.x; i < a.n_sumsq; i += blockDim.x) t += a.sumsq_part[i];
-  const double tr_M = block_sum(t, scratch);
   // four lanes share a row: each adds every fourth column tile (independent loads), then the quad is combined
   const int part = threadIdx.x & 3;
   const int N = a.N, nct = a.n_col_tiles;
@@ -462,6 +468,7 @@ __global__ __launch_bounds__(1024) void finish_apply_kernel(const FinishGroup g)
       ph += p;
     }
   }
+  const double tr_M = block_sum(t, scratch);      // (reduced after the row loop: all loads of the kernel are in flight together)
   const double tr_Mhat = block_sum(ph, scratch);
   const double gamma = tr_Mhat > 0.0 ? sqrt(tr_M / tr_Mhat) : 1.0;
   if (threadIdx.x == 0) {
