@@ -15,10 +15,10 @@
 // Exchange between workgroups.  The dies of the chip have separate L2 caches, and a device-wide fence writes the
 // die's L2 back and invalidates it: measured here, two such fences per thread cost 27 us of a 58 us launch, and even
 // one release / acquire pair per workgroup cost 8 us.  The exchange therefore uses nothing but operations that are
-// performed at the memory side: float atomics for H, an atomic counter, and loads of H that bypass the caches
-// (system-coherent buffer loads).  Order is kept by construction: every wavefront waits until its atomics have been
-// acknowledged (s_waitcnt) before the workgroup's barrier, the counter is incremented after that barrier, and H is
-// loaded after the counter has been seen complete.
+// performed at the memory side: float atomics for H (with return, see below), an atomic counter, and loads of H at
+// device scope that bypass this die's caches.  Order is kept by construction: every wavefront waits until its atomics
+// have returned their old values before the workgroup's barrier, the counter is incremented after that barrier, and
+// H is loaded after the counter has been seen complete.
 //
 // Progress.  The workgroups of a row block only wait for each other, and the grid is ordered row block by row
 // block, so a launch on its own always makes progress: on every die workgroups are started in index order, hence the
@@ -177,16 +177,25 @@ __global__ __launch_bounds__(kFusedThreads, (RC <= 80 ? 3 : 2)) void fused_apply
     __builtin_amdgcn_sched_barrier(0);   // one 16-column group at a time: keeps the operand fragments of later groups out of registers
   }
   // register q of lane (r16, g4) holds H[row block row 16 wave + 4 g4 + q][16 tj + r16]
+  // The atomics return the old value: a wavefront then knows that its additions have been performed where all dies
+  // see them once the values are back, which the acknowledgement of an atomic without return does not guarantee (with
+  // other kernels loading the memory system the arrival counter was seen to overtake such additions).
   if (!(TIMING & 1)) {
+    float old[TJ][4];
 #pragma unroll
     for (int tj = 0; tj < TJ; ++tj) {
       const int j = 16 * tj + r16;
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const int hrow = rb * kFusedRows + wave * 16 + 4 * g4 + q;
-        if (hrow < N && j < R) unsafeAtomicAdd(P.H + (size_t)hrow * P.ldh + j, tot[tj][q]);
+        old[tj][q] = 0.f;
+        if (hrow < N && j < R) old[tj][q] = unsafeAtomicAdd(P.H + (size_t)hrow * P.ldh + j, tot[tj][q]);
       }
     }
+#pragma unroll
+    for (int tj = 0; tj < TJ; ++tj)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) asm volatile("" : : "v"(old[tj][q]));   // the returned value must have arrived here
   }
   {
     double s = (double)ssq;
@@ -194,8 +203,8 @@ __global__ __launch_bounds__(kFusedThreads, (RC <= 80 ? 3 : 2)) void fused_apply
     for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
     if (lane == 0) red[wave] = s;
   }
-  // every atomic of this wavefront has been acknowledged by the memory side before the barrier lets thread 0 count
-  // the workgroup's arrival (a workgroup-scope release: a wait on the memory counters, no cache maintenance)
+  // every atomic of this wavefront has returned before the barrier lets thread 0 count the workgroup's arrival
+  // (a workgroup-scope release: a wait on the memory counters, no cache maintenance)
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
   __syncthreads();
   if (tid == 0) {
