@@ -329,7 +329,7 @@ hipError_t launch_h(const GemmDesc* d, int n, hipStream_t s) {
 template <int RC>
 hipError_t launch_j(const GemmDesc* d, int n, hipStream_t s) {
   if (RC == 32) return launch_gemm_group<32, 32, 32, 2, 2, false, false, EPI_STORE, false, 0, true>(d, n, s);
-  return launch_gemm_group<RC, 64, 32, 1, 4, false, false, EPI_STORE, false, 0, true>(d, n, s);
+  return launch_gemm_group<RC, 32, 32, 1, 2, false, false, EPI_STORE, false, 0, true>(d, n, s);
 }
 // W_{t+1} = A_t B_t
 template <int RC>
@@ -601,8 +601,12 @@ int launch_fused_apply(std::vector<PrecondCall>& list, hipStream_t s) {
 
 // With hj_ready the caller has already produced H and J of every instance (all due for an update, none at t = 0)
 // and ordered s behind them; only Xhat and gamma remain.
+// do_products / do_finish select the two halves of the work on the matrices (the products; the reduction of the
+// partial sums to gamma and the row norms), so that a caller can issue the products of different instances at
+// different times and reduce once.
 int precond_apply(std::vector<PrecondCall>& calls, bool scale_output, hipStream_t s,
-                  std::vector<PrecondCall>& to_update_out, bool hj_ready = false) {
+                  std::vector<PrecondCall>& to_update_out, bool hj_ready = false, bool do_products = true,
+                  bool do_finish = true) {
   std::vector<PrecondCall> full, to_init, to_update;
   for (auto& c : calls) {
     ngsgd_precond& p = *c.p;
@@ -625,7 +629,9 @@ int precond_apply(std::vector<PrecondCall>& calls, bool scale_output, hipStream_
   // No factor is updated by this call: one fused pass per matrix instead of the H and Xhat products.
   bool fused = !hj_ready && to_update.empty() && !full.empty();
   for (auto& c : full) fused = fused && fused_fits(*c.p, c.N);
-  if (fused) {
+  if (!do_products) {
+    // the caller has issued the products already
+  } else if (fused) {
     NG_TRY(clear_accumulators(full, s));
     NG_TRY(launch_fused_apply(full, s));
   } else if (!hj_ready) {
@@ -635,7 +641,7 @@ int precond_apply(std::vector<PrecondCall>& calls, bool scale_output, hipStream_
     NG_TRY(launch_j_products(to_update, s));
   }
   // Xhat = X - H W   (eq. hatxt:compute:2), row-norm partials (eq. pi)
-  if (!fused) {
+  if (!fused && do_products && !full.empty()) {
     std::vector<GemmDesc> d;
     for (auto& c : full) {
       ngsgd_precond& p = *c.p;
@@ -651,7 +657,7 @@ int precond_apply(std::vector<PrecondCall>& calls, bool scale_output, hipStream_
     HIP_TRY((launch_gemm_group<64, 64, BK, 2, 2, true, false, EPI_SUB_ROWNORM, false>(d.data(), (int)d.size(), s)));
   }
   // gamma_t, tr(X X^T), tr(Xhat Xhat^T)
-  for (size_t done = 0; done < full.size();) {
+  for (size_t done = 0; do_finish && done < full.size();) {
     ProfScope prof(NGSGD_PROF_PRECOND_MISC, s);
     FinishGroup g;
     const int n = (int)std::min<size_t>(kMaxInstances, full.size() - done);
@@ -681,7 +687,7 @@ int precond_apply(std::vector<PrecondCall>& calls, bool scale_output, hipStream_
     LAUNCH_CHECK();
     done += n;
   }
-  if (scale_output) {
+  if (scale_output && do_finish) {
     ProfScope prof(NGSGD_PROF_PRECOND_MISC, s);
     for (auto& c : full) {
       ngsgd_precond& p = *c.p;
@@ -690,7 +696,7 @@ int precond_apply(std::vector<PrecondCall>& calls, bool scale_output, hipStream_
       LAUNCH_CHECK();
     }
   }
-  to_update_out.insert(to_update_out.end(), to_update.begin(), to_update.end());
+  if (do_products) to_update_out.insert(to_update_out.end(), to_update.begin(), to_update.end());
   return NGSGD_OK;
 }
 
@@ -1687,10 +1693,15 @@ extern "C" int ngsgd_step(ngsgd_net* net, const float* dev_x, const int32_t* dev
     }
     // Xhat and gamma behind every group's H and J; the second half of each group's factor update is enqueued
     // after the rest of this step so that the caller's stream is never short of work
-    for (int k = 0; k < kSideStreams; ++k)
-      if (!early_calls[k].empty()) HIP_TRY(hipStreamWaitEvent(s, net->side[k].hj_done, 0));
+    // (the group whose matrices appeared last is still busy with H and J when the backward pass ends: the Xhat
+    // products of the other groups go first)
     std::vector<PrecondCall> due;
-    NG_TRY(precond_apply(calls, false, s, due, true));
+    for (int k = 0; k < kSideStreams; ++k) {
+      if (early_calls[k].empty()) continue;
+      HIP_TRY(hipStreamWaitEvent(s, net->side[k].hj_done, 0));
+      NG_TRY(precond_apply(early_calls[k], false, s, due, true, true, false));
+    }
+    NG_TRY(precond_apply(calls, false, s, due, true, false, true));
     for (int k = 0; k < kSideStreams; ++k)
       if (!early_calls[k].empty()) HIP_TRY(hipEventRecord(net->side[k].outputs_done, s));
     for (auto& c : calls) c.p->t += 1;
