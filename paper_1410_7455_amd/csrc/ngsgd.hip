@@ -823,7 +823,7 @@ int factor_finish(std::vector<PrecondCall>& to_update, hipStream_t s) {
       r_max = std::max(r_max, p.rank);
     }
     og.count = n;
-    const size_t dyn = (size_t)2 * r_max * (r_max | 1) * sizeof(double);   // the factor L and its inverse
+    const size_t dyn = (size_t)r_max * (2 * r_max + 1) * sizeof(double);   // the augmented matrix [O | E^{-1/2} A_t]
     auto launch_new_factor = [&](const bool only_if_reorthogonalised) -> int {
       for (int rc : {32, 80, 96}) {
         std::vector<GemmDesc> d;

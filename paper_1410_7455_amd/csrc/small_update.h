@@ -557,17 +557,19 @@ __global__ __launch_bounds__(kSmallThreads) void orth_fix_kernel(const OrthGroup
   if (!(st->flags & kFlagOrthCheck)) return;   // uniform over the workgroup
   const int R = a.R;
   const int tid = threadIdx.x, nt = blockDim.x;
-  const int Rs = R | 1;
-  double* O = dyn;                    // R x Rs, becomes L, later holds A_t
+  // The augmented matrix [O | B], R x 2R with row stride S: O = E^{-1/2} (W W^T) E^{-1/2} (full, symmetric) and
+  // B = E^{-1/2} A_t.  Gaussian elimination without pivoting (O is symmetric positive definite) turns O into
+  // D L1^T and B into L1^{-1} B, where O = L1 D L1^T with unit lower triangular L1; the Cholesky factor is
+  // L = L1 D^{1/2}, so L^{-1} B = D^{-1/2} (L1^{-1} B).  One barrier per eliminated column.
+  const int S = 2 * R + 1;
+  double* M = dyn;
 
   double dev = 0.0;
   for (int idx = tid; idx < R * R; idx += nt) {
     const int i = idx / R, j = idx % R;
-    if (j <= i) {
-      const double s = 0.5 * (a.G[i * R + j] + a.G[j * R + i]) / sqrt(st->e[i] * st->e[j]);
-      O[i * Rs + j] = s;
-      dev = fmax(dev, fabs(s - (i == j ? 1.0 : 0.0)));
-    }
+    const double o = 0.5 * (a.G[i * R + j] + a.G[j * R + i]) / sqrt(st->e[i] * st->e[j]);
+    M[i * S + j] = o;
+    dev = fmax(dev, fabs(o - (i == j ? 1.0 : 0.0)));
   }
   dev = block_max(dev, scratch);
   if (!(dev > kOrthoTolerance)) {
@@ -575,51 +577,28 @@ __global__ __launch_bounds__(kSmallThreads) void orth_fix_kernel(const OrthGroup
     if (tid == 0) st->flags &= ~kFlagOrthCheck;
     return;
   }
-  __syncthreads();
-  // Cholesky O = L L^T in place (lower triangle), right-looking: scale column j, then every thread takes its
-  // share of the rank-1 update of the trailing triangle
-  for (int j = 0; j < R; ++j) {
-    const double pivot = sqrt(fmax(O[j * Rs + j], 1.0e-300));
-    __syncthreads();   // everyone has read the old diagonal entry
-    for (int i = j + tid; i < R; i += nt) O[i * Rs + j] = i == j ? pivot : O[i * Rs + j] / pivot;
-    __syncthreads();
-    const int rem = R - j - 1;   // trailing rows / columns j+1 .. R-1
-    for (int idx = tid; idx < rem * rem; idx += nt) {
-      const int i = j + 1 + idx / rem, k = j + 1 + idx % rem;
-      if (k <= i) O[i * Rs + k] -= O[i * Rs + j] * O[k * Rs + j];
-    }
-    __syncthreads();
-  }
   // The fix W <- E^{1/2} L^{-1} E^{-1/2} W is applied to the factor it came from: W = A_t B_t, so the triangular
   // mixing matrix goes into A_t and the product with B_t (still in its buffer) is simply launched again, gated on
-  // the flag set below.  L^{-1}: thread j solves column j by forward substitution (entries i >= j).
-  double* X = dyn + (size_t)R * Rs;   // R x Rs
-  for (int idx = tid; idx < R * Rs; idx += nt) X[idx] = 0.0;
-  __syncthreads();
-  if (tid < R) {
-    const int j = tid;
-    for (int i = j; i < R; ++i) {
-      double s0 = i == j ? 1.0 : 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
-      int k = j;
-      for (; k + 4 <= i; k += 4) {
-        s0 -= O[i * Rs + k] * X[k * Rs + j];
-        s1 -= O[i * Rs + k + 1] * X[(k + 1) * Rs + j];
-        s2 -= O[i * Rs + k + 2] * X[(k + 2) * Rs + j];
-        s3 -= O[i * Rs + k + 3] * X[(k + 3) * Rs + j];
-      }
-      for (; k < i; ++k) s0 -= O[i * Rs + k] * X[k * Rs + j];
-      X[i * Rs + j] = ((s0 + s1) + (s2 + s3)) / O[i * Rs + i];   // only this thread reads column j
-    }
-  }
-  __syncthreads();
-  // A_t into the space of L (no longer needed), then A_t <- (E^{1/2} L^{-1} E^{-1/2}) A_t
-  for (int idx = tid; idx < R * R; idx += nt) O[(idx / R) * Rs + idx % R] = (double)a.At[(idx / R) * a.ldat + idx % R];
-  __syncthreads();
+  // the flag set below.
   for (int idx = tid; idx < R * R; idx += nt) {
     const int i = idx / R, k = idx % R;
-    double acc = 0.0;
-    for (int j = 0; j <= i; ++j) acc += X[i * Rs + j] * rsqrt(st->e[j]) * O[j * Rs + k];
-    a.At[i * a.ldat + k] = (float)(sqrt(st->e[i]) * acc);
+    M[i * S + R + k] = (double)a.At[i * a.ldat + k] * rsqrt(st->e[i]);
+  }
+  __syncthreads();
+  for (int k = 0; k < R - 1; ++k) {
+    // rows below k, columns right of k (column k itself becomes zero and is not needed again)
+    const int rows = R - 1 - k, cols = 2 * R - 1 - k;
+    const double inv_p = 1.0 / fmax(M[k * S + k], 1.0e-300);
+    for (int idx = tid; idx < rows * cols; idx += nt) {
+      const int i = k + 1 + idx / cols, j = k + 1 + idx % cols;
+      M[i * S + j] -= M[i * S + k] * inv_p * M[k * S + j];
+    }
+    __syncthreads();
+  }
+  for (int idx = tid; idx < R * R; idx += nt) {
+    const int i = idx / R, k = idx % R;
+    const double d = fmax(M[i * S + i], 1.0e-300);        // pivot i = D_ii
+    a.At[i * a.ldat + k] = (float)(sqrt(st->e[i]) * rsqrt(d) * M[i * S + R + k]);
   }
   if (tid == 0) st->flags = (st->flags & ~kFlagOrthCheck) | kFlagReorth;
 }
