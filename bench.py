@@ -78,7 +78,7 @@ def measured_traffic_per_launch(category):
         if re.search(pattern, line):
             cols = line.split()
             try:
-                n, read_mb, write_mb = float(cols[-5]), float(cols[-2]), float(cols[-1])
+                n, read_mb, write_mb = float(cols[-7]), float(cols[-2]), float(cols[-1])
             except (ValueError, IndexError):
                 continue
             calls += n
