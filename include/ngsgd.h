@@ -201,7 +201,9 @@ int ngsgd_join(ngsgd_net* net, void* hip_stream);
  * preconditioners are reset, as the paper's re-spawned processes do (App. B.3.2).
  * The replicas may have been stepped on other streams than hip_stream: the averaging kernel waits (on
  * the device) for each replica's latest ngsgd_step and factor updates, and each replica's next call
- * waits for the averaged weights, so the caller needs no synchronisation of its own. */
+ * waits for the averaged weights, so the caller needs no synchronisation of its own.  (The call records an
+ * event on the stream of each replica's latest ngsgd_step: those streams must still exist, and no other
+ * host thread may be enqueuing a step of these replicas during the call.) */
 int ngsgd_average(ngsgd_net* const* nets, int32_t n, int32_t reset_preconditioners, void* hip_stream);
 
 /* Weights of one layer as a dense dims[layer+1] x (in_dim+1) row-major matrix, bias last. */

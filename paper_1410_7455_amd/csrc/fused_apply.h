@@ -152,51 +152,60 @@ __global__ __launch_bounds__(kFusedThreads, (RC <= 80 ? 3 : 2)) void fused_apply
   }
   __syncthreads();
 
-  // ---- phase 1: this patch's part of H = X W^T, in two MFMA chains summed with an ordinary add ---------------
-  floatx4 acc[TJ], tot[TJ];
-#pragma unroll
-  for (int tj = 0; tj < TJ; ++tj) acc[tj] = tot[tj] = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-  for (int kk = 0; kk < KK; ++kk) {
-    float4 bf[TJ];
-#pragma unroll
-    for (int tj = 0; tj < TJ; ++tj)
-      bf[tj] = *reinterpret_cast<const float4*>(&Ws[(16 * tj + r16) * LDW + 16 * kk + 4 * g4]);
-#pragma unroll
-    for (int q = 0; q < 4; ++q)
-#pragma unroll
-      for (int tj = 0; tj < TJ; ++tj)
-        acc[tj] = __builtin_amdgcn_mfma_f32_16x16x4f32(pick4(xr[kk], q), pick4(bf[tj], q), acc[tj], 0, 0, 0);
-    if (kk == KK / 2 - 1 || kk == KK - 1) {
-#pragma unroll
-      for (int tj = 0; tj < TJ; ++tj) {
-        tot[tj] += acc[tj];
-        acc[tj] = floatx4{0.f, 0.f, 0.f, 0.f};
-      }
-    }
-    __builtin_amdgcn_sched_barrier(0);   // one 16-column group at a time: keeps the operand fragments of later groups out of registers
-  }
-  // register q of lane (r16, g4) holds H[row block row 16 wave + 4 g4 + q][16 tj + r16]
+  // ---- phase 1: this patch's part of H = X W^T --------------------------------------------------------------
+  // Two 16-wide tiles of the rank at a time, each in two MFMA chains (even and odd 16-column groups) that are
+  // summed with an ordinary add: the chains stay short (the matrix unit does not round its accumulator additions
+  // to nearest) and consecutive MFMAs never depend on each other.  The additions to H of a pair of tiles are
+  // issued as soon as the pair is complete, so that they travel while the next pair is being multiplied.
+  // Register q of lane (r16, g4) holds H[row block row 16 wave + 4 g4 + q][16 tj + r16].
   // The atomics return the old value: a wavefront then knows that its additions have been performed where all dies
   // see them once the values are back, which the acknowledgement of an atomic without return does not guarantee (with
   // other kernels loading the memory system the arrival counter was seen to overtake such additions).
-  if (!(TIMING & 1)) {
-    float old[TJ][4];
+  static_assert(KK % 2 == 0, "column groups are taken in pairs");
+  float old[TJ][4];
 #pragma unroll
-    for (int tj = 0; tj < TJ; ++tj) {
+  for (int tj0 = 0; tj0 < TJ; tj0 += 2) {
+    constexpr int kPair = 2;
+    floatx4 ch[kPair][2];
+#pragma unroll
+    for (int t = 0; t < kPair; ++t) ch[t][0] = ch[t][1] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < KK; kk += 2) {
+      float4 bf[kPair][2];
+#pragma unroll
+      for (int t = 0; t < kPair; ++t)
+#pragma unroll
+        for (int par = 0; par < 2; ++par)
+          if (tj0 + t < TJ)
+            bf[t][par] = *reinterpret_cast<const float4*>(&Ws[(16 * (tj0 + t) + r16) * LDW + 16 * (kk + par) + 4 * g4]);
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int par = 0; par < 2; ++par)
+#pragma unroll
+          for (int t = 0; t < kPair; ++t)
+            if (tj0 + t < TJ)
+              ch[t][par] = __builtin_amdgcn_mfma_f32_16x16x4f32(pick4(xr[kk + par], q), pick4(bf[t][par], q), ch[t][par], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);   // two 16-column groups at a time: keeps the fragments of later groups out of registers
+    }
+#pragma unroll
+    for (int t = 0; t < kPair; ++t) {
+      if (tj0 + t >= TJ) continue;
+      const int tj = tj0 + t;
+      const floatx4 tot = ch[t][0] + ch[t][1];
       const int j = 16 * tj + r16;
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const int hrow = rb * kFusedRows + wave * 16 + 4 * g4 + q;
         old[tj][q] = 0.f;
-        if (hrow < N && j < R) old[tj][q] = unsafeAtomicAdd(P.H + (size_t)hrow * P.ldh + j, tot[tj][q]);
+        if (!(TIMING & 1) && hrow < N && j < R) old[tj][q] = unsafeAtomicAdd(P.H + (size_t)hrow * P.ldh + j, tot[q]);
       }
     }
-#pragma unroll
-    for (int tj = 0; tj < TJ; ++tj)
-#pragma unroll
-      for (int q = 0; q < 4; ++q) asm volatile("" : : "v"(old[tj][q]));   // the returned value must have arrived here
   }
+#pragma unroll
+  for (int tj = 0; tj < TJ; ++tj)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) asm volatile("" : : "v"(old[tj][q]));   // the returned value must have arrived here
   {
     double s = (double)ssq;
 #pragma unroll
@@ -250,43 +259,48 @@ __global__ __launch_bounds__(kFusedThreads, (RC <= 80 ? 3 : 2)) void fused_apply
   }
 
   // ---- phase 2: Xhat^T = X^T - W^T H^T with the registers of X as the accumulator -----------------------------
-  floatx4 xa[KK];
-#pragma unroll
-  for (int cc = 0; cc < KK; ++cc) xa[cc] = floatx4{xr[cc].x, xr[cc].y, xr[cc].z, xr[cc].w};
-#pragma unroll
-  for (int jj = 0; jj < TJ; ++jj) {
-#pragma unroll
-    for (int cc = 0; cc < KK; ++cc) {
-      const float* wp = &Ws[(16 * jj + 4 * g4) * LDW + 16 * cc + r16];
-      const float w0 = wp[0], w1 = wp[LDW], w2 = wp[2 * LDW], w3 = wp[3 * LDW];
-      xa[cc] = __builtin_amdgcn_mfma_f32_16x16x4f32(w0, hb[jj].x, xa[cc], 0, 0, 0);
-      xa[cc] = __builtin_amdgcn_mfma_f32_16x16x4f32(w1, hb[jj].y, xa[cc], 0, 0, 0);
-      xa[cc] = __builtin_amdgcn_mfma_f32_16x16x4f32(w2, hb[jj].z, xa[cc], 0, 0, 0);
-      xa[cc] = __builtin_amdgcn_mfma_f32_16x16x4f32(w3, hb[jj].w, xa[cc], 0, 0, 0);
-      if (cc & 1) __builtin_amdgcn_sched_barrier(0);   // two column groups at a time (see phase 1)
-    }
-  }
-
-  // ---- Xhat out, squared row norms over this chunk (eq. pi) -----------------------------------------------------
+  // Two 16-column groups at a time (two independent MFMA chains); a pair is stored as soon as it is complete, so
+  // the stores of one pair travel while the next is being multiplied.  Squared row norms over this chunk (eq. pi).
   float sq = 0.f;
-  if (row_ok) {
-    float* orow = P.Xout + (size_t)row * P.ldo;
+  float* const orow = P.Xout + (size_t)min(row, N - 1) * P.ldo;
 #pragma unroll
-    for (int cc = 0; cc < KK; ++cc) {
-      const int col = c0 + 16 * cc + 4 * g4;
-      const floatx4 v = xa[cc];
-      if (col + 3 < D) {
-        *reinterpret_cast<float4*>(orow + col) = make_float4(v[0], v[1], v[2], v[3]);
-        sq += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
-      } else {
+  for (int cc0 = 0; cc0 < KK; cc0 += 2) {
+    floatx4 xa[2];
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
-          if (col + q < D) {
-            orow[col + q] = v[q];
-            sq += v[q] * v[q];
-          }
+    for (int u = 0; u < 2; ++u) xa[u] = floatx4{xr[cc0 + u].x, xr[cc0 + u].y, xr[cc0 + u].z, xr[cc0 + u].w};
+#pragma unroll
+    for (int jj = 0; jj < TJ; ++jj) {
+      float w[2][4];
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const float* wp = &Ws[(16 * jj + 4 * g4) * LDW + 16 * (cc0 + u) + r16];
+        w[u][0] = wp[0]; w[u][1] = wp[LDW]; w[u][2] = wp[2 * LDW]; w[u][3] = wp[3 * LDW];
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+          xa[u] = __builtin_amdgcn_mfma_f32_16x16x4f32(w[u][q], pick4(hb[jj], q), xa[u], 0, 0, 0);
+    }
+    if (row_ok) {
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        const int col = c0 + 16 * (cc0 + u) + 4 * g4;
+        const floatx4 v = xa[u];
+        if (col + 3 < D) {
+          *reinterpret_cast<float4*>(orow + col) = make_float4(v[0], v[1], v[2], v[3]);
+          sq += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+        } else {
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+            if (col + q < D) {
+              orow[col + q] = v[q];
+              sq += v[q] * v[q];
+            }
+        }
       }
     }
+    __builtin_amdgcn_sched_barrier(0);   // one pair at a time
   }
   sq += __shfl_xor(sq, 16);
   sq += __shfl_xor(sq, 32);

@@ -1298,7 +1298,9 @@ struct ngsgd_net {
   SideSync side[kSideStreams];
   int n_side = kSideStreams;   // streams in use
   // ordering between the stream that steps this replica and a stream that averages it with others
-  hipEvent_t step_done = nullptr;   // recorded at the end of every step on the step's stream
+  hipEvent_t step_done = nullptr;   // recorded by an averaging call on the stream of the latest step (an event per
+                                    // step would cost every step a marker packet on its critical stream)
+  hipStream_t step_stream = nullptr;
   bool stepped = false;
   hipEvent_t avg_done = nullptr;    // recorded behind an averaging kernel that rewrote the weights
   bool avg_pending = false;
@@ -1741,7 +1743,7 @@ extern "C" int ngsgd_step(ngsgd_net* net, const float* dev_x, const int32_t* dev
   }
   net->last_N = N;
   net->last_lr = lr;
-  HIP_TRY(hipEventRecord(net->step_done, s));   // what an averaging call on another stream waits for
+  net->step_stream = s;   // an averaging call on another stream orders itself behind this stream's work so far
   net->stepped = true;
   return NGSGD_OK;
 }
@@ -1766,7 +1768,10 @@ extern "C" int ngsgd_average(ngsgd_net* const* nets, int32_t n, int32_t reset_pr
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   for (int i = 0; i < n; ++i) {
     // behind the replica's latest step (whatever stream it ran on), its factor updates and an earlier averaging
-    if (nets[i]->stepped) HIP_TRY(hipStreamWaitEvent(s, nets[i]->step_done, 0));
+    if (nets[i]->stepped && nets[i]->step_stream != s) {
+      HIP_TRY(hipEventRecord(nets[i]->step_done, nets[i]->step_stream));
+      HIP_TRY(hipStreamWaitEvent(s, nets[i]->step_done, 0));
+    }
     NG_TRY(order_after_average(nets[i], s, false));
     for (SideSync& sd : nets[i]->side) NG_TRY(join_side(&sd, s));
   }
