@@ -403,6 +403,10 @@ struct FinishArgs {
   const float* W;            // R x D
   const float* H;            // N x ldh, final
   int ldx, ldw, ldh, D, R, chunk_cols;
+  // what the fused apply kernel accumulated into (arrival counters and H, contiguous): cleared on exit, so that the
+  // next call without a factor update needs no clearing launch in front of it (nullptr: left as it is)
+  float* clear_ptr;
+  int clear_floats;          // a multiple of 4
 };
 struct FinishGroup {
   int count;
@@ -480,6 +484,10 @@ __global__ __launch_bounds__(1024) void finish_apply_kernel(const FinishGroup g)
   if (a.rownorm2_out != nullptr) {
     __syncthreads();   // prow was written by other lanes
     for (int r = threadIdx.x; r < N; r += blockDim.x) a.rownorm2_out[r] = (float)(gamma * gamma * a.prow[r]);
+  }
+  if (a.clear_ptr != nullptr) {   // (every read of H and of the deferred count lies before a barrier above)
+    float4* z = reinterpret_cast<float4*>(a.clear_ptr);
+    for (int i = threadIdx.x; i < a.clear_floats / 4; i += blockDim.x) z[i] = make_float4(0.f, 0.f, 0.f, 0.f);
   }
 }
 

@@ -133,6 +133,8 @@ struct ngsgd_precond {
   int ldh = 0;   // leading dimension of H and A_t (= rank class)
   PrecondScalars* st = nullptr;
   float* zero_region = nullptr;   // [arrival counters, deferred count | H | K | L], cleared before each call
+  int clean_rows = 0;             // the counters and this many rows of H are known to be clear (left so by the
+                                  // finishing kernel of a call that went through the fused apply kernel)
   size_t zero_floats_all = 0;
   size_t arrive_slots = 0;        // arrival counters of the fused apply kernel, one per block of 64 rows, and
   int* arrive = nullptr;          // (last slot) the number of patches it deferred; padded to 256 bytes
@@ -459,10 +461,11 @@ int precond_validate(const std::vector<PrecondCall>& calls) {
 
 inline bool factor_due(const ngsgd_precond& p) { return p.t < p.always_update_first || p.t % p.update_period == 0; }
 
-// Clears the accumulation buffers of the listed instances (H always; K, L when the factor is updated).
-int clear_accumulators(const std::vector<PrecondCall>& list, hipStream_t s) {
+// Clears the accumulation buffers of the listed instances (H always; K, L when the factor is updated).  With
+// `keep_clean` (the fused apply path, whose finishing kernel clears what it used) an instance whose counters and
+// H rows are still clear is skipped, and no kernel is launched when that holds for all of them.
+int clear_accumulators(const std::vector<PrecondCall>& list, hipStream_t s, bool keep_clean = false) {
   for (size_t done = 0; done < list.size();) {
-    ProfScope prof(NGSGD_PROF_PRECOND_MISC, s);
     FillGroup fg;
     const int n = (int)std::min<size_t>(kMaxInstances, list.size() - done);
     fg.count = n;
@@ -472,12 +475,16 @@ int clear_accumulators(const std::vector<PrecondCall>& list, hipStream_t s) {
       ngsgd_precond& p = *c.p;
       fg.ptr[i] = reinterpret_cast<uint32_t*>(p.zero_region);
       fg.n[i] = factor_due(p) ? p.zero_floats_all : p.arrive_slots + (size_t)c.N * p.ldh;
+      if (keep_clean && p.clean_rows >= c.N) fg.n[i] = 0;
+      if (!keep_clean) p.clean_rows = 0;   // the caller is about to accumulate into H and leaves it that way
       n_max = std::max(n_max, fg.n[i]);
     }
+    done += n;
+    if (n_max == 0) continue;
+    ProfScope prof(NGSGD_PROF_PRECOND_MISC, s);
     const unsigned blocks = (unsigned)std::min<size_t>((n_max + 2047) / 2048, 64);
     hipLaunchKernelGGL(fill_zero_group_kernel, dim3(blocks > 0 ? blocks : 1, n), dim3(256), 0, s, fg);
     LAUNCH_CHECK();
-    done += n;
   }
   return NGSGD_OK;
 }
@@ -632,7 +639,8 @@ int precond_apply(std::vector<PrecondCall>& calls, bool scale_output, hipStream_
   if (!do_products) {
     // the caller has issued the products already
   } else if (fused) {
-    NG_TRY(clear_accumulators(full, s));
+    NG_TRY(clear_accumulators(full, s, true));
+    for (auto& c : full) c.p->clean_rows = 0;   // until the finishing kernel below has been enqueued
     NG_TRY(launch_fused_apply(full, s));
   } else if (!hj_ready) {
     if (!to_init.empty()) NG_TRY(run_init(to_init, s));
@@ -682,9 +690,13 @@ int precond_apply(std::vector<PrecondCall>& calls, bool scale_output, hipStream_
       a.H = p.H; a.ldh = p.ldh;
       a.D = p.dim; a.R = p.rank;
       a.chunk_cols = kFusedChunk;
+      a.clear_ptr = fused ? p.zero_region : nullptr;
+      a.clear_floats = p.arrive_slots + c.N * p.ldh;
     }
     hipLaunchKernelGGL(finish_apply_kernel, dim3(n), dim3(1024), 0, s, g);
     LAUNCH_CHECK();
+    if (fused)
+      for (int i = 0; i < n; ++i) full[done + i].p->clean_rows = full[done + i].N;
     done += n;
   }
   if (scale_output && do_finish) {
