@@ -240,8 +240,17 @@ int ensure_kernel_attributes() {
                               hipFuncAttributeMaxDynamicSharedMemorySize, max_dyn));
   HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(eig_update_kernel<kEigMaxItems, kEigThreads>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, max_dyn));
-  HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(orth_fix_kernel),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, max_dyn));
+  {
+    const int orth_dyn = kMaxRank * (kMaxRank + 1) * (int)sizeof(double);
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(orth_fix_kernel<6>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, orth_dyn));
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(orth_fix_kernel<12>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, orth_dyn));
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(orth_fix_kernel<20>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, orth_dyn));
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(orth_fix_kernel<24>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, orth_dyn));
+  }
   HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(init_block_solve_kernel),
                               hipFuncAttributeMaxDynamicSharedMemorySize, kInitSolveLds));
   g_attr_done = true;
@@ -835,7 +844,6 @@ int factor_finish(std::vector<PrecondCall>& to_update, hipStream_t s) {
       r_max = std::max(r_max, p.rank);
     }
     og.count = n;
-    const size_t dyn = (size_t)r_max * (2 * r_max + 1) * sizeof(double);   // the augmented matrix [O | E^{-1/2} A_t]
     auto launch_new_factor = [&](const bool only_if_reorthogonalised) -> int {
       for (int rc : {32, 80, 96}) {
         std::vector<GemmDesc> d;
@@ -882,7 +890,17 @@ int factor_finish(std::vector<PrecondCall>& to_update, hipStream_t s) {
       }
       HIP_TRY((launch_gemm_group<64, 64, BK, 2, 2, true, true, EPI_ATOMIC_F64, false, 0, true>(dg.data(),
                                                                                              (int)dg.size(), s)));
-      hipLaunchKernelGGL(orth_fix_kernel, dim3(n), dim3(kSmallThreads), dyn, s, og);
+      const size_t dyn = (size_t)r_max * (r_max + 1) * sizeof(double);   // W W^T of an instance
+      const int cpt = orth_columns_per_thread(r_max);
+      if (cpt <= 6) {
+        hipLaunchKernelGGL(orth_fix_kernel<6>, dim3(n), dim3(kSmallThreads), dyn, s, og);
+      } else if (cpt <= 12) {
+        hipLaunchKernelGGL(orth_fix_kernel<12>, dim3(n), dim3(kSmallThreads), dyn, s, og);
+      } else if (cpt <= 20) {
+        hipLaunchKernelGGL(orth_fix_kernel<20>, dim3(n), dim3(kSmallThreads), dyn, s, og);
+      } else {
+        hipLaunchKernelGGL(orth_fix_kernel<24>, dim3(n), dim3(kSmallThreads), dyn, s, og);
+      }
       LAUNCH_CHECK();
     }
     // where the check failed the kernel has folded the fix into A_t: W_{t+1} = A_t B_t once more for those

@@ -549,27 +549,46 @@ struct OrthGroup {
   OrthArgs a[kMaxInstances];
 };
 
+// The augmented matrix [O | B], R x 2R: O = E^{-1/2} (W W^T) E^{-1/2} (full, symmetric) and B = E^{-1/2} A_t.
+// Gaussian elimination without pivoting (O is symmetric positive definite) turns O into D L1^T and B into
+// L1^{-1} B, where O = L1 D L1^T with unit lower triangular L1; the Cholesky factor is L = L1 D^{1/2}, so
+// L^{-1} B = D^{-1/2} (L1^{-1} B).  The matrix lives in registers: kOrthTPR threads share a row, thread q of a row
+// holds the columns q, q + kOrthTPR, ... (CPT of them: the kernel is instantiated per rank class); what a step needs
+// from other threads (the pivot row, the pivot column and the reciprocal of the pivot) is published in LDS by its
+// owners at the end of the step before, in one of two buffers used alternately.  A step is then one barrier, one
+// LDS read and one multiply-add per element, without branches or address arithmetic; the elimination is bound by
+// the instructions issued, so wavefronts whose rows all lie above the pivot skip the step.
+constexpr int kOrthTPR = 8;
+constexpr int kOrthRowsPerWave = 64 / kOrthTPR;
+static_assert(kMaxRank * kOrthTPR <= kSmallThreads, "one thread group per row");
+inline int orth_columns_per_thread(int R) { return (2 * R + kOrthTPR - 1) / kOrthTPR; }
+
+template <int CPT>
 __global__ __launch_bounds__(kSmallThreads) void orth_fix_kernel(const OrthGroup g) {
-  extern __shared__ __attribute__((aligned(16))) double dyn[];
+  extern __shared__ __attribute__((aligned(16))) double dyn[];   // W W^T of the instance, R x (R + 1)
   __shared__ double scratch[16];
+  __shared__ double s_ise[kMaxRank];                // E_ii^{-1/2}
+  __shared__ double s_prow[2][kOrthTPR * CPT];      // pivot row of a step
+  __shared__ double s_pcol[2][kMaxRank];            // pivot column of a step
+  __shared__ double s_invp[2];                      // reciprocal of the pivot
+  __shared__ double s_dinv[kMaxRank];               // D_ii^{-1/2}
   const OrthArgs& a = g.a[blockIdx.x];
   PrecondScalars* st = a.st;
   if (!(st->flags & kFlagOrthCheck)) return;   // uniform over the workgroup
   const int R = a.R;
   const int tid = threadIdx.x, nt = blockDim.x;
-  // The augmented matrix [O | B], R x 2R with row stride S: O = E^{-1/2} (W W^T) E^{-1/2} (full, symmetric) and
-  // B = E^{-1/2} A_t.  Gaussian elimination without pivoting (O is symmetric positive definite) turns O into
-  // D L1^T and B into L1^{-1} B, where O = L1 D L1^T with unit lower triangular L1; the Cholesky factor is
-  // L = L1 D^{1/2}, so L^{-1} B = D^{-1/2} (L1^{-1} B).  One barrier per eliminated column.
-  const int S = 2 * R + 1;
-  double* M = dyn;
-
+  // the check: G and E through LDS (coalesced reads), O symmetrised from there
+  double* const Gs = dyn;   // R x (R + 1)
+  const int SG = R + 1;
+  for (int idx = tid; idx < R * R; idx += nt) Gs[(idx / R) * SG + idx % R] = a.G[idx];
+  for (int k = tid; k < R; k += nt) s_ise[k] = rsqrt(st->e[k]);
+  __syncthreads();
   double dev = 0.0;
   for (int idx = tid; idx < R * R; idx += nt) {
-    const int i = idx / R, j = idx % R;
-    const double o = 0.5 * (a.G[i * R + j] + a.G[j * R + i]) / sqrt(st->e[i] * st->e[j]);
-    M[i * S + j] = o;
-    dev = fmax(dev, fabs(o - (i == j ? 1.0 : 0.0)));
+    const int r = idx / R, c = idx % R;
+    if (c < r) continue;
+    const double o = 0.5 * (Gs[r * SG + c] + Gs[c * SG + r]) * s_ise[r] * s_ise[c];
+    dev = fmax(dev, fabs(o - (r == c ? 1.0 : 0.0)));
   }
   dev = block_max(dev, scratch);
   if (!(dev > kOrthoTolerance)) {
@@ -580,25 +599,66 @@ __global__ __launch_bounds__(kSmallThreads) void orth_fix_kernel(const OrthGroup
   // The fix W <- E^{1/2} L^{-1} E^{-1/2} W is applied to the factor it came from: W = A_t B_t, so the triangular
   // mixing matrix goes into A_t and the product with B_t (still in its buffer) is simply launched again, gated on
   // the flag set below.
-  for (int idx = tid; idx < R * R; idx += nt) {
-    const int i = idx / R, k = idx % R;
-    M[i * S + R + k] = (double)a.At[i * a.ldat + k] * rsqrt(st->e[i]);
+  const int i = tid / kOrthTPR, q = tid % kOrthTPR;
+  const bool row_ok = i < R;
+  const int ic = min(i, R - 1);
+  const int wave_row0 = (tid >> 6) * kOrthRowsPerWave;   // first row held by this wavefront
+  const double ise_i = s_ise[ic];
+  double v[CPT];
+#pragma unroll
+  for (int c = 0; c < CPT; ++c) {
+    const int j = q + kOrthTPR * c;
+    v[c] = 0.0;
+    if (row_ok && j < R) v[c] = 0.5 * (Gs[i * SG + j] + Gs[j * SG + i]) * ise_i * s_ise[j];
+    if (row_ok && j >= R && j < 2 * R) v[c] = (double)a.At[i * a.ldat + (j - R)] * ise_i;
   }
-  __syncthreads();
+  // What step k reads: row k (with zeros in the columns up to k, which the step must leave alone), column k, and the
+  // reciprocal of the pivot.  Published by their owners while they update for step k - 1: the register of column k
+  // is met in the unrolled loop under a uniform compare, so no register is picked by index.
+  if (row_ok && q == 0) {
+    s_pcol[0][i] = v[0];
+    if (i == 0) s_invp[0] = 1.0 / fmax(v[0], 1.0e-300);
+  }
+  if (i == 0) {
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) s_prow[0][q + kOrthTPR * c] = (q + kOrthTPR * c > 0) ? v[c] : 0.0;
+  }
   for (int k = 0; k < R - 1; ++k) {
-    // rows below k, columns right of k (column k itself becomes zero and is not needed again)
-    const int rows = R - 1 - k, cols = 2 * R - 1 - k;
-    const double inv_p = 1.0 / fmax(M[k * S + k], 1.0e-300);
-    for (int idx = tid; idx < rows * cols; idx += nt) {
-      const int i = k + 1 + idx / cols, j = k + 1 + idx % cols;
-      M[i * S + j] -= M[i * S + k] * inv_p * M[k * S + j];
-    }
+    const int buf = k & 1, nb = buf ^ 1;
     __syncthreads();
+    if (wave_row0 + kOrthRowsPerWave - 1 > k && wave_row0 < R) {   // (uniform over the wavefront) some row lies below k
+      // rows below k, columns right of k (column k itself becomes zero and is not needed again)
+      const double f = (row_ok && i > k) ? s_pcol[buf][ic] * s_invp[buf] : 0.0;
+      double pr[CPT];
+#pragma unroll
+      for (int c = 0; c < CPT; ++c) pr[c] = s_prow[buf][q + kOrthTPR * c];
+      const int kn = k + 1, kc = kn / kOrthTPR, kq = kn % kOrthTPR;
+#pragma unroll
+      for (int c = 0; c < CPT; ++c) {
+        v[c] -= f * pr[c];
+        if (c == kc && row_ok && q == kq && i >= kn) {
+          s_pcol[nb][i] = v[c];
+          if (i == kn) s_invp[nb] = 1.0 / fmax(v[c], 1.0e-300);
+        }
+      }
+      if (i == kn) {
+#pragma unroll
+        for (int c = 0; c < CPT; ++c) s_prow[nb][q + kOrthTPR * c] = (q + kOrthTPR * c > kn) ? v[c] : 0.0;
+      }
+    }
   }
-  for (int idx = tid; idx < R * R; idx += nt) {
-    const int i = idx / R, k = idx % R;
-    const double d = fmax(M[i * S + i], 1.0e-300);        // pivot i = D_ii
-    a.At[i * a.ldat + k] = (float)(sqrt(st->e[i]) * rsqrt(d) * M[i * S + R + k]);
+  // D_ii is the diagonal entry of row i as it stood when the row became the pivot row: rows are not touched afterwards
+#pragma unroll
+  for (int c = 0; c < CPT; ++c)
+    if (row_ok && q + kOrthTPR * c == i) s_dinv[i] = rsqrt(fmax(v[c], 1.0e-300));
+  __syncthreads();
+  if (row_ok) {
+    const double scale = s_dinv[i] / ise_i;   // E_ii^{1/2} D_ii^{-1/2}
+#pragma unroll
+    for (int c = 0; c < CPT; ++c) {
+      const int j = q + kOrthTPR * c;
+      if (j >= R && j < 2 * R) a.At[i * a.ldat + (j - R)] = (float)(scale * v[c]);
+    }
   }
   if (tid == 0) st->flags = (st->flags & ~kFlagOrthCheck) | kFlagReorth;
 }
