@@ -305,6 +305,38 @@ def test_average_replicas(ngsgd):
             assert rel(gpu.last_gradient(l).cpu().numpy(), ora.last["delta"][l]) < TOL
 
 
+def test_average_replicas_on_their_own_streams(ngsgd):
+    """Replicas stepped on streams of their own, averaged on another stream and stepped again, with no host
+    synchronisation in between: the averaging call orders itself behind each replica's latest step (and its factor
+    updates), and each replica's next step behind the averaged weights."""
+    import torch
+    spec = workloads.c0_tiny()   # (its first minibatch has no equal eigenvalues across the rank cut: free running)
+    pairs = [make_pair(ngsgd, spec, side_streams=1) for _ in range(3)]
+    streams = [torch.cuda.Stream() for _ in pairs]
+    data = [[workloads.minibatch(spec, t, replica=r) for t in range(7)] for r in range(len(pairs))]
+    dev = [[(torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda()) for x, y in d] for d in data]
+    outs = [torch.zeros(1, dtype=torch.float64, device="cuda") for _ in pairs]
+    torch.cuda.synchronize()
+    for r, (ora, gpu) in enumerate(pairs):
+        with torch.cuda.stream(streams[r]):
+            for t in range(6):
+                gpu.step(*dev[r][t], spec.lr, outs[r], stream=streams[r])
+        for t in range(6):
+            ora.step(*data[r][t], spec.lr)
+    ngsgd.average([g for _, g in pairs], reset_preconditioners=True)      # on the default stream, at once
+    average_parameters([o for o, _ in pairs])
+    for r, (ora, gpu) in enumerate(pairs):                                  # and on, on the replicas' streams
+        with torch.cuda.stream(streams[r]):
+            gpu.step(*dev[r][6], spec.lr, outs[r], stream=streams[r])
+        obj_o = ora.step(*data[r][6], spec.lr)
+        streams[r].synchronize()
+        assert abs(float(outs[r].item()) - obj_o) / len(data[r][6][1]) < 1e-3
+    torch.cuda.synchronize()
+    for ora, gpu in pairs:
+        for l in range(spec.n_layers):
+            assert rel(gpu.get_params(l).cpu().numpy(), ora.W[l]) < TOL
+
+
 def test_back_to_back_steps_equal_synchronised_steps(ngsgd):
     """The factor updates of a step overlap the following steps on internal streams: steps enqueued back to back
     must give what steps separated by a device synchronisation give.
