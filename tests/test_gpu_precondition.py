@@ -288,7 +288,8 @@ def test_eigenvalues_under_the_floor(ngsgd):
     form is a different map.)"""
     import torch
     from oracle.online_ng_efficient import OnlineNaturalGradientEfficient
-    rng = np.random.default_rng(4)   # (one rank per instantiation of the correction kernel)
+    rng = np.random.default_rng(4)
+    N, D, R = 96, 200, 6
     kw = dict(num_samples_history=300.0, update_period=1)
     warm = OnlineNaturalGradient(D, R, **kw)
     for _ in range(3):
