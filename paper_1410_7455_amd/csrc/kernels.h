@@ -414,7 +414,7 @@ struct FinishGroup {
 };
 
 __global__ __launch_bounds__(1024) void finish_apply_kernel(const FinishGroup g) {
-  __shared__ double scratch[16];
+  __shared__ double scratch[32];
   const FinishArgs& a = g.a[blockIdx.x];
   const int n_deferred = a.deferred_count != nullptr ? *a.deferred_count : 0;
   if (n_deferred > 0) {
@@ -446,15 +446,15 @@ __global__ __launch_bounds__(1024) void finish_apply_kernel(const FinishGroup g)
     __threadfence();
     __syncthreads();   // the partial row norms written above are read below by other lanes
   }
+  // Everything below hangs on a few rounds of loads from memory that no cache of this workgroup's die holds yet:
+  // they are issued together, and what a row's four lanes find stays in registers until gamma is known.
   double t = 0.0;
   for (int i = threadIdx.x; i < a.n_sumsq; i += blockDim.x) t += a.sumsq_part[i];
   // four lanes share a row: each adds every fourth column tile (independent loads), then the quad is combined
   const int part = threadIdx.x & 3;
   const int N = a.N, nct = a.n_col_tiles;
   const int rows_per_pass = blockDim.x >> 2;
-  double ph = 0.0;
-  for (int r0 = 0; r0 < N; r0 += rows_per_pass) {
-    const int r = r0 + (threadIdx.x >> 2);
+  auto row_sum = [&](int r) -> double {
     float p0 = 0.f, p1 = 0.f;
     if (r < N) {
       int c = part;
@@ -467,13 +467,47 @@ __global__ __launch_bounds__(1024) void finish_apply_kernel(const FinishGroup g)
     double p = (double)p0 + (double)p1;
     p += __shfl_xor(p, 1);
     p += __shfl_xor(p, 2);
+    return p;
+  };
+  constexpr int kKeep = 4;   // passes whose row sums stay in registers (N <= 1024 with 1024 threads)
+  double pv[kKeep];
+  double ph = 0.0;
+#pragma unroll
+  for (int ps = 0; ps < kKeep; ++ps) {
+    const int r = ps * rows_per_pass + (threadIdx.x >> 2);
+    pv[ps] = row_sum(r);
+    if (r < N && part == 0) {
+      a.prow[r] = pv[ps];
+      ph += pv[ps];
+    }
+  }
+  for (int r0 = kKeep * rows_per_pass; r0 < N; r0 += rows_per_pass) {   // (larger minibatches: through memory)
+    const int r = r0 + (threadIdx.x >> 2);
+    const double p = row_sum(r);
     if (r < N && part == 0) {
       a.prow[r] = p;
       ph += p;
     }
   }
-  const double tr_M = block_sum(t, scratch);      // (reduced after the row loop: all loads of the kernel are in flight together)
-  const double tr_Mhat = block_sum(ph, scratch);
+  // tr(X X^T) and tr(Xhat Xhat^T) in one reduction
+  {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+    t = wave_sum(t);
+    ph = wave_sum(ph);
+    __syncthreads();
+    if (lane == 0) {
+      scratch[wave] = t;
+      scratch[16 + wave] = ph;
+    }
+    __syncthreads();
+    t = 0.0;
+    ph = 0.0;
+    for (int w = 0; w < nw; ++w) {
+      t += scratch[w];
+      ph += scratch[16 + w];
+    }
+  }
+  const double tr_M = t, tr_Mhat = ph;
   const double gamma = tr_Mhat > 0.0 ? sqrt(tr_M / tr_Mhat) : 1.0;
   if (threadIdx.x == 0) {
     a.st->gamma = gamma;
@@ -482,8 +516,16 @@ __global__ __launch_bounds__(1024) void finish_apply_kernel(const FinishGroup g)
     if (a.gamma_out != nullptr) *a.gamma_out = (float)gamma;
   }
   if (a.rownorm2_out != nullptr) {
-    __syncthreads();   // prow was written by other lanes
-    for (int r = threadIdx.x; r < N; r += blockDim.x) a.rownorm2_out[r] = (float)(gamma * gamma * a.prow[r]);
+#pragma unroll
+    for (int ps = 0; ps < kKeep; ++ps) {
+      const int r = ps * rows_per_pass + (threadIdx.x >> 2);
+      if (r < N && part == 0) a.rownorm2_out[r] = (float)(gamma * gamma * pv[ps]);
+    }
+    if (N > kKeep * rows_per_pass) {
+      __syncthreads();   // prow was written by other lanes
+      for (int r = kKeep * rows_per_pass + threadIdx.x; r < N; r += blockDim.x)
+        a.rownorm2_out[r] = (float)(gamma * gamma * a.prow[r]);
+    }
   }
   if (a.clear_ptr != nullptr) {   // (every read of H and of the deferred count lies before a barrier above)
     float4* z = reinterpret_cast<float4*>(a.clear_ptr);
