@@ -340,7 +340,7 @@ hipError_t launch_h(const GemmDesc* d, int n, hipStream_t s) {
 template <int RC>
 hipError_t launch_j(const GemmDesc* d, int n, hipStream_t s) {
   if (RC == 32) return launch_gemm_group<32, 32, 32, 2, 2, false, false, EPI_STORE, false, 0, true>(d, n, s);
-  return launch_gemm_group<RC, 32, 32, 1, 2, false, false, EPI_STORE, false, 0, true>(d, n, s);
+  return launch_gemm_group<RC, 32, 32, RC / 16, 2, false, false, EPI_STORE, false, 0, true>(d, n, s);
 }
 // W_{t+1} = A_t B_t
 template <int RC>
