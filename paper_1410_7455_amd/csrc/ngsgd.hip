@@ -345,7 +345,7 @@ hipError_t launch_j(const GemmDesc* d, int n, hipStream_t s) {
 // W_{t+1} = A_t B_t
 template <int RC>
 hipError_t launch_wnew(const GemmDesc* d, int n, hipStream_t s) {
-  return launch_gemm_group<RC, 128, BK, 1, 4, true, false, EPI_STORE, false>(d, n, s);
+  return launch_gemm_group<RC, 64, BK, RC / 16, 2, true, false, EPI_STORE, false>(d, n, s);
 }
 
 template <typename F32, typename F80, typename F96>
