@@ -353,6 +353,23 @@ hipError_t by_rank_class(int rc, F32 f32, F80 f80, F96 f96) {
   return rc == 32 ? f32() : (rc == 80 ? f80() : f96());
 }
 
+// R x R Gram products of the factor update (K = J J^T, L = H^T H, W W^T), fp64 accumulation across the splits of the
+// long dimension.  Ranks up to 32: one 32 x 32 tile per instance; above: 64 x 64 tiles (a single 80 x 80 tile with one
+// row of MFMA tiles per wavefront was measured slower at rank 80: 399 instead of 387 us for the 512 x 5000 call,
+// fewer and longer workgroups)
+template <bool KC>
+hipError_t launch_small_gram(int rc, const GemmDesc* d, int n, hipStream_t s) {
+  if (rc == 32) return launch_gemm_group<32, 32, BK, 2, 1, KC, KC, EPI_ATOMIC_F64, false, 0, true>(d, n, s);
+  return launch_gemm_group<64, 64, BK, 2, 2, KC, KC, EPI_ATOMIC_F64, false, 0, true>(d, n, s);
+}
+constexpr int kGramMinSplitSteps = 4;   // K-blocks per split of a 32 x 32 tile at least: below that the atomic epilogue dominates
+inline int gram_splits(int rc, int rank, int instances, int k) {
+  const int ksteps = (k + BK - 1) / BK;
+  if (rc == 32) return std::min(choose_splits(instances, ksteps), std::max(1, ksteps / kGramMinSplitSteps));
+  const int tiles = ((rank + 63) / 64) * ((rank + 63) / 64);
+  return choose_splits(tiles * instances, ksteps);
+}
+
 struct PrecondCall {
   ngsgd_precond* p;
   float* M;
@@ -741,6 +758,8 @@ int factor_begin(std::vector<PrecondCall>& to_update, hipStream_t s) {
   {
     // K = J J^T, L = H^T H, fp64 accumulation across the splits
     std::vector<GemmDesc> dk, dl;
+    int rc = 0;
+    for (auto& c : to_update) rc = std::max(rc, c.p->ldh);
     for (auto& c : to_update) {
       ngsgd_precond& p = *c.p;
       GemmDesc g;
@@ -748,22 +767,19 @@ int factor_begin(std::vector<PrecondCall>& to_update, hipStream_t s) {
       g.B = p.J; g.ldb = p.ldw;
       g.C = p.K; g.ldc = p.rank;
       g.M = p.rank; g.N = p.rank; g.K = p.dim;
-      const int tiles = ((p.rank + 63) / 64) * ((p.rank + 63) / 64);
-      g.splits = choose_splits(tiles * (int)to_update.size(), (p.dim + BK - 1) / BK);
+      g.splits = gram_splits(rc, p.rank, (int)to_update.size(), p.dim);
       dk.push_back(g);
       GemmDesc h;
       h.A = p.H; h.lda = p.ldh;
       h.B = p.H; h.ldb = p.ldh;
       h.C = p.L; h.ldc = p.rank;
       h.M = p.rank; h.N = p.rank; h.K = p.last_N;
-      h.splits = choose_splits(tiles * (int)to_update.size(), (p.last_N + BK - 1) / BK);
+      h.splits = gram_splits(rc, p.rank, (int)to_update.size(), p.last_N);
       dl.push_back(h);
     }
     ProfScope prof(NGSGD_PROF_PRECOND_KL, s);
-    HIP_TRY((launch_gemm_group<64, 64, BK, 2, 2, true, true, EPI_ATOMIC_F64, false, 0, true>(dk.data(),
-                                                                                           (int)dk.size(), s)));
-    HIP_TRY((launch_gemm_group<64, 64, BK, 2, 2, false, false, EPI_ATOMIC_F64, false, 0, true>(dl.data(),
-                                                                                             (int)dl.size(), s)));
+    HIP_TRY(launch_small_gram<true>(rc, dk.data(), (int)dk.size(), s));
+    HIP_TRY(launch_small_gram<false>(rc, dl.data(), (int)dl.size(), s));
   }
   // B_t over J (needs D_t, rho_t: before the R x R update)
   for (size_t done = 0; done < to_update.size();) {
@@ -882,14 +898,12 @@ int factor_finish(std::vector<PrecondCall>& to_update, hipStream_t s) {
         w.B = p.W; w.ldb = p.ldw;
         w.C = p.K; w.ldc = p.rank;
         w.M = p.rank; w.N = p.rank; w.K = p.dim;
-        const int tiles = ((p.rank + 63) / 64) * ((p.rank + 63) / 64);
-        w.splits = choose_splits(tiles * n, (p.dim + BK - 1) / BK);
+        w.splits = gram_splits(rank_class(r_max), p.rank, n, p.dim);
         w.gate = &p.st->flags;
         w.gate_mask = kFlagOrthCheck;
         dg.push_back(w);
       }
-      HIP_TRY((launch_gemm_group<64, 64, BK, 2, 2, true, true, EPI_ATOMIC_F64, false, 0, true>(dg.data(),
-                                                                                             (int)dg.size(), s)));
+      HIP_TRY(launch_small_gram<true>(rank_class(r_max), dg.data(), (int)dg.size(), s));
       const size_t dyn = (size_t)r_max * (r_max + 1) * sizeof(double);   // W W^T of an instance
       const int cpt = orth_columns_per_thread(r_max);
       if (cpt <= 6) {
