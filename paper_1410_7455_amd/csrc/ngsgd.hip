@@ -231,9 +231,12 @@ void precond_configure(ngsgd_precond& p, int dim, int rank, int max_batch, float
 }
 
 bool g_attr_done = false;
+constexpr int kEigLdsReserve = 126 * 1024;   // dynamic LDS of a large eigen-update workgroup (of 160 KB per compute unit)
+constexpr int kEigReserveFromRank = 48;
+
 int ensure_kernel_attributes() {
   if (g_attr_done) return NGSGD_OK;
-  const int max_dyn = 2 * kMaxRank * (kMaxRank | 1) * (int)sizeof(double);
+  const int max_dyn = std::max(kEigLdsReserve, 2 * kMaxRank * (kMaxRank | 1) * (int)sizeof(double));
   HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(eig_update_kernel<1, kEigThreads>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, max_dyn));
   HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(eig_update_kernel<2, kEigThreads>),
@@ -832,7 +835,11 @@ int factor_begin(std::vector<PrecondCall>& to_update, hipStream_t s) {
     {
       const int m_max = (r_max + 1) & ~1;
       const int n_blocks = (m_max / 2) * (m_max / 2 + 1) / 2;   // 2x2 blocks of the upper triangle
-      const size_t eig_dyn = (size_t)2 * 4 * n_blocks * sizeof(double);   // two copies of four planes
+      size_t eig_dyn = (size_t)2 * 4 * n_blocks * sizeof(double);   // two copies of four planes
+      // A large eigen-problem is a long sequential chain bound by LDS latency, on which the next step waits: it asks for
+      // most of the compute unit's LDS, so that no workgroup of the layer products (which live on LDS bandwidth) is
+      // placed next to it.  That costs the products one compute unit in 256 per instance.
+      if (m_max >= kEigReserveFromRank) eig_dyn = std::max<size_t>(eig_dyn, kEigLdsReserve);
       const int n_off = (m_max / 2) * (m_max / 2 - 1) / 2;   // off-diagonal blocks, owned by the waves after the first
       const int items = std::max(1, (n_off + (kEigThreads - 64) - 1) / (kEigThreads - 64));
       if (items <= 1) {
