@@ -90,10 +90,13 @@ typedef struct {
   int32_t method;                 /* NGSGD_METHOD_ONLINE (App. B) or _SIMPLE (App. A)  */
   float simple_epsilon;           /* floor on tr(X^T X) in beta, App. A.2 (1e-20)      */
   int32_t side_streams;           /* internal streams for the factor updates: 0 = default
-                                   * (3), else 1..3.  Three start each group of factors as
-                                   * soon as its matrix exists (shortest single-network
-                                   * step); one is better when many networks share the GPU,
-                                   * which has few hardware queues per process            */
+                                   * (2), else 1..3.  Two: the last layer's derivatives and
+                                   * the layer inputs start after the forward pass, the
+                                   * other derivatives after the backward pass (shortest
+                                   * single-network step); three start the upper hidden
+                                   * layers in the middle of the backward pass; one is
+                                   * better when many networks share the GPU, which has
+                                   * few hardware queues per process                      */
 } ngsgd_config;
 
 /* ---- one preconditioner instance (App. B) ------------------------------------------------- */

@@ -111,8 +111,13 @@ inline int rank_class(int rank) { return rank <= 32 ? 32 : (rank <= 80 ? 80 : 96
 // the next step's forward / backward pass; the new factor is first needed by the next preconditioning.  The
 // instances are split over kSideStreams streams by the moment their matrix exists (the last layer's derivatives
 // and all layer inputs after the forward pass, the other derivatives as the backward pass produces them), so that
-// each group's products H, J and its R x R work start as early as possible.
-constexpr int kSideStreams = 3;
+// each group's products H, J and its R x R work start as early as possible.  Two streams are the default (the last
+// layer's derivatives and the layer inputs; the other derivatives after the backward pass): a third, which starts the
+// upper hidden layers' derivatives in the middle of the backward pass, measured 1 - 2 % slower on the speech-shaped
+// network (its small launches share the chip with the backward pass, and every further hardware queue in use
+// lengthens the gaps between dependent kernels on all of them, plain steps included).
+constexpr int kSideStreams = 3;          // most
+constexpr int kDefaultSideStreams = 2;
 struct SideSync {
   hipStream_t stream = nullptr;
   hipEvent_t inputs_ready = nullptr;   // recorded on the caller's stream: the group's matrices exist
@@ -233,6 +238,7 @@ void precond_configure(ngsgd_precond& p, int dim, int rank, int max_batch, float
 bool g_attr_done = false;
 constexpr int kEigLdsReserve = 126 * 1024;   // dynamic LDS of a large eigen-update workgroup (of 160 KB per compute unit)
 constexpr int kEigReserveFromRank = 48;
+constexpr int kEigvecLdsReserve = 76 * 1024;   // on top of the 48 KB of the staged rotation log
 
 int ensure_kernel_attributes() {
   if (g_attr_done) return NGSGD_OK;
@@ -243,6 +249,8 @@ int ensure_kernel_attributes() {
                               hipFuncAttributeMaxDynamicSharedMemorySize, max_dyn));
   HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(eig_update_kernel<kEigMaxItems, kEigThreads>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, max_dyn));
+  HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(eigvec_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              kEigvecLdsReserve));
   {
     const int orth_dyn = kMaxRank * (kMaxRank + 1) * (int)sizeof(double);
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(orth_fix_kernel<6>),
@@ -853,7 +861,7 @@ int factor_begin(std::vector<PrecondCall>& to_update, hipStream_t s) {
     }
     const int rows_per_block = kEigvecThreads / 64;
     hipLaunchKernelGGL(eigvec_kernel, dim3(n, (r_max + rows_per_block - 1) / rows_per_block), dim3(kEigvecThreads),
-                       0, s, g);
+                       r_max >= kEigReserveFromRank ? kEigvecLdsReserve : 0, s, g);
     LAUNCH_CHECK();
     done += n;
   }
@@ -1417,7 +1425,7 @@ void net_layout(ngsgd_net& net, const ngsgd_config* cfg, Carver& c) {
   net.method = cfg->method;
   net.alpha = cfg->alpha;
   net.simple_epsilon = cfg->simple_epsilon;
-  net.n_side = cfg->side_streams > 0 ? cfg->side_streams : kSideStreams;
+  net.n_side = cfg->side_streams > 0 ? cfg->side_streams : kDefaultSideStreams;
   const bool simple = cfg->method == NGSGD_METHOD_SIMPLE;
   net.layers.assign(cfg->n_layers, ngsgd_layer());
   int din = cfg->dims[0];

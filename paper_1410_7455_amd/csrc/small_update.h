@@ -460,6 +460,7 @@ __device__ __forceinline__ double wave_shift_down(double x) {
 // in chunks of kEigvecChunk rounds, the next chunk being fetched while the current one is replayed.
 __global__ __launch_bounds__(kEigvecThreads) void eigvec_kernel(const SmallGroup g) {
   __shared__ double2 s_log[2][kEigvecChunk * kMaxHalf];
+  extern __shared__ double eigvec_reserved[];   // not used: see the launch
   const SmallArgs& a = g.a[blockIdx.x];
   const int R = a.R;
   const int m = (R + 1) & ~1, half = m / 2;

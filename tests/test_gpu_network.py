@@ -134,7 +134,7 @@ def test_small_pnorm_net_plain(ngsgd):
     run_and_compare(ngsgd, spec, ora, gpu, 2, rows=spec.minibatch - 9)
 
 
-@pytest.mark.parametrize("side_streams", [0, 1, 2])
+@pytest.mark.parametrize("side_streams", [0, 1, 3])
 def test_small_pnorm_net_past_the_always_update_phase(ngsgd, side_streams):
     """Sixteen steps without any synchronisation of state: steps 10, 11 only apply the factors, step 12 is the first
     periodic update and step 13 is the step that follows one, which the library orders around the factor updates
