@@ -253,13 +253,13 @@ int ensure_kernel_attributes() {
                               kEigvecLdsReserve));
   {
     const int orth_dyn = kMaxRank * (kMaxRank + 1) * (int)sizeof(double);
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(orth_fix_kernel<2>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, orth_dyn));
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(orth_fix_kernel<3>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, orth_dyn));
+    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(orth_fix_kernel<5>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, orth_dyn));
     HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(orth_fix_kernel<6>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, orth_dyn));
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(orth_fix_kernel<12>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, orth_dyn));
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(orth_fix_kernel<20>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, orth_dyn));
-    HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(orth_fix_kernel<24>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, orth_dyn));
   }
   HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(init_block_solve_kernel),
@@ -927,15 +927,15 @@ int factor_finish(std::vector<PrecondCall>& to_update, hipStream_t s) {
       }
       HIP_TRY(launch_small_gram<true>(rank_class(r_max), dg.data(), (int)dg.size(), s));
       const size_t dyn = (size_t)r_max * (r_max + 1) * sizeof(double);   // W W^T of an instance
-      const int cpt = orth_columns_per_thread(r_max);
-      if (cpt <= 6) {
-        hipLaunchKernelGGL(orth_fix_kernel<6>, dim3(n), dim3(kSmallThreads), dyn, s, og);
-      } else if (cpt <= 12) {
-        hipLaunchKernelGGL(orth_fix_kernel<12>, dim3(n), dim3(kSmallThreads), dyn, s, og);
-      } else if (cpt <= 20) {
-        hipLaunchKernelGGL(orth_fix_kernel<20>, dim3(n), dim3(kSmallThreads), dyn, s, og);
+      const int ct = orth_columns_per_thread(r_max);   // 2 R / 32 rounded up: 1 .. 6
+      if (ct <= 2) {
+        hipLaunchKernelGGL(orth_fix_kernel<2>, dim3(n), dim3(kSmallThreads), dyn, s, og);
+      } else if (ct <= 3) {
+        hipLaunchKernelGGL(orth_fix_kernel<3>, dim3(n), dim3(kSmallThreads), dyn, s, og);
+      } else if (ct <= 5) {
+        hipLaunchKernelGGL(orth_fix_kernel<5>, dim3(n), dim3(kSmallThreads), dyn, s, og);
       } else {
-        hipLaunchKernelGGL(orth_fix_kernel<24>, dim3(n), dim3(kSmallThreads), dyn, s, og);
+        hipLaunchKernelGGL(orth_fix_kernel<6>, dim3(n), dim3(kSmallThreads), dyn, s, og);
       }
       LAUNCH_CHECK();
     }

@@ -553,26 +553,28 @@ struct OrthGroup {
 // The augmented matrix [O | B], R x 2R: O = E^{-1/2} (W W^T) E^{-1/2} (full, symmetric) and B = E^{-1/2} A_t.
 // Gaussian elimination without pivoting (O is symmetric positive definite) turns O into D L1^T and B into
 // L1^{-1} B, where O = L1 D L1^T with unit lower triangular L1; the Cholesky factor is L = L1 D^{1/2}, so
-// L^{-1} B = D^{-1/2} (L1^{-1} B).  The matrix lives in registers: kOrthTPR threads share a row, thread q of a row
-// holds the columns q, q + kOrthTPR, ... (CPT of them: the kernel is instantiated per rank class); what a step needs
-// from other threads (the pivot row, the pivot column and the reciprocal of the pivot) is published in LDS by its
-// owners at the end of the step before, in one of two buffers used alternately.  A step is then one barrier, one
-// LDS read and one multiply-add per element, without branches or address arithmetic; the elimination is bound by
-// the instructions issued, so wavefronts whose rows all lie above the pivot skip the step.
-constexpr int kOrthTPR = 8;
-constexpr int kOrthRowsPerWave = 64 / kOrthTPR;
-static_assert(kMaxRank * kOrthTPR <= kSmallThreads, "one thread group per row");
-inline int orth_columns_per_thread(int R) { return (2 * R + kOrthTPR - 1) / kOrthTPR; }
+// L^{-1} B = D^{-1/2} (L1^{-1} B).  The matrix lives in registers as 4 x CT tiles: thread (ti, tj) holds the rows
+// 4 ti .. 4 ti + 3 and the columns tj, tj + 32, ... (CT of them: the kernel is instantiated per rank class).  What a step
+// needs from other threads (the pivot row, the pivot column and the reciprocal of the pivot) is published in LDS by
+// its owners at the end of the step before, in one of two buffers used alternately.  A step is then one barrier,
+// CT + 4 LDS reads and 4 CT multiply-adds per thread, without address arithmetic (the elimination is bound by its LDS
+// reads: a tile needs 2.3 times fewer of them per element than a row strip); wavefronts whose rows all lie above
+// the pivot skip the step.
+constexpr int kOrthTileRows = 4;
+constexpr int kOrthTileStride = 32;   // columns tj, tj + 32, ...: the threads of a row of tiles
+constexpr int kOrthRowsPerWave = (64 / kOrthTileStride) * kOrthTileRows;
+static_assert((kMaxRank + kOrthTileRows - 1) / kOrthTileRows * kOrthTileStride <= kSmallThreads, "one thread per tile");
+inline int orth_columns_per_thread(int R) { return (2 * R + kOrthTileStride - 1) / kOrthTileStride; }
 
-template <int CPT>
+template <int CT>
 __global__ __launch_bounds__(kSmallThreads) void orth_fix_kernel(const OrthGroup g) {
   extern __shared__ __attribute__((aligned(16))) double dyn[];   // W W^T of the instance, R x (R + 1)
   __shared__ double scratch[16];
-  __shared__ double s_ise[kMaxRank];                // E_ii^{-1/2}
-  __shared__ double s_prow[2][kOrthTPR * CPT];      // pivot row of a step
-  __shared__ double s_pcol[2][kMaxRank];            // pivot column of a step
-  __shared__ double s_invp[2];                      // reciprocal of the pivot
-  __shared__ double s_dinv[kMaxRank];               // D_ii^{-1/2}
+  __shared__ double s_ise[kMaxRank];                       // E_ii^{-1/2}
+  __shared__ double s_prow[2][kOrthTileStride * CT];       // pivot row of a step
+  __shared__ double s_pcol[2][kMaxRank + kOrthTileRows];   // pivot column of a step
+  __shared__ double s_invp[2];                             // reciprocal of the pivot
+  __shared__ double s_dinv[kMaxRank];                      // D_ii^{-1/2}
   const OrthArgs& a = g.a[blockIdx.x];
   PrecondScalars* st = a.st;
   if (!(st->flags & kFlagOrthCheck)) return;   // uniform over the workgroup
@@ -600,65 +602,82 @@ __global__ __launch_bounds__(kSmallThreads) void orth_fix_kernel(const OrthGroup
   // The fix W <- E^{1/2} L^{-1} E^{-1/2} W is applied to the factor it came from: W = A_t B_t, so the triangular
   // mixing matrix goes into A_t and the product with B_t (still in its buffer) is simply launched again, gated on
   // the flag set below.
-  const int i = tid / kOrthTPR, q = tid % kOrthTPR;
-  const bool row_ok = i < R;
-  const int ic = min(i, R - 1);
+  const int ti = tid / kOrthTileStride, tj = tid % kOrthTileStride;
+  const int row0 = ti * kOrthTileRows;
   const int wave_row0 = (tid >> 6) * kOrthRowsPerWave;   // first row held by this wavefront
-  const double ise_i = s_ise[ic];
-  double v[CPT];
+  double v[kOrthTileRows][CT];
 #pragma unroll
-  for (int c = 0; c < CPT; ++c) {
-    const int j = q + kOrthTPR * c;
-    v[c] = 0.0;
-    if (row_ok && j < R) v[c] = 0.5 * (Gs[i * SG + j] + Gs[j * SG + i]) * ise_i * s_ise[j];
-    if (row_ok && j >= R && j < 2 * R) v[c] = (double)a.At[i * a.ldat + (j - R)] * ise_i;
+  for (int r = 0; r < kOrthTileRows; ++r) {
+    const int i = row0 + r;
+    const double ise_i = s_ise[min(i, R - 1)];
+#pragma unroll
+    for (int c = 0; c < CT; ++c) {
+      const int j = tj + kOrthTileStride * c;
+      v[r][c] = 0.0;
+      if (i < R && j < R) v[r][c] = 0.5 * (Gs[i * SG + j] + Gs[j * SG + i]) * ise_i * s_ise[j];
+      if (i < R && j >= R && j < 2 * R) v[r][c] = (double)a.At[i * a.ldat + (j - R)] * ise_i;
+    }
   }
   // What step k reads: row k (with zeros in the columns up to k, which the step must leave alone), column k, and the
-  // reciprocal of the pivot.  Published by their owners while they update for step k - 1: the register of column k
-  // is met in the unrolled loop under a uniform compare, so no register is picked by index.
-  if (row_ok && q == 0) {
-    s_pcol[0][i] = v[0];
-    if (i == 0) s_invp[0] = 1.0 / fmax(v[0], 1.0e-300);
-  }
-  if (i == 0) {
+  // reciprocal of the pivot.  Published by their owners while they update for step k - 1: the registers of row k and
+  // of column k are met in unrolled loops under uniform compares, so no register is picked by index.
+  auto publish = [&](const int kn, const int nb) {   // row, column and pivot of step kn into buffer nb
+    const int kr = kn % kOrthTileRows, kti = kn / kOrthTileRows;
+    const int kc = kn / kOrthTileStride, ktj = kn % kOrthTileStride;
 #pragma unroll
-    for (int c = 0; c < CPT; ++c) s_prow[0][q + kOrthTPR * c] = (q + kOrthTPR * c > 0) ? v[c] : 0.0;
-  }
+    for (int r = 0; r < kOrthTileRows; ++r) {
+      if (r == kr && ti == kti) {
+#pragma unroll
+        for (int c = 0; c < CT; ++c)
+          s_prow[nb][tj + kOrthTileStride * c] = (tj + kOrthTileStride * c > kn) ? v[r][c] : 0.0;
+      }
+    }
+#pragma unroll
+    for (int c = 0; c < CT; ++c) {
+      if (c == kc && tj == ktj) {
+#pragma unroll
+        for (int r = 0; r < kOrthTileRows; ++r) {
+          s_pcol[nb][row0 + r] = v[r][c];
+          if (row0 + r == kn) s_invp[nb] = 1.0 / fmax(v[r][c], 1.0e-300);
+        }
+      }
+    }
+  };
+  if (row0 < R) publish(0, 0);
   for (int k = 0; k < R - 1; ++k) {
     const int buf = k & 1, nb = buf ^ 1;
     __syncthreads();
     if (wave_row0 + kOrthRowsPerWave - 1 > k && wave_row0 < R) {   // (uniform over the wavefront) some row lies below k
       // rows below k, columns right of k (column k itself becomes zero and is not needed again)
-      const double f = (row_ok && i > k) ? s_pcol[buf][ic] * s_invp[buf] : 0.0;
-      double pr[CPT];
+      const double invp = s_invp[buf];
+      double f[kOrthTileRows], pr[CT];
 #pragma unroll
-      for (int c = 0; c < CPT; ++c) pr[c] = s_prow[buf][q + kOrthTPR * c];
-      const int kn = k + 1, kc = kn / kOrthTPR, kq = kn % kOrthTPR;
+      for (int r = 0; r < kOrthTileRows; ++r) f[r] = (row0 + r > k && row0 + r < R) ? s_pcol[buf][row0 + r] * invp : 0.0;
 #pragma unroll
-      for (int c = 0; c < CPT; ++c) {
-        v[c] -= f * pr[c];
-        if (c == kc && row_ok && q == kq && i >= kn) {
-          s_pcol[nb][i] = v[c];
-          if (i == kn) s_invp[nb] = 1.0 / fmax(v[c], 1.0e-300);
-        }
-      }
-      if (i == kn) {
+      for (int c = 0; c < CT; ++c) pr[c] = s_prow[buf][tj + kOrthTileStride * c];
 #pragma unroll
-        for (int c = 0; c < CPT; ++c) s_prow[nb][q + kOrthTPR * c] = (q + kOrthTPR * c > kn) ? v[c] : 0.0;
-      }
+      for (int r = 0; r < kOrthTileRows; ++r)
+#pragma unroll
+        for (int c = 0; c < CT; ++c) v[r][c] -= f[r] * pr[c];
+      publish(k + 1, nb);
     }
   }
   // D_ii is the diagonal entry of row i as it stood when the row became the pivot row: rows are not touched afterwards
 #pragma unroll
-  for (int c = 0; c < CPT; ++c)
-    if (row_ok && q + kOrthTPR * c == i) s_dinv[i] = rsqrt(fmax(v[c], 1.0e-300));
-  __syncthreads();
-  if (row_ok) {
-    const double scale = s_dinv[i] / ise_i;   // E_ii^{1/2} D_ii^{-1/2}
+  for (int r = 0; r < kOrthTileRows; ++r)
 #pragma unroll
-    for (int c = 0; c < CPT; ++c) {
-      const int j = q + kOrthTPR * c;
-      if (j >= R && j < 2 * R) a.At[i * a.ldat + (j - R)] = (float)(scale * v[c]);
+    for (int c = 0; c < CT; ++c)
+      if (row0 + r < R && tj + kOrthTileStride * c == row0 + r) s_dinv[row0 + r] = rsqrt(fmax(v[r][c], 1.0e-300));
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < kOrthTileRows; ++r) {
+    const int i = row0 + r;
+    if (i >= R) continue;
+    const double scale = s_dinv[i] / s_ise[i];   // E_ii^{1/2} D_ii^{-1/2}
+#pragma unroll
+    for (int c = 0; c < CT; ++c) {
+      const int j = tj + kOrthTileStride * c;
+      if (j >= R && j < 2 * R) a.At[i * a.ldat + (j - R)] = (float)(scale * v[r][c]);
     }
   }
   if (tid == 0) st->flags = (st->flags & ~kFlagOrthCheck) | kFlagReorth;
