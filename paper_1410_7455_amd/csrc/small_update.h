@@ -556,10 +556,9 @@ struct OrthGroup {
 // L^{-1} B = D^{-1/2} (L1^{-1} B).  The matrix lives in registers as 4 x CT tiles: thread (ti, tj) holds the rows
 // 4 ti .. 4 ti + 3 and the columns tj, tj + 32, ... (CT of them: the kernel is instantiated per rank class).  What a step
 // needs from other threads (the pivot row, the pivot column and the reciprocal of the pivot) is published in LDS by
-// its owners at the end of the step before, in one of two buffers used alternately.  A step is then one barrier,
-// CT + 4 LDS reads and 4 CT multiply-adds per thread, without address arithmetic (the elimination is bound by its LDS
-// reads: a tile needs 2.3 times fewer of them per element than a row strip); wavefronts whose rows all lie above
-// the pivot skip the step.
+// its owners at the end of the step before, in one of two buffers used alternately; a step (two pivots, see below)
+// is then one barrier, LDS reads without address arithmetic and multiply-adds (a tile needs 2.3 times fewer reads
+// per element than a strip of one row); wavefronts whose rows all lie above the pivot skip the step.
 constexpr int kOrthTileRows = 4;
 constexpr int kOrthTileStride = 32;   // columns tj, tj + 32, ...: the threads of a row of tiles
 constexpr int kOrthRowsPerWave = (64 / kOrthTileStride) * kOrthTileRows;
@@ -571,9 +570,9 @@ __global__ __launch_bounds__(kSmallThreads) void orth_fix_kernel(const OrthGroup
   extern __shared__ __attribute__((aligned(16))) double dyn[];   // W W^T of the instance, R x (R + 1)
   __shared__ double scratch[16];
   __shared__ double s_ise[kMaxRank];                       // E_ii^{-1/2}
-  __shared__ double s_prow[2][kOrthTileStride * CT];       // pivot row of a step
-  __shared__ double s_pcol[2][kMaxRank + kOrthTileRows];   // pivot column of a step
-  __shared__ double s_invp[2];                             // reciprocal of the pivot
+  __shared__ double s_prow[2][2][kOrthTileStride * CT];    // the two pivot rows of a step
+  __shared__ double s_pcol[2][2][kMaxRank + kOrthTileRows];   // the two pivot columns of a step
+  __shared__ double s_invp[2];                             // reciprocal of the first pivot of a step
   __shared__ double s_dinv[kMaxRank];                      // D_ii^{-1/2}
   const OrthArgs& a = g.a[blockIdx.x];
   PrecondScalars* st = a.st;
@@ -618,48 +617,67 @@ __global__ __launch_bounds__(kSmallThreads) void orth_fix_kernel(const OrthGroup
       if (i < R && j >= R && j < 2 * R) v[r][c] = (double)a.At[i * a.ldat + (j - R)] * ise_i;
     }
   }
-  // What step k reads: row k (with zeros in the columns up to k, which the step must leave alone), column k, and the
-  // reciprocal of the pivot.  Published by their owners while they update for step k - 1: the registers of row k and
-  // of column k are met in unrolled loops under uniform compares, so no register is picked by index.
-  auto publish = [&](const int kn, const int nb) {   // row, column and pivot of step kn into buffer nb
-    const int kr = kn % kOrthTileRows, kti = kn / kOrthTileRows;
-    const int kc = kn / kOrthTileStride, ktj = kn % kOrthTileStride;
+  // Two pivots per barrier.  What the pair (k, k + 1) reads: rows k and k + 1 as they stand after pivot k - 1 (with zeros
+  // in the columns up to k, which the pair must leave alone), columns k and k + 1 likewise, and the reciprocal of
+  // pivot k.  Every thread derives from them what pivot k makes of row k + 1, of column k + 1 and of pivot k + 1 (a
+  // few operations on values it has read anyway) and applies both eliminations to its tile at once.  The four lines
+  // of the next pair are published by their owners behind the update, in the other of two buffers: the registers of a
+  // row or column are met in unrolled loops under uniform compares, so no register is picked by index.
+  auto publish = [&](const int kn, const int nb) {   // rows and columns kn, kn + 1 and 1 / pivot kn into buffer nb
 #pragma unroll
-    for (int r = 0; r < kOrthTileRows; ++r) {
-      if (r == kr && ti == kti) {
+    for (int u = 0; u < 2; ++u) {
+      const int ku = kn + u;
+      const int kr = ku % kOrthTileRows, kti = ku / kOrthTileRows;
+      const int kc = ku / kOrthTileStride, ktj = ku % kOrthTileStride;
 #pragma unroll
-        for (int c = 0; c < CT; ++c)
-          s_prow[nb][tj + kOrthTileStride * c] = (tj + kOrthTileStride * c > kn) ? v[r][c] : 0.0;
+      for (int r = 0; r < kOrthTileRows; ++r) {
+        if (r == kr && ti == kti) {
+#pragma unroll
+          for (int c = 0; c < CT; ++c)
+            s_prow[nb][u][tj + kOrthTileStride * c] = (tj + kOrthTileStride * c > kn) ? v[r][c] : 0.0;
+        }
       }
-    }
 #pragma unroll
-    for (int c = 0; c < CT; ++c) {
-      if (c == kc && tj == ktj) {
+      for (int c = 0; c < CT; ++c) {
+        if (c == kc && tj == ktj) {
 #pragma unroll
-        for (int r = 0; r < kOrthTileRows; ++r) {
-          s_pcol[nb][row0 + r] = v[r][c];
-          if (row0 + r == kn) s_invp[nb] = 1.0 / fmax(v[r][c], 1.0e-300);
+          for (int r = 0; r < kOrthTileRows; ++r) {
+            s_pcol[nb][u][row0 + r] = v[r][c];
+            if (u == 0 && row0 + r == kn) s_invp[nb] = 1.0 / fmax(v[r][c], 1.0e-300);
+          }
         }
       }
     }
   };
   if (row0 < R) publish(0, 0);
-  for (int k = 0; k < R - 1; ++k) {
-    const int buf = k & 1, nb = buf ^ 1;
+  for (int k = 0; k < R - 1; k += 2) {
+    const int buf = (k >> 1) & 1, nb = buf ^ 1;
     __syncthreads();
     if (wave_row0 + kOrthRowsPerWave - 1 > k && wave_row0 < R) {   // (uniform over the wavefront) some row lies below k
-      // rows below k, columns right of k (column k itself becomes zero and is not needed again)
-      const double invp = s_invp[buf];
-      double f[kOrthTileRows], pr[CT];
+      const int k1 = k + 1;   // (k1 <= R - 1: a row of the matrix; as the last row it eliminates nothing)
+      const double inv0 = s_invp[buf];
+      const double m = s_pcol[buf][0][k1] * inv0;            // what pivot k takes off row k + 1
+      const double a01 = s_prow[buf][0][k1];                 // entry (k, k + 1)
+      const double inv1 = 1.0 / fmax(s_pcol[buf][1][k1] - m * a01, 1.0e-300);   // pivot k + 1 after pivot k
+      double f[kOrthTileRows], gq[kOrthTileRows], p0[CT], q1[CT];
 #pragma unroll
-      for (int r = 0; r < kOrthTileRows; ++r) f[r] = (row0 + r > k && row0 + r < R) ? s_pcol[buf][row0 + r] * invp : 0.0;
+      for (int r = 0; r < kOrthTileRows; ++r) {
+        const int i = row0 + r;
+        const double c0 = s_pcol[buf][0][i], c1 = s_pcol[buf][1][i];
+        f[r] = (i > k && i < R) ? c0 * inv0 : 0.0;
+        gq[r] = (i > k1 && i < R) ? (c1 - f[r] * a01) * inv1 : 0.0;
+      }
 #pragma unroll
-      for (int c = 0; c < CT; ++c) pr[c] = s_prow[buf][tj + kOrthTileStride * c];
+      for (int c = 0; c < CT; ++c) {
+        const int j = tj + kOrthTileStride * c;
+        p0[c] = s_prow[buf][0][j];
+        q1[c] = (j > k1) ? s_prow[buf][1][j] - m * p0[c] : 0.0;   // row k + 1 after pivot k, dead columns zero
+      }
 #pragma unroll
       for (int r = 0; r < kOrthTileRows; ++r)
 #pragma unroll
-        for (int c = 0; c < CT; ++c) v[r][c] -= f[r] * pr[c];
-      publish(k + 1, nb);
+        for (int c = 0; c < CT; ++c) v[r][c] -= f[r] * p0[c] + gq[r] * q1[c];
+      if (k + 2 < R - 1) publish(k + 2, nb);
     }
   }
   // D_ii is the diagonal entry of row i as it stood when the row became the pivot row: rows are not touched afterwards
