@@ -218,6 +218,23 @@ def test_c1_full_size_first_steps(ngsgd):
     print("c1 worst errors, steps 14..17 free running", worst)
 
 
+def test_wide_layers_ragged_minibatch(ngsgd):
+    """Layers as wide as those of configs[1] with a minibatch that is no multiple of any tile (500 rows): the
+    twelve-wavefront 64 x 96 tiles of the forward and backward products with a ragged row tile, ragged column tiles
+    and a K tail, and the last row block of the fused apply kernel (500 = 7 x 64 + 52) at ranks 20 and 80."""
+    import dataclasses
+    base = workloads.c1_pnorm()
+    spec = dataclasses.replace(base, name="wide_ragged", index=11, dims=[360, 3000, 3000, 5000], nonlin=base.nonlin[:2],
+                               minibatch=500)
+    ora, gpu = make_pair(ngsgd, spec, renorm=True, max_change=0.075)
+    worst = run_and_compare(ngsgd, spec, ora, gpu, 3, ambiguous_first={(spec.n_layers - 1, ngsgd.NGSGD_SIDE_OUTPUT)})
+    print("wide ragged worst errors, free running", worst)
+    # past the always-update phase, step by step from shared state: apply-only steps (fused kernel) and an update
+    sync_from_oracle(ngsgd, spec, ora, gpu)
+    worst = run_and_compare(ngsgd, spec, ora, gpu, 10, first_step=3, sync_every_step=True)
+    print("wide ragged worst errors, step by step", worst)
+
+
 def test_c3_wide_tanh_first_steps(ngsgd):
     """BASELINE configs[3] at full size (440 -> 6 x tanh 2048 -> 8000, minibatch 1024, ranks 20 / 80): the tanh
     kernels, 2049-wide inputs and an 8000-way softmax (the widest row the softmax kernel keeps in registers)."""
