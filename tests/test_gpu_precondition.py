@@ -139,8 +139,8 @@ def test_degenerate_first_minibatches(ngsgd):
             assert rel(got, expect) < TOL, f"route {dim} step {step}"
 
 
-@pytest.mark.parametrize("N,D,R,spread", [(96, 200, 6, 1e5), (96, 200, 6, None), (128, 300, 40, None),
-                                          (160, 400, 80, None), (200, 500, 96, None)])
+@pytest.mark.parametrize("N,D,R,spread", [(96, 200, 6, 1e5), (96, 200, 6, None), (96, 200, 13, None),
+                                          (128, 300, 40, None), (160, 400, 80, None), (200, 500, 96, None)])
 def test_forced_reorthogonalisation(ngsgd, N, D, R, spread):
     """A skewed factor with an ill-conditioned D_t makes cond(C_t) exceed 1e6, which triggers the check of
     App. B.3.1, and the check then finds R R^T off the identity.
